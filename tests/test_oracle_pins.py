@@ -1,0 +1,463 @@
+"""Pins of the CPU oracle against what the paper and plain mathematics fix.
+
+None of these tests re-uses the oracle's own formulas: expected values come from the
+paper's worked example, exact rational arithmetic (fractions), fp64 brute force written as
+explicit loops, numpy / scipy library routines for the special cases that reduce to them,
+closed forms and invariants.  A planted mistake in the oracle (dropped term, wrong sign,
+transposed operand, wrong tie rule) fails at least one of them.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy.signal import correlate2d
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# --------------------------------------------------------------------------- Sec. 2.1
+
+def test_qparams_worked_example_from_paper():
+    # Sec. 2.1: range (2.1, 3.5) is relaxed to (0, 3.5)
+    for xmin, xmax, bits, rmin, rmax, z, num, den in _rows("qparams_worked_example.txt"):
+        s, zp = oracle.choose_qparams(float(xmin), float(xmax), int(bits))
+        assert zp == int(z)
+        assert s == np.float32(float(num) / float(den))
+        # relaxed range is what the 256 codes cover
+        lo = (0 - zp) * s
+        hi = (2 ** int(bits) - 1 - zp) * s
+        assert abs(lo - float(rmin)) < 1e-6 and abs(hi - float(rmax)) < 1e-5
+
+
+def test_zero_is_exactly_representable():
+    rng = np.random.default_rng(1)
+    cases = [(-1.0, 1.0), (-6.0, 0.0), (0.0, 6.0), (2.1, 3.5), (-3.5, -2.1), (0.0, 0.0), (-1e-3, 5e3)]
+    cases += [tuple(sorted(rng.normal(0, 3, 2))) for _ in range(200)]
+    for xmin, xmax in cases:
+        s, z = oracle.choose_qparams(xmin, xmax)
+        assert 0 <= z <= 255 and s > 0
+        q = oracle.quantize(np.zeros(3, np.float32), s, z)
+        assert (q == z).all()
+        assert (oracle.dequantize(np.full(3, z, np.uint8), s, z) == 0.0).all()
+        # negative zero too
+        assert oracle.quantize(np.array([-0.0], np.float32), s, z)[0] == z
+
+
+def test_round_trip_error_at_most_half_a_step():
+    rng = np.random.default_rng(2)
+    for xmin, xmax in [(-1.0, 1.0), (0.0, 6.0), (-2.3, 0.7), (-5.4, 5.4), (-0.01, 100.0)]:
+        s, z = oracle.choose_qparams(xmin, xmax)
+        lo, hi = (0 - z) * float(s), (255 - z) * float(s)  # representable range
+        x = rng.uniform(lo, hi, 200_000).astype(np.float32)
+        y = oracle.dequantize(oracle.quantize(x, s, z), s, z)
+        err = np.abs(x.astype(np.float64) - y.astype(np.float64))
+        assert err.max() <= 0.5 * s * (1 + 2.0 ** -12) + 1e-12
+        # outside the range the quantizer saturates (eq. 2)
+        big = np.array([hi + 10 * s, hi + 1e6, np.inf], np.float32)
+        small = np.array([lo - 10 * s, lo - 1e6, -np.inf], np.float32)
+        assert (oracle.quantize(big, s, z) == 255).all()
+        assert (oracle.quantize(small, s, z) == 0).all()
+
+
+def test_quantize_of_dequantize_is_identity_for_all_codes():
+    codes = np.arange(256, dtype=np.uint8)
+    rng = np.random.default_rng(3)
+    for _ in range(100):
+        s = float(np.float32(10 ** rng.uniform(-4, 2)))
+        z = int(rng.integers(0, 256))
+        assert (oracle.quantize(oracle.dequantize(codes, s, z), s, z) == codes).all()
+
+
+def test_dequantize_closed_form():
+    # eq. 3 with a power-of-two step is exact in binary32
+    codes = np.arange(256, dtype=np.uint8)
+    for j, z in [(3, 0), (7, 128), (0, 255), (10, 17)]:
+        s = 2.0 ** -j
+        want = (codes.astype(np.int64) - z) * s
+        assert (oracle.dequantize(codes, s, z).astype(np.float64) == want).all()
+
+
+def test_ties_round_away_from_zero():
+    # x = (k + 0.5) * Delta with Delta = 2^-j is exact in binary32, so x / Delta is an exact tie
+    for j in (0, 2, 5):
+        d = 2.0 ** -j
+        k = np.arange(-100, 100)
+        x = ((k + 0.5) * d).astype(np.float32)
+        q = oracle.quantize(x, d, 128).astype(np.int64) - 128
+        want = np.where(k >= 0, k + 1, k)  # away from zero
+        assert (q == want).all()
+
+
+def test_clamp_three_cases_and_custom_range():
+    # clamp(a, b, x) of Sec. 2.1, with a restricted code range [qmin, qmax]
+    x = np.array([-1000.0, -3.0, 0.0, 2.0, 1000.0], np.float32)
+    q = oracle.quantize(x, 1.0, 10, 5, 14)
+    assert q.tolist() == [5, 7, 10, 12, 14]
+    assert oracle.quantize(np.array([np.nan], np.float32), 0.1, 77)[0] == 77
+
+
+def test_quantize_matches_exact_rational_rounding_of_the_binary32_quotient():
+    rng = np.random.default_rng(4)
+    x = rng.normal(0, 2, 4000).astype(np.float32)
+    for s, z in [(np.float32(0.0213), 131), (np.float32(1 / 3), 3), (np.float32(7.7e-3), 250)]:
+        got = oracle.quantize(x, float(s), z)
+        t = x / s  # numpy binary32 division: IEEE, round to nearest even
+        for xi, ti, gi in zip(x, t, got):
+            fr = Fraction(float(ti))
+            r = int(abs(fr) + Fraction(1, 2))  # floor(|t| + 1/2): ties away from zero
+            r = r if fr >= 0 else -r
+            assert gi == min(255, max(0, r + z))
+
+
+# --------------------------------------------------------------------------- Sec. 2.2
+
+def test_symmetric_weight_quantizer_ranges_from_paper():
+    rng = np.random.default_rng(5)
+    rows = {(int(b), int(sg), int(rs)): (int(lo), int(hi)) for b, sg, rs, lo, hi in _rows("clamp_ranges.txt")}
+    w = rng.normal(0, 0.1, (16, 3, 3, 8)).astype(np.float32)
+    for bits in (8, 4):
+        lo, hi = rows[(bits, 1, 1)]
+        wq, d = oracle.quantize_weights(w, bits, restricted=True)
+        assert wq.min() >= lo and wq.max() <= hi
+        # the extreme of every channel lands exactly on +-hi, nothing below -hi
+        amax = np.abs(w.reshape(16, -1)).max(1)
+        assert np.allclose(d, amax / hi, rtol=1e-6)
+        assert (np.abs(wq.reshape(16, -1)).max(1) == hi).all()
+        # round trip within half a step per channel
+        err = np.abs(wq.reshape(16, -1) * d[:, None].astype(np.float64) - w.reshape(16, -1))
+        assert (err <= 0.5 * d[:, None] * (1 + 1e-6)).all()
+    # full range admits -2^(bits-1) when the scale is given by the positive side
+    wq, _ = oracle.quantize_weights(np.array([[-1.0, 127 / 128.0]], np.float32) * 1.0, 8, restricted=False)
+    assert rows[(8, 1, 0)] == (-128, 127) and wq.min() >= -128
+    assert oracle.quantize_weights(np.zeros((2, 4), np.float32))[1].tolist() == [1.0, 1.0]
+
+
+def test_int4_pack_unpack_exhaustive():
+    vals = np.array([[a, b] for a in range(-8, 8) for b in range(-8, 8)], np.int8)  # all 256 bytes
+    packed = oracle.pack_int4(vals)
+    assert packed.shape == (256, 1)
+    # low nibble = even element, high nibble = odd element, two's complement
+    for (a, b), byte in zip(vals.tolist(), packed[:, 0].tolist()):
+        assert byte == ((a & 0xF) | ((b & 0xF) << 4))
+    assert (oracle.unpack_int4(packed) == vals).all()
+    assert sorted(set(packed[:, 0].tolist())) == list(range(256))
+
+
+def test_per_channel_sqnr_not_worse_than_per_layer():
+    # Appendix A: when channel ranges differ widely a single quantizer wastes precision
+    rng = np.random.default_rng(6)
+    scale = 10 ** rng.uniform(-2, 0, 32)
+    w = (rng.normal(0, 1, (32, 64)) * scale[:, None]).astype(np.float32)
+    wq, d = oracle.quantize_weights(w, 8)
+    per_ch = wq * d[:, None]
+    wl, dl = oracle.quantize_weights(w.reshape(1, -1), 8)
+    per_layer = (wl * dl[:, None]).reshape(w.shape)
+    sqnr = lambda a: 10 * np.log10((w ** 2).sum() / ((w - a) ** 2).sum())
+    assert sqnr(per_ch) > sqnr(per_layer) + 3
+
+
+# ------------------------------------------------------------- fixed-point rescale
+
+def _exact_two_stage(a, mult, shift):
+    """The two-stage rescale in exact rational arithmetic."""
+    if shift < 0:
+        a = max(-2 ** 31, min(2 ** 31 - 1, a * 2 ** (-shift)))
+    if a == -2 ** 31 and mult == -2 ** 31:
+        h = 2 ** 31 - 1
+    else:
+        v = Fraction(a * mult, 2 ** 31)
+        h = (v + Fraction(1, 2)).__floor__()  # nearest, ties toward +inf
+    n = max(shift, 0)
+    if n == 0:
+        return h
+    v = Fraction(abs(h), 2 ** n)
+    r = (v + Fraction(1, 2)).__floor__()  # nearest, ties away from zero (on |h|)
+    return r if h >= 0 else -r
+
+
+def test_quantize_multiplier_properties():
+    rng = np.random.default_rng(7)
+    for M in list(10 ** rng.uniform(-9, 1.5, 500)) + [0.5, 1.0, 0.25, 1 - 2.0 ** -33, 2.0 ** -31, 3.0]:
+        m, s = oracle.quantize_multiplier(M)
+        assert 2 ** 30 <= m < 2 ** 31 and -31 <= s <= 31
+        assert abs(m * 2.0 ** (-31 - s) - M) <= M * 2.0 ** -31
+    assert oracle.quantize_multiplier(0.0) == (0, 0)
+    assert oracle.quantize_multiplier(0.5) == (2 ** 30, 0)
+    assert oracle.quantize_multiplier(1.0) == (2 ** 30, -1)
+    # rounding the mantissa up to 2^31 renormalises
+    assert oracle.quantize_multiplier(1 - 2.0 ** -40) == (2 ** 30, -1)
+    assert oracle.quantize_multiplier(1e-12) == (0, 0)  # below 2^-32: everything rescales to 0
+
+
+def test_rescale_against_exact_rational_arithmetic():
+    rng = np.random.default_rng(8)
+    mults = [2 ** 30, 2 ** 31 - 1, 2 ** 30 + 1] + rng.integers(2 ** 30, 2 ** 31, 60).tolist()
+    shifts = list(range(0, 32)) + [-1, -3, -8]
+    a_small = list(range(-300, 301))
+    a_rand = rng.integers(-2 ** 31, 2 ** 31, 300).tolist() + [2 ** 31 - 1, -2 ** 31, -2 ** 31 + 1]
+    for m in mults:
+        for s in rng.choice(shifts, 8, replace=False).tolist():
+            for a in a_small[:: 7] + a_rand[:: 5]:
+                assert oracle.rescale(a, m, s) == _exact_two_stage(a, m, s), (a, m, s)
+    # ties: mult = 2^30 makes stage 1 an exact halving, so every odd a is a stage-1 tie
+    for a in range(-41, 42):
+        for s in (0, 1, 2, 5):
+            assert oracle.rescale(a, 2 ** 30, s) == _exact_two_stage(a, 2 ** 30, s)
+    # saturating corner
+    assert oracle.rescale(-2 ** 31, -2 ** 31, 0) == 2 ** 31 - 1
+
+
+def test_rescale_closed_forms():
+    # stage 1 with mult = 2^30: nearest(a/2), ties toward +inf; stage 2: ties away from zero
+    assert [oracle.rescale(a, 2 ** 30, 0) for a in (-3, -2, -1, 0, 1, 2, 3)] == [-1, -1, 0, 0, 1, 1, 2]
+    # a multiple of 2^(s+1): exact division, no rounding anywhere
+    for s in range(0, 20):
+        for k in (-5, -1, 0, 1, 9):
+            assert oracle.rescale(k * 2 ** (s + 1), 2 ** 30, s) == k
+    # stage 2 ties: h = +-(2k+1)*2^(n-1) -> away from zero
+    for n in (1, 4):
+        for k in (0, 1, 3):
+            h = (2 * k + 1) * 2 ** (n - 1)
+            assert oracle.rescale(2 * h, 2 ** 30, n) == k + 1
+            assert oracle.rescale(-2 * h, 2 ** 30, n) == -(k + 1)
+    # left shift saturates before the multiply
+    assert oracle.rescale(2 ** 30, 2 ** 30, -2) == _exact_two_stage(2 ** 30, 2 ** 30, -2) == 2 ** 30
+
+
+def test_rescale_within_one_of_real_product():
+    rng = np.random.default_rng(9)
+    for _ in range(300):
+        M = 10 ** rng.uniform(-6, 0.3)
+        m, s = oracle.quantize_multiplier(M)
+        for a in rng.integers(-2 ** 24, 2 ** 24, 20).tolist():
+            real = a * M
+            assert abs(oracle.rescale(a, m, s) - real) <= 1.0 + abs(real) * 2.0 ** -29
+
+
+def test_requantize_tensor_and_clamp():
+    rng = np.random.default_rng(10)
+    acc = rng.integers(-200000, 200000, (37, 13)).astype(np.int32)
+    mult, shift = oracle.quantize_multipliers(10 ** rng.uniform(-4, -2, 13))
+    y = oracle.requantize(acc, mult, shift, True, 7, 3, 250)
+    for r in range(37):
+        for c in range(13):
+            want = min(250, max(3, _exact_two_stage(int(acc[r, c]), int(mult[c]), int(shift[c])) + 7))
+            assert y[r, c] == want
+    y1 = oracle.requantize(acc, mult[:1], shift[:1], False, 0, 0, 255)
+    want = [min(255, max(0, _exact_two_stage(int(a), int(mult[0]), int(shift[0])))) for a in acc.ravel()]
+    assert y1.ravel().tolist() == want
+
+
+# ------------------------------------------------------------- eq. 4-6: integer conv
+
+def _brute_conv_fp64(xr, wr, stride, pad):
+    """Real-valued cross-correlation with zero padding, explicit loops, fp64."""
+    N, H, W, Cin = xr.shape
+    Cout, kh, kw, _ = wr.shape
+    sh, sw = stride
+    ph, pw = pad
+    Ho, Wo = (H + 2 * ph - kh) // sh + 1, (W + 2 * pw - kw) // sw + 1
+    y = np.zeros((N, Ho, Wo, Cout))
+    for n in range(N):
+        for ho in range(Ho):
+            for wo in range(Wo):
+                for co in range(Cout):
+                    t = 0.0
+                    for a in range(kh):
+                        for b in range(kw):
+                            hi, wi = ho * sh - ph + a, wo * sw - pw + b
+                            if 0 <= hi < H and 0 <= wi < W:
+                                for ci in range(Cin):
+                                    t += xr[n, hi, wi, ci] * wr[co, a, b, ci]
+                    y[n, ho, wo, co] = t
+    return y
+
+
+@pytest.mark.parametrize("kh,kw,stride,pad", [(3, 3, (1, 1), (1, 1)), (3, 3, (2, 2), (1, 1)), (1, 1, (1, 1), (0, 0)),
+                                               (5, 3, (2, 1), (2, 0)), (1, 1, (2, 2), (0, 0)), (3, 3, (1, 2), (0, 1))])
+@pytest.mark.parametrize("with_zw", [False, True])
+def test_integer_conv_equals_real_conv_of_dequantized_operands(kh, kw, stride, pad, with_zw):
+    # eq. 4: y = Delta_w Delta_x conv(w_Q - z_w, x_Q - z_x); power-of-two steps keep fp64 exact
+    rng = np.random.default_rng(11 + kh * 7 + kw + stride[0] + 3 * pad[0] + with_zw)
+    N, H, W, Cin, Cout = 2, 6, 5, 4, 3
+    x = rng.integers(0, 256, (N, H, W, Cin)).astype(np.uint8)
+    w = rng.integers(-128, 128, (Cout, kh, kw, Cin)).astype(np.int8)
+    z_x = int(rng.integers(0, 256))
+    z_w = rng.integers(-20, 20, Cout).astype(np.int32) if with_zw else None
+    s_x, d_c = 2.0 ** -5, 2.0 ** -np.arange(3, 3 + Cout)
+    xr = (x.astype(np.float64) - z_x) * s_x
+    wr = (w.astype(np.float64) - (0 if z_w is None else z_w[:, None, None, None])) * d_c[:, None, None, None]
+    real = _brute_conv_fp64(xr, wr, stride, pad)
+    acc = oracle.qconv2d_acc(x, z_x, w, stride, pad, z_w=z_w)
+    assert acc.shape == real.shape
+    assert (acc.astype(np.float64) * (s_x * d_c) == real).all()
+
+
+def test_four_term_expansion_of_eq_5_6():
+    # conv(w_Q - z_w, x_Q - z_x) = conv(w_Q, x_Q) - z_w sum(x_Q) - z_x sum(w_Q) + (taps) z_x z_w
+    rng = np.random.default_rng(12)
+    N, H, W, Cin, Cout, k = 1, 5, 5, 3, 4, 3
+    x = rng.integers(0, 256, (N, H, W, Cin)).astype(np.uint8)
+    w = rng.integers(-128, 128, (Cout, k, k, Cin)).astype(np.int8)
+    z_x, z_w = 113, np.array([5, -9, 0, 31], np.int32)
+    acc = oracle.qconv2d_acc(x, z_x, w, (1, 1), (0, 0), z_w=z_w)  # no padding: all taps present
+    raw = oracle.qconv2d_acc(x, 0, w, (1, 1), (0, 0))
+    xs = x.astype(np.int64)
+    for ho in range(3):
+        for wo in range(3):
+            win = xs[0, ho:ho + 3, wo:wo + 3, :].sum()
+            for co in range(Cout):
+                want = raw[0, ho, wo, co] - z_w[co] * win - z_x * w[co].astype(np.int64).sum() + k * k * Cin * z_x * z_w[co]
+                assert acc[0, ho, wo, co] == want
+
+
+def test_single_channel_conv_reduces_to_library_cross_correlation():
+    rng = np.random.default_rng(13)
+    x = rng.integers(0, 256, (1, 9, 8, 1)).astype(np.uint8)
+    w = rng.integers(-128, 128, (1, 3, 3, 1)).astype(np.int8)
+    z_x = 77
+    acc = oracle.qconv2d_acc(x, z_x, w, (1, 1), (1, 1))
+    want = correlate2d(x[0, :, :, 0].astype(np.int64) - z_x, w[0, :, :, 0].astype(np.int64), mode="same")
+    assert (acc[0, :, :, 0] == want).all()
+
+
+def test_pointwise_conv_and_gemm_reduce_to_integer_matrix_product():
+    rng = np.random.default_rng(14)
+    M, K, N = 23, 40, 11
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    z_a = 201
+    z_w = rng.integers(-5, 5, N).astype(np.int32)
+    bias = rng.integers(-5000, 5000, N).astype(np.int32)
+    ref = (A.astype(np.int64) - z_a) @ (Bt.astype(np.int64) - z_w[:, None]).T
+    acc = oracle.qconv2d_acc(A.reshape(1, M, 1, K), z_a, Bt.reshape(N, 1, 1, K), (1, 1), (0, 0), z_w=z_w)
+    assert (acc.reshape(M, N) == ref).all()
+    # qgemm: mult = 2^30, shift = 0 halves the accumulator (ties toward +inf): checkable in closed form
+    mult = np.full(N, 2 ** 30, np.int32)
+    shift = np.zeros(N, np.int32)
+    C = oracle.qgemm(A, z_a, Bt, mult, shift, 128, 0, 255, bias=bias, z_w=z_w)
+    want = np.clip(np.floor((ref + bias[None, :] + 1) / 2).astype(np.int64) + 128, 0, 255)
+    assert (C == want).all()
+    # a transposed-operand mistake cannot pass: the product is not symmetric
+    assert not (ref[:N, :N] == ref[:N, :N].T).all()
+
+
+def test_padding_contributes_nothing_when_border_is_zero_point():
+    # Sec. 2.1: zero padding causes no quantization error -> padded conv == conv of an image
+    # explicitly framed with the code z_x
+    rng = np.random.default_rng(15)
+    x = rng.integers(0, 256, (1, 6, 6, 2)).astype(np.uint8)
+    w = rng.integers(-128, 128, (3, 3, 3, 2)).astype(np.int8)
+    z_x = 9
+    framed = np.full((1, 8, 8, 2), z_x, np.uint8)
+    framed[:, 1:7, 1:7, :] = x
+    assert (oracle.qconv2d_acc(x, z_x, w, (1, 1), (1, 1)) == oracle.qconv2d_acc(framed, z_x, w, (1, 1), (0, 0))).all()
+
+
+def test_conv_full_pipeline_and_sampling():
+    rng = np.random.default_rng(16)
+    x = rng.integers(0, 256, (2, 7, 6, 4)).astype(np.uint8)
+    w = rng.integers(-127, 128, (5, 3, 3, 4)).astype(np.int8)
+    bias = rng.integers(-3000, 3000, 5).astype(np.int32)
+    mult, shift = oracle.quantize_multipliers(10 ** rng.uniform(-3.5, -2.5, 5))
+    z_x, z_o = 120, 3
+    y = oracle.qconv2d(x, z_x, w, (2, 1), (1, 1), mult, shift, z_o, 3, 200, bias=bias)
+    acc = oracle.qconv2d_acc(x, z_x, w, (2, 1), (1, 1))
+    for idx in np.ndindex(*y.shape):
+        a = int(acc[idx]) + int(bias[idx[3]])
+        assert y[idx] == min(200, max(3, _exact_two_stage(a, int(mult[idx[3]]), int(shift[idx[3]])) + z_o))
+    sample = rng.integers(0, y.size, 50)
+    assert (oracle.qconv2d(x, z_x, w, (2, 1), (1, 1), mult, shift, z_o, 3, 200, bias=bias, sample=sample)
+            == y.ravel()[sample]).all()
+
+
+def test_int4_weights_give_the_same_conv_as_their_int8_values():
+    rng = np.random.default_rng(17)
+    x = rng.integers(0, 256, (1, 5, 5, 6)).astype(np.uint8)
+    w = rng.integers(-8, 8, (4, 3, 3, 6)).astype(np.int8)
+    w[0, 0, 0, :2] = (-8, 7)
+    a8 = oracle.qconv2d_acc(x, 100, w, (1, 1), (1, 1))
+    a4 = oracle.qconv2d_acc(x, 100, oracle.pack_int4(w), (1, 1), (1, 1), weight_bits=4)
+    assert (a8 == a4).all()
+
+
+def test_depthwise_matches_per_channel_library_cross_correlation():
+    rng = np.random.default_rng(18)
+    N, H, W, Cc = 2, 9, 7, 5
+    x = rng.integers(0, 256, (N, H, W, Cc)).astype(np.uint8)
+    w = rng.integers(-128, 128, (3, 3, Cc)).astype(np.int8)
+    z_x = 31
+    bias = rng.integers(-100, 100, Cc).astype(np.int32)
+    mult = np.full(Cc, 2 ** 30, np.int32)  # rescale = exact halving with ties up
+    shift = np.zeros(Cc, np.int32)
+    for stride in ((1, 1), (2, 2)):
+        y = oracle.qdwconv2d(x, z_x, w, stride, (1, 1), mult, shift, 128, 0, 255, bias=bias)
+        for n in range(N):
+            for c in range(Cc):
+                full = correlate2d(x[n, :, :, c].astype(np.int64) - z_x, w[:, :, c].astype(np.int64), mode="same")
+                acc = full[:: stride[0], :: stride[1]] + bias[c]
+                want = np.clip(np.floor((acc + 1) / 2).astype(np.int64) + 128, 0, 255)
+                assert (y[n, :, :, c] == want).all()
+    sample = rng.integers(0, y.size, 40)
+    ys = oracle.qdwconv2d(x, z_x, w, (2, 2), (1, 1), mult, shift, 128, 0, 255, bias=bias, sample=sample)
+    assert (ys == y.ravel()[sample]).all()
+
+
+def test_whole_layer_against_float_convolution():
+    # quantize -> integer conv + ReLU6 -> dequantize tracks the float layer within the error
+    # budget: one output LSB plus the propagated input / weight rounding errors
+    rng = np.random.default_rng(19)
+    xf = rng.uniform(0, 6, (1, 8, 8, 8)).astype(np.float32)
+    wf = rng.normal(0, 0.1, (6, 3, 3, 8)).astype(np.float32)
+    s_x, z_x = oracle.choose_qparams(0.0, 6.0)
+    xq = oracle.quantize(xf, s_x, z_x)
+    wq, d_c = oracle.quantize_weights(wf, 8)
+    s_o, z_o = oracle.choose_qparams(0.0, 6.0)
+    lo, hi = oracle.act_range(2, s_o, z_o)
+    assert (lo, hi) == (0, 255)
+    mult, shift = oracle.quantize_multipliers(np.float64(s_x) * d_c.astype(np.float64) / s_o)
+    y = oracle.dequantize(oracle.qconv2d(xq, z_x, wq, (1, 1), (1, 1), mult, shift, z_o, lo, hi), s_o, z_o)
+    ref = np.clip(_brute_conv_fp64(xf.astype(np.float64), wf.astype(np.float64), (1, 1), (1, 1)), 0, 6)
+    k_taps = 3 * 3 * 8
+    bound = s_o + k_taps * (0.5 * s_x * np.abs(wf).max() + 0.5 * d_c.max() * 6.0)
+    assert np.abs(y - ref).max() <= bound
+    assert np.abs(y - ref).mean() <= 2 * s_o  # and is typically about one LSB
+    # ReLU6 clamp of the paper's activation range: act_range for a coarser output scale
+    assert oracle.act_range(2, 0.05, 0) == (0, 120)
+    assert oracle.act_range(1, 0.05, 17) == (17, 255)
+    assert oracle.act_range(0, 0.05, 17) == (0, 255)
+
+
+# ------------------------------------------------------------- Sec. 3.2.1: rescaling add
+
+def test_qadd_identity_case_is_plain_saturating_add():
+    a = np.arange(256, dtype=np.uint8).repeat(256)
+    b = np.tile(np.arange(256, dtype=np.uint8), 256)
+    p = oracle.qadd_params(0.1, 0.1, 0.1)
+    y = oracle.qadd(a, 0, b, 0, p, 0, 0, 255)
+    assert (y == np.minimum(255, a.astype(np.int64) + b)).all()
+
+
+def test_qadd_within_one_lsb_of_real_arithmetic():
+    rng = np.random.default_rng(20)
+    a = rng.integers(0, 256, 20000).astype(np.uint8)
+    b = rng.integers(0, 256, 20000).astype(np.uint8)
+    for _ in range(20):
+        s_a, s_b, s_o = 10 ** rng.uniform(-2, -1, 3)
+        s_o *= 2
+        z_a, z_b, z_o = rng.integers(0, 256, 3).tolist()
+        p = oracle.qadd_params(s_a, s_b, s_o)
+        assert p["left_shift"] == 20
+        y = oracle.qadd(a, z_a, b, z_b, p, z_o, 0, 255).astype(np.float64)
+        real = (s_a * (a.astype(np.float64) - z_a) + s_b * (b.astype(np.float64) - z_b)) / s_o + z_o
+        inside = (real > 0.5) & (real < 254.5)
+        assert np.abs(y - real)[inside].max() <= 1.0
+        assert (y[real <= -1] == 0).all() and (y[real >= 256] == 255).all()
