@@ -1,0 +1,185 @@
+/*
+ * qnn.h -- C ABI of the MI355X (gfx950) quantized-inference library.
+ *
+ * The library implements the integer inference scheme of "Quantizing deep
+ * convolutional networks for efficient inference: A whitepaper" (arXiv
+ * 1806.08342): uint8 activations with one affine quantizer (Delta, z) per
+ * tensor, int8 (or 4-bit) weights with one symmetric quantizer per output
+ * channel, int32 accumulation with the zero-point correction of eq. 5-6 and an
+ * int32 bias, and a fixed-point rescale back to uint8 with the ReLU / ReLU6
+ * clamp fused in.
+ *
+ * General rules for every entry point
+ *   - Pointers marked DEVICE are HIP device pointers owned by the caller
+ *     (for example the storage of a torch tensor).  Pointers marked HOST are
+ *     ordinary host pointers.  The library never allocates, frees or keeps
+ *     any of them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Device entry points only enqueue work on that stream and return; they
+ *     never synchronise.  Output buffers must not overlap input buffers.
+ *   - Return value: QNN_OK, or an error code; on error nothing is enqueued.
+ *     QNN_EINVAL      a null pointer, a non-positive size, a parameter outside
+ *                     the documented range;
+ *     QNN_EUNSUPPORTED a documented feature this build does not implement;
+ *     QNN_ELAUNCH     the HIP runtime refused the launch (qnn_last_error()
+ *                     gives the HIP error text).
+ *     The contents of device arrays (mult, shift, bias) are trusted and not read
+ *     on the host; `shift` entries must lie in [-31, 31], which the host helper
+ *     qnn_quantize_multiplier guarantees.
+ *
+ * The fixed-point rescale (not defined by the paper; this is the library's
+ * definition, referred to as RESCALE(a; mult, shift) below), on an int32 a:
+ *   1. if shift < 0:  a <- saturate_int32(a * 2^(-shift))
+ *   2. h = nearest integer to a*mult / 2^31, ties toward +infinity, computed
+ *      exactly in 64 bits; the single overflowing case a = mult = INT32_MIN
+ *      gives INT32_MAX                    (saturating rounding doubling high multiply)
+ *   3. r = nearest integer to h / 2^max(shift,0), ties away from zero
+ *   so that r ~= a * mult * 2^(-31-shift).  Outputs are
+ *   y = clamp(act_min, act_max, z_out + r) stored as uint8, 0 <= act_min <= act_max <= 255,
+ *   0 <= z_out <= 255.  ReLU is act_min = z_out; ReLU6 additionally lowers act_max
+ *   (qnn_act_range).
+ */
+#ifndef QNN_H
+#define QNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { QNN_OK = 0, QNN_EINVAL = 1, QNN_EUNSUPPORTED = 2, QNN_ELAUNCH = 3 } qnn_status;
+
+/* storage order of the GEMM weight operand B (a K x N matrix) */
+#define QNN_B_COLUMNS_CONTIGUOUS 0 /* element (k,n) at B[n*ldb + k]: one output column = one contiguous kernel */
+#define QNN_B_ROWS_CONTIGUOUS 1    /* element (k,n) at B[k*ldb + n] */
+
+/* Text of the last HIP error seen by a call that returned QNN_ELAUNCH on this thread
+ * (HOST string owned by the library, valid until the next failing call). */
+const char *qnn_last_error(void);
+
+/* Library version, "major.minor". */
+const char *qnn_version(void);
+
+/* ---------------------------------------------------------------- device entry points */
+
+/* Uniform affine quantizer, Sec. 2.1 eq. 1-2:
+ *   q[i] = clamp(qmin, qmax, round(x[i] / scale) + zero_point)
+ * x / scale is one IEEE binary32 division, round() rounds ties away from zero, NaN
+ * quantizes like 0.0.  Requires scale > 0 finite and 0 <= qmin <= zero_point <= qmax <= 255.
+ * x: DEVICE fp32[n] (read), q: DEVICE uint8[n] (written).  n == 0 is a no-op. */
+qnn_status qnn_quantize(const float *x, uint8_t *q, size_t n, float scale, int32_t zero_point, int32_t qmin,
+                        int32_t qmax, void *stream);
+
+/* De-quantizer, Sec. 2.1 eq. 3:  x[i] = (q[i] - zero_point) * scale  (one binary32 multiply).
+ * q: DEVICE uint8[n] (read), x: DEVICE fp32[n] (written).  0 <= zero_point <= 255. */
+qnn_status qnn_dequantize(const uint8_t *q, float *x, size_t n, float scale, int32_t zero_point, void *stream);
+
+/* Stand-alone rescale of an int32 accumulator tensor to uint8 (the epilogue of the
+ * convolution kernels as a kernel of its own):
+ *   y[r][c] = clamp(act_min, act_max, z_out + RESCALE(acc[r][c]; mult[p], shift[p])),
+ *   p = c when per_channel != 0 (Sec. 2.6: one quantizer per output channel), else 0.
+ * acc: DEVICE int32[rows*channels] row-major (read); y: DEVICE uint8[rows*channels] (written);
+ * mult, shift: DEVICE int32[channels] (or [1]). */
+qnn_status qnn_requantize(const int32_t *acc, uint8_t *y, size_t rows, size_t channels, const int32_t *mult,
+                          const int32_t *shift, int per_channel, int32_t z_out, int32_t act_min, int32_t act_max,
+                          void *stream);
+
+/* Quantized matrix product / fully connected layer, Sec. 2.1 eq. 4-6 with z_w = 0:
+ *   C[m][n] = clamp(act_min, act_max, z_out + RESCALE(bias[n] + sum_k (A[m][k] - z_a) * B[k][n]; mult[n], shift[n]))
+ * The sum is evaluated as sum_k A*B - z_a * sum_k B[k][n] (eq. 5-6; the weight column
+ * sums are formed inside the kernel), in int32; |sum| must stay below 2^31, which K <= 65536
+ * guarantees (larger K is rejected with QNN_EINVAL).
+ * A: DEVICE uint8, M x K row-major, row pitch lda >= K (bytes = elements).
+ * B: DEVICE weights, K x N, layout b_layout; weight_bits 8 -> int8 elements; weight_bits 4 ->
+ *    two's-complement nibbles, element 2j of a column in the low nibble of byte j and element
+ *    2j+1 in the high nibble (requires QNN_B_COLUMNS_CONTIGUOUS, K and ldb even; ldb counts
+ *    elements, so a column occupies ldb/2 bytes).
+ *    QNN_B_COLUMNS_CONTIGUOUS is the fast layout; QNN_B_ROWS_CONTIGUOUS is accepted for int8
+ *    and runs a slower gather path (use qnn_pack_b once, weights being constant at inference).
+ * bias: DEVICE int32[N] or NULL (scale s_a * Delta_n, zero-point 0); mult, shift: DEVICE int32[N].
+ * C: DEVICE uint8, M x N row-major, row pitch ldc >= N (written). */
+qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
+                     int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
+                     const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
+                     void *stream);
+
+/* Transpose a K x N int8 matrix with contiguous rows (src[k*ld_src + n]) into the
+ * columns-contiguous layout (dst[n*ld_dst + k]) that qnn_qgemm runs fastest on.
+ * src, dst: DEVICE int8; ld_src >= N, ld_dst >= K. */
+qnn_status qnn_pack_b(const int8_t *src, int64_t ld_src, int64_t K, int64_t N, int8_t *dst, int64_t ld_dst,
+                      void *stream);
+
+/* Quantized 2-D convolution (cross-correlation), Sec. 2.1 eq. 4-6 with z_w = 0:
+ *   y[n][ho][wo][co] = clamp(act_min, act_max, z_out + RESCALE(bias[co] +
+ *        sum_{a,b,ci} (x[n][ho*stride_h - pad_h + a][wo*stride_w - pad_w + b][ci] - z_x) * w[co][a][b][ci];
+ *        mult[co], shift[co]))
+ * Taps outside the image contribute 0, i.e. the border is padded with the code z_x of real
+ * zero (Sec. 2.1: zero padding causes no quantization error).
+ * x: DEVICE uint8 NHWC [N][H][W][Cin] contiguous (read).
+ * w: DEVICE weights [Cout][kh][kw][Cin] contiguous; weight_bits 8 -> int8; 4 -> nibble pairs along
+ *    Cin as in qnn_qgemm (Cin even).
+ * Ho = (H + 2 pad_h - kh)/stride_h + 1, Wo likewise; y: DEVICE uint8 NHWC [N][Ho][Wo][Cout] (written).
+ * kh*kw*Cin <= 65536.  bias may be NULL; bias, mult, shift: DEVICE int32[Cout]. */
+qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
+                       int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias,
+                       const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
+                       uint8_t *y, void *stream);
+
+/* Depthwise convolution (one kh x kw kernel per channel; the separable layers of the
+ * MobileNet family the paper evaluates), same arithmetic as qnn_qconv2d per channel:
+ *   y[n][ho][wo][c] = clamp(..., z_out + RESCALE(bias[c] + sum_{a,b} (x[n][hi][wi][c] - z_x) * w[a][b][c]; mult[c], shift[c]))
+ * x: DEVICE uint8 NHWC [N][H][W][C]; w: DEVICE int8 [kh][kw][C]; y: DEVICE uint8 NHWC [N][Ho][Wo][C].
+ * kh, kw <= 7.  bias may be NULL; bias, mult, shift: DEVICE int32[C]. */
+qnn_status qnn_qdwconv2d(const uint8_t *x, int N, int H, int W, int C, int32_t z_x, const int8_t *w, int kh, int kw,
+                         int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias, const int32_t *mult,
+                         const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *y,
+                         void *stream);
+
+/* Element-wise addition of two uint8 tensors that carry different quantizers (Sec. 3.2.1:
+ * both operands are rescaled to a common scale before the add; a following ReLU is the clamp):
+ *   ta = (a[i] - z_a) * 2^left_shift,  tb = (b[i] - z_b) * 2^left_shift
+ *   u  = RESCALE(ta; mult_a, shift_a) + RESCALE(tb; mult_b, shift_b)
+ *   y[i] = clamp(act_min, act_max, z_out + RESCALE(u; mult_o, shift_o))
+ * Parameters come from qnn_qadd_params.  0 <= left_shift <= 22.
+ * a, b: DEVICE uint8[n] (read); y: DEVICE uint8[n] (written). */
+qnn_status qnn_qadd(const uint8_t *a, int32_t z_a, int32_t mult_a, int32_t shift_a, const uint8_t *b, int32_t z_b,
+                    int32_t mult_b, int32_t shift_b, int32_t left_shift, int32_t mult_o, int32_t shift_o,
+                    int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *y, size_t n, void *stream);
+
+/* ------------------------------------------------------------------ host-only helpers */
+
+/* Quantizer parameters from a real range, Sec. 2.1: the range is first widened to contain 0,
+ * scale = (xmax - xmin) / (2^bits - 1) rounded to binary32, zero_point = round(-xmin / scale)
+ * clamped to [0, 2^bits - 1].  A degenerate range gives scale 1, zero_point 0.
+ * scale, zero_point: HOST outputs.  2 <= bits <= 16. */
+qnn_status qnn_choose_qparams(double xmin, double xmax, int bits, float *scale, int32_t *zero_point);
+
+/* (mult, shift) with real_mult ~= mult * 2^(-31 - shift), mult in [2^30, 2^31); real_mult = 0 or
+ * below 2^-32 gives (0, 0); real_mult >= 2^31 is QNN_EINVAL.  HOST outputs. */
+qnn_status qnn_quantize_multiplier(double real_mult, int32_t *mult, int32_t *shift);
+
+/* Clamp range of a fused activation in the quantized output domain (Sec. 3.2.1):
+ * kind 0 none -> [0,255]; 1 ReLU -> [z_out,255]; 2 ReLU6 -> [z_out, min(255, z_out + round(6/s_out))]. */
+qnn_status qnn_act_range(int kind, float s_out, int32_t z_out, int32_t *act_min, int32_t *act_max);
+
+/* The seven integer parameters of qnn_qadd from the three real scales (left_shift = 20). */
+qnn_status qnn_qadd_params(double s_a, double s_b, double s_out, int32_t *left_shift, int32_t *mult_a,
+                           int32_t *shift_a, int32_t *mult_b, int32_t *shift_b, int32_t *mult_o, int32_t *shift_o);
+
+/* Symmetric per-channel weight quantizer, Sec. 2.2 eq. 7-11 and Sec. 2.6: for each of `channels`
+ * kernels of `per_channel` fp32 values, delta[c] = max|w_c| / (2^(bits-1) - 1) (1 if the kernel is
+ * all zero) and wq = clamp(round(w / delta[c])), ties away from zero, clamp range
+ * [-(2^(bits-1) - 1), 2^(bits-1) - 1] if restricted else [-2^(bits-1), 2^(bits-1) - 1].  bits is 8 or 4.
+ * w: HOST fp32[channels*per_channel]; wq: HOST int8 (one value per byte); delta: HOST fp32[channels]. */
+qnn_status qnn_quantize_weights(const float *w, size_t channels, size_t per_channel, int bits, int restricted,
+                                int8_t *wq, float *delta);
+
+/* Pack n (even) int8 values in [-8,7] two per byte, element 2j in the low nibble.  HOST pointers. */
+qnn_status qnn_pack_int4(const int8_t *v, size_t n, uint8_t *packed);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QNN_H */

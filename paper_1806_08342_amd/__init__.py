@@ -1,0 +1,33 @@
+"""MI355X-native quantized-inference hot path (arXiv 1806.08342): thin Python binding over
+the C-ABI library ``libqnn.so`` built from the HIP sources in ``csrc/``.
+
+PyTorch is used for device memory and streams only; every step of the path runs in the
+library's own kernels.  Importing the package does not load the library; the first call
+does, and fails loudly when it has not been built.
+"""
+from .binding import (  # noqa: F401
+    QnnError,
+    act_range,
+    choose_qparams,
+    dequantize,
+    library_path,
+    load_library,
+    pack_b,
+    pack_int4,
+    qadd,
+    qadd_params,
+    qconv2d,
+    qdwconv2d,
+    qgemm,
+    quantize,
+    quantize_multiplier,
+    quantize_multipliers,
+    quantize_weights,
+    requantize,
+)
+
+__all__ = [
+    "QnnError", "act_range", "choose_qparams", "dequantize", "library_path", "load_library", "pack_b", "pack_int4",
+    "qadd", "qadd_params", "qconv2d", "qdwconv2d", "qgemm", "quantize", "quantize_multiplier",
+    "quantize_multipliers", "quantize_weights", "requantize",
+]

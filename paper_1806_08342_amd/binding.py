@@ -1,0 +1,256 @@
+"""ctypes binding of libqnn.so: argument marshalling only.
+
+Device tensors are torch tensors on a HIP device; the functions pass their ``data_ptr()`` and
+the current torch stream to the C ABI (``include/qnn.h``) and allocate the output tensor.
+No arithmetic of the method happens in Python.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libqnn.so")
+_lib = None
+
+STATUS = {0: "QNN_OK", 1: "QNN_EINVAL", 2: "QNN_EUNSUPPORTED", 3: "QNN_ELAUNCH"}
+B_COLUMNS_CONTIGUOUS, B_ROWS_CONTIGUOUS = 0, 1
+
+EXPORTS = [
+    "qnn_last_error", "qnn_version", "qnn_quantize", "qnn_dequantize", "qnn_requantize", "qnn_qgemm", "qnn_pack_b",
+    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
+    "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4",
+]
+
+
+class QnnError(RuntimeError):
+    def __init__(self, name, code, detail=""):
+        super().__init__(f"{name} failed with {STATUS.get(code, code)}{(': ' + detail) if detail else ''}")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libqnn.so.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it first (python -m paper_1806_08342_amd._build, or "
+            "__graft_entry__.build()); there is no CPU fallback")
+    lib = C.CDLL(_LIB_PATH)
+    lib.qnn_last_error.restype = C.c_char_p
+    lib.qnn_version.restype = C.c_char_p
+    vp, i32, i64, sz, f32, f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float, C.c_double
+    ci = C.c_int
+    sigs = {
+        "qnn_quantize": [vp, vp, sz, f32, i32, i32, i32, vp],
+        "qnn_dequantize": [vp, vp, sz, f32, i32, vp],
+        "qnn_requantize": [vp, vp, sz, sz, vp, vp, ci, i32, i32, i32, vp],
+        "qnn_qgemm": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
+        "qnn_pack_b": [vp, i64, i64, i64, vp, i64, vp],
+        "qnn_qconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
+        "qnn_qdwconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
+        "qnn_qadd": [vp, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp],
+        "qnn_choose_qparams": [f64, f64, ci, C.POINTER(f32), C.POINTER(i32)],
+        "qnn_quantize_multiplier": [f64, C.POINTER(i32), C.POINTER(i32)],
+        "qnn_act_range": [ci, f32, i32, C.POINTER(i32), C.POINTER(i32)],
+        "qnn_qadd_params": [f64, f64, f64] + [C.POINTER(i32)] * 7,
+        "qnn_quantize_weights": [vp, sz, sz, ci, ci, vp, vp],
+        "qnn_pack_int4": [vp, sz, vp],
+    }
+    for name, args in sigs.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(name, rc):
+    if rc != 0:
+        detail = load_library().qnn_last_error().decode() if rc == 3 else ""
+        raise QnnError(name, rc, detail)
+
+
+def _torch():
+    import torch
+
+    return torch
+
+
+def _stream():
+    return C.c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    torch = _torch()
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous device tensor of {dtype}, got "
+                        f"{getattr(t, 'dtype', type(t))} on {getattr(t, 'device', '?')}")
+    return C.c_void_p(t.data_ptr())
+
+
+# ------------------------------------------------------------------ host helpers
+
+def choose_qparams(xmin, xmax, bits=8):
+    s, z = C.c_float(), C.c_int32()
+    _check("qnn_choose_qparams", load_library().qnn_choose_qparams(xmin, xmax, bits, C.byref(s), C.byref(z)))
+    return float(s.value), int(z.value)
+
+
+def quantize_multiplier(real_mult):
+    m, s = C.c_int32(), C.c_int32()
+    _check("qnn_quantize_multiplier", load_library().qnn_quantize_multiplier(float(real_mult), C.byref(m), C.byref(s)))
+    return int(m.value), int(s.value)
+
+
+def quantize_multipliers(real_mults):
+    """Vector form: returns (mult, shift) as int32 numpy arrays."""
+    vals = np.asarray(real_mults, dtype=np.float64).ravel()
+    out = [quantize_multiplier(v) for v in vals]
+    return (np.array([o[0] for o in out], dtype=np.int32), np.array([o[1] for o in out], dtype=np.int32))
+
+
+def act_range(kind, s_out, z_out):
+    lo, hi = C.c_int32(), C.c_int32()
+    _check("qnn_act_range", load_library().qnn_act_range(int(kind), float(s_out), int(z_out), C.byref(lo), C.byref(hi)))
+    return int(lo.value), int(hi.value)
+
+
+def qadd_params(s_a, s_b, s_out):
+    v = [C.c_int32() for _ in range(7)]
+    _check("qnn_qadd_params", load_library().qnn_qadd_params(float(s_a), float(s_b), float(s_out), *[C.byref(t) for t in v]))
+    names = ["left_shift", "mult_a", "shift_a", "mult_b", "shift_b", "mult_o", "shift_o"]
+    return {k: int(t.value) for k, t in zip(names, v)}
+
+
+def quantize_weights(w, bits=8, restricted=True):
+    """Host fp32 array [channels, ...] -> (int8 array of the same shape, Delta_c[channels])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    ch = w.shape[0]
+    wq = np.empty(w.shape, dtype=np.int8)
+    d = np.empty(ch, dtype=np.float32)
+    _check("qnn_quantize_weights", load_library().qnn_quantize_weights(
+        w.ctypes.data, ch, w.size // ch, int(bits), int(bool(restricted)), wq.ctypes.data, d.ctypes.data))
+    return wq, d
+
+
+def pack_int4(v):
+    v = np.ascontiguousarray(v, dtype=np.int8)
+    out = np.empty(v.shape[:-1] + (v.shape[-1] // 2,), dtype=np.uint8)
+    _check("qnn_pack_int4", load_library().qnn_pack_int4(v.ctypes.data, v.size, out.ctypes.data))
+    return out
+
+
+# ---------------------------------------------------------------- device kernels
+
+def quantize(x, scale, zero_point, qmin=0, qmax=255, out=None):
+    torch = _torch()
+    q = torch.empty(x.shape, dtype=torch.uint8, device=x.device) if out is None else out
+    _check("qnn_quantize", load_library().qnn_quantize(_dev(x, torch.float32, "x"), _dev(q, torch.uint8, "q"),
+                                                      x.numel(), scale, zero_point, qmin, qmax, _stream()))
+    return q
+
+
+def dequantize(q, scale, zero_point, out=None):
+    torch = _torch()
+    x = torch.empty(q.shape, dtype=torch.float32, device=q.device) if out is None else out
+    _check("qnn_dequantize", load_library().qnn_dequantize(_dev(q, torch.uint8, "q"), _dev(x, torch.float32, "x"),
+                                                          q.numel(), scale, zero_point, _stream()))
+    return x
+
+
+def requantize(acc, mult, shift, per_channel, z_out, act_min, act_max, out=None):
+    torch = _torch()
+    rows, ch = acc.shape
+    y = torch.empty((rows, ch), dtype=torch.uint8, device=acc.device) if out is None else out
+    _check("qnn_requantize", load_library().qnn_requantize(
+        _dev(acc, torch.int32, "acc"), _dev(y, torch.uint8, "y"), rows, ch, _dev(mult, torch.int32, "mult"),
+        _dev(shift, torch.int32, "shift"), int(bool(per_channel)), z_out, act_min, act_max, _stream()))
+    return y
+
+
+def qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8,
+          b_layout=B_COLUMNS_CONTIGUOUS, out=None):
+    """A: uint8 [M,K].  B: int8 [N,K] (columns contiguous), int8 [K,N] (rows contiguous), or uint8
+    [N,K/2] nibble-packed when weight_bits == 4.  Returns uint8 [M,N]."""
+    torch = _torch()
+    M, K = A.shape
+    if weight_bits == 4:
+        N, ldb = B.shape[0], B.shape[1] * 2
+        bp = _dev(B, torch.uint8, "B")
+    elif b_layout == B_COLUMNS_CONTIGUOUS:
+        N, ldb = B.shape
+        bp = _dev(B, torch.int8, "B")
+    else:
+        ldb = N = B.shape[1]
+        bp = _dev(B, torch.int8, "B")
+    Cm = torch.empty((M, N), dtype=torch.uint8, device=A.device) if out is None else out
+    _check("qnn_qgemm", load_library().qnn_qgemm(
+        _dev(A, torch.uint8, "A"), K, z_a, bp, ldb, b_layout, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
+        _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max,
+        _dev(Cm, torch.uint8, "C"), N, _stream()))
+    return Cm
+
+
+def pack_b(B_rows):
+    """int8 [K,N] with contiguous rows -> int8 [N,K] (the layout qgemm runs fastest on)."""
+    torch = _torch()
+    K, N = B_rows.shape
+    out = torch.empty((N, K), dtype=torch.int8, device=B_rows.device)
+    _check("qnn_pack_b", load_library().qnn_pack_b(_dev(B_rows, torch.int8, "B"), N, K, N,
+                                                  _dev(out, torch.int8, "out"), K, _stream()))
+    return out
+
+
+def _out_hw(H, W, kh, kw, stride, pad):
+    return (H + 2 * pad[0] - kh) // stride[0] + 1, (W + 2 * pad[1] - kw) // stride[1] + 1
+
+
+def qconv2d(x, z_x, w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8, out=None):
+    """x: uint8 NHWC.  w: int8 [Cout,kh,kw,Cin], or uint8 [Cout,kh,kw,Cin/2] packed 4-bit."""
+    torch = _torch()
+    N, H, W, Cin = x.shape
+    Cout, kh, kw = w.shape[:3]
+    wp = _dev(w, torch.uint8 if weight_bits == 4 else torch.int8, "w")
+    Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
+    y = torch.empty((N, Ho, Wo, Cout), dtype=torch.uint8, device=x.device) if out is None else out
+    _check("qnn_qconv2d", load_library().qnn_qconv2d(
+        _dev(x, torch.uint8, "x"), N, H, W, Cin, z_x, wp, Cout, kh, kw, weight_bits, stride[0], stride[1], pad[0],
+        pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"),
+        z_out, act_min, act_max, _dev(y, torch.uint8, "y"), _stream()))
+    return y
+
+
+def qdwconv2d(x, z_x, w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, out=None):
+    """x: uint8 NHWC.  w: int8 [kh,kw,C]."""
+    torch = _torch()
+    N, H, W, Cc = x.shape
+    kh, kw = w.shape[:2]
+    Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
+    y = torch.empty((N, Ho, Wo, Cc), dtype=torch.uint8, device=x.device) if out is None else out
+    _check("qnn_qdwconv2d", load_library().qnn_qdwconv2d(
+        _dev(x, torch.uint8, "x"), N, H, W, Cc, z_x, _dev(w, torch.int8, "w"), kh, kw, stride[0], stride[1], pad[0],
+        pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"),
+        z_out, act_min, act_max, _dev(y, torch.uint8, "y"), _stream()))
+    return y
+
+
+def qadd(a, z_a, b, z_b, params, z_out, act_min, act_max, out=None):
+    torch = _torch()
+    y = torch.empty(a.shape, dtype=torch.uint8, device=a.device) if out is None else out
+    p = params
+    _check("qnn_qadd", load_library().qnn_qadd(
+        _dev(a, torch.uint8, "a"), z_a, p["mult_a"], p["shift_a"], _dev(b, torch.uint8, "b"), z_b, p["mult_b"],
+        p["shift_b"], p["left_shift"], p["mult_o"], p["shift_o"], z_out, act_min, act_max, _dev(y, torch.uint8, "y"),
+        a.numel(), _stream()))
+    return y

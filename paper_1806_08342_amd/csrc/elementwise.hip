@@ -1,0 +1,342 @@
+// Streaming (HBM-bound) kernels: affine quantize / de-quantize (Sec. 2.1 eq. 1-3),
+// stand-alone rescale of int32 accumulators, rescaling add (Sec. 3.2.1), weight transpose.
+//
+// All of them move each byte once: 16-byte loads per lane, consecutive lanes on
+// consecutive addresses, grid sized to a few waves per SIMD and a grid-stride loop.
+#include "qnn_device.h"
+
+namespace qnn {
+
+constexpr int kThreads = 256;
+
+using f32x4 = float __attribute__((ext_vector_type(4)));
+using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
+using i32x4 = int32_t __attribute__((ext_vector_type(4)));
+
+static int grid_for(size_t work_items, int per_block, int max_blocks = 256 * 16)
+{
+    size_t b = (work_items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > (size_t)max_blocks) b = max_blocks;
+    return (int)b;
+}
+
+// ------------------------------------------------------------------ quantize
+
+__device__ __forceinline__ uint32_t quantize_one(float x, float scale, float lo, float hi, int32_t z)
+{
+    float t = __fdiv_rn(x, scale);   // one correctly rounded binary32 division
+    float r = roundf(t);             // ties away from zero
+    r = (t != t) ? 0.0f : r;         // NaN behaves like 0.0
+    r = r < lo ? lo : r;
+    r = r > hi ? hi : r;
+    return (uint32_t)((int32_t)r + z);
+}
+
+// VEC = 4: x is 16-byte aligned, q 4-byte aligned; VEC = 1: anything.
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) quantize_kernel(const float *__restrict__ x, uint8_t *__restrict__ q,
+                                                            size_t n, float scale, int32_t z, float lo, float hi)
+{
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    if (VEC == 4) {
+        const size_t nvec = n / 4;
+        const f32x4 *xv = reinterpret_cast<const f32x4 *>(x);
+        uint32_t *qv = reinterpret_cast<uint32_t *>(q);
+        size_t v = tid;
+        // four independent 16-byte loads in flight per lane
+        for (; v + 3 * nthreads < nvec; v += 4 * nthreads) {
+            f32x4 a[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) a[u] = __builtin_nontemporal_load(&xv[v + u * nthreads]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                uint32_t p = quantize_one(a[u].x, scale, lo, hi, z) | (quantize_one(a[u].y, scale, lo, hi, z) << 8) |
+                             (quantize_one(a[u].z, scale, lo, hi, z) << 16) |
+                             (quantize_one(a[u].w, scale, lo, hi, z) << 24);
+                __builtin_nontemporal_store(p, &qv[v + u * nthreads]);
+            }
+        }
+        for (; v < nvec; v += nthreads) {
+            f32x4 a = xv[v];
+            qv[v] = quantize_one(a.x, scale, lo, hi, z) | (quantize_one(a.y, scale, lo, hi, z) << 8) |
+                    (quantize_one(a.z, scale, lo, hi, z) << 16) | (quantize_one(a.w, scale, lo, hi, z) << 24);
+        }
+        for (size_t i = nvec * 4 + tid; i < n; i += nthreads) q[i] = (uint8_t)quantize_one(x[i], scale, lo, hi, z);
+    } else {
+        for (size_t i = tid; i < n; i += nthreads) q[i] = (uint8_t)quantize_one(x[i], scale, lo, hi, z);
+    }
+}
+
+// ---------------------------------------------------------------- dequantize
+
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) dequantize_kernel(const uint8_t *__restrict__ q, float *__restrict__ x,
+                                                              size_t n, float scale, int32_t z)
+{
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    if (VEC == 4) {
+        const size_t nvec = n / 4;
+        const uint32_t *qv = reinterpret_cast<const uint32_t *>(q);
+        f32x4 *xv = reinterpret_cast<f32x4 *>(x);
+        size_t v = tid;
+        for (; v + 3 * nthreads < nvec; v += 4 * nthreads) {
+            uint32_t p[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) p[u] = __builtin_nontemporal_load(&qv[v + u * nthreads]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                f32x4 o;
+                o.x = __fmul_rn((float)((int32_t)(p[u] & 0xffu) - z), scale);
+                o.y = __fmul_rn((float)((int32_t)((p[u] >> 8) & 0xffu) - z), scale);
+                o.z = __fmul_rn((float)((int32_t)((p[u] >> 16) & 0xffu) - z), scale);
+                o.w = __fmul_rn((float)((int32_t)(p[u] >> 24) - z), scale);
+                __builtin_nontemporal_store(o, &xv[v + u * nthreads]);
+            }
+        }
+        for (; v < nvec; v += nthreads) {
+            uint32_t p = qv[v];
+            f32x4 o;
+            o.x = __fmul_rn((float)((int32_t)(p & 0xffu) - z), scale);
+            o.y = __fmul_rn((float)((int32_t)((p >> 8) & 0xffu) - z), scale);
+            o.z = __fmul_rn((float)((int32_t)((p >> 16) & 0xffu) - z), scale);
+            o.w = __fmul_rn((float)((int32_t)(p >> 24) - z), scale);
+            xv[v] = o;
+        }
+        for (size_t i = nvec * 4 + tid; i < n; i += nthreads) x[i] = __fmul_rn((float)((int32_t)q[i] - z), scale);
+    } else {
+        for (size_t i = tid; i < n; i += nthreads) x[i] = __fmul_rn((float)((int32_t)q[i] - z), scale);
+    }
+}
+
+// ---------------------------------------------------------------- requantize
+
+// VEC = 4: acc 16-byte aligned, y 4-byte aligned, channels % 4 == 0 (so four consecutive
+// elements never straddle a row).  One lane rescales 4 accumulators and stores 4 bytes.
+template <int VEC, bool PER_CHANNEL>
+__global__ void __launch_bounds__(kThreads)
+    requantize_kernel(const int32_t *__restrict__ acc, uint8_t *__restrict__ y, size_t total, uint32_t channels,
+                      const int32_t *__restrict__ mult, const int32_t *__restrict__ shift, int32_t z_out,
+                      int32_t act_min, int32_t act_max)
+{
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    RescaleParams uni = make_rescale(mult[0], shift[0]);
+    if (VEC == 4) {
+        const size_t nvec = total / 4;
+        const i32x4 *av = reinterpret_cast<const i32x4 *>(acc);
+        uint32_t *yv = reinterpret_cast<uint32_t *>(y);
+        for (size_t v = tid; v < nvec; v += nthreads) {
+            i32x4 a = __builtin_nontemporal_load(&av[v]);
+            int32_t in[4] = {a.x, a.y, a.z, a.w};
+            uint32_t packed = 0;
+            uint32_t c = PER_CHANNEL ? (uint32_t)((v * 4) % channels) : 0u;
+            i32x4 m4 = {0, 0, 0, 0}, s4 = {0, 0, 0, 0};
+            if (PER_CHANNEL) {
+                m4 = *reinterpret_cast<const i32x4 *>(mult + c);
+                s4 = *reinterpret_cast<const i32x4 *>(shift + c);
+            }
+            const int32_t mm[4] = {m4.x, m4.y, m4.z, m4.w};
+            const int32_t ss[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                RescaleParams p = PER_CHANNEL ? make_rescale(mm[j], ss[j]) : uni;
+                // clamp before adding z_out: the rescaled value may sit at the int32 limits
+                int32_t r = clamp_i32(act_min - z_out, act_max - z_out, rescale_general(in[j], p)) + z_out;
+                packed |= (uint32_t)r << (8 * j);
+            }
+            __builtin_nontemporal_store(packed, &yv[v]);
+        }
+    } else {
+        for (size_t i = tid; i < total; i += nthreads) {
+            RescaleParams p = uni;
+            if (PER_CHANNEL) {
+                uint32_t c = (uint32_t)(i % channels);
+                p = make_rescale(mult[c], shift[c]);
+            }
+            y[i] = (uint8_t)(clamp_i32(act_min - z_out, act_max - z_out, rescale_general(acc[i], p)) + z_out);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------- qadd
+
+struct QaddArgs {
+    int32_t z_a, mult_a, shift_a, z_b, mult_b, shift_b, left_shift, mult_o, shift_o, z_out, act_min, act_max;
+};
+
+// The rescaled value of an input depends only on its 8-bit code, so each block first
+// tabulates RESCALE((v - z) * 2^L) for the 256 codes of a and of b in LDS; the streaming
+// loop is then two table reads, an add and one rescale per element.
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) qadd_kernel(const uint8_t *__restrict__ a, const uint8_t *__restrict__ b,
+                                                        uint8_t *__restrict__ y, size_t n, QaddArgs g)
+{
+    __shared__ int32_t tab_a[256];
+    __shared__ int32_t tab_b[256];
+    {
+        const int v = threadIdx.x; // kThreads == 256
+        tab_a[v] = rescale_general((v - g.z_a) * (1 << g.left_shift), make_rescale(g.mult_a, g.shift_a));
+        tab_b[v] = rescale_general((v - g.z_b) * (1 << g.left_shift), make_rescale(g.mult_b, g.shift_b));
+    }
+    __syncthreads();
+    const RescaleParams po = make_rescale(g.mult_o, g.shift_o);
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    auto one = [&](uint32_t ca, uint32_t cb) -> uint32_t {
+        int64_t u = (int64_t)tab_a[ca] + (int64_t)tab_b[cb];
+        u = u > INT32_MAX ? INT32_MAX : (u < INT32_MIN ? INT32_MIN : u);
+        return (uint32_t)(clamp_i32(g.act_min - g.z_out, g.act_max - g.z_out, rescale_general((int32_t)u, po)) + g.z_out);
+    };
+    if (VEC == 16) {
+        const size_t nvec = n / 16;
+        const u32x4 *av = reinterpret_cast<const u32x4 *>(a);
+        const u32x4 *bv = reinterpret_cast<const u32x4 *>(b);
+        u32x4 *yv = reinterpret_cast<u32x4 *>(y);
+        for (size_t v = tid; v < nvec; v += nthreads) {
+            u32x4 pa = __builtin_nontemporal_load(&av[v]);
+            u32x4 pb = __builtin_nontemporal_load(&bv[v]);
+            const uint32_t wa[4] = {pa.x, pa.y, pa.z, pa.w};
+            const uint32_t wb[4] = {pb.x, pb.y, pb.z, pb.w};
+            uint32_t wo[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                uint32_t o = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o |= one((wa[d] >> (8 * j)) & 0xffu, (wb[d] >> (8 * j)) & 0xffu) << (8 * j);
+                wo[d] = o;
+            }
+            u32x4 out = {wo[0], wo[1], wo[2], wo[3]};
+            __builtin_nontemporal_store(out, &yv[v]);
+        }
+        for (size_t i = nvec * 16 + tid; i < n; i += nthreads) y[i] = (uint8_t)one(a[i], b[i]);
+    } else {
+        for (size_t i = tid; i < n; i += nthreads) y[i] = (uint8_t)one(a[i], b[i]);
+    }
+}
+
+// ------------------------------------------------------------------- pack_b
+
+// dst[n][k] = src[k][n], 64x64 byte tiles through LDS so both sides are coalesced
+__global__ void __launch_bounds__(kThreads) pack_b_kernel(const int8_t *__restrict__ src, int64_t ld_src, int64_t K,
+                                                          int64_t N, int8_t *__restrict__ dst, int64_t ld_dst)
+{
+    __shared__ int8_t tile[64][65];
+    const int64_t k0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+        const int64_t k = k0 + r, n = n0 + tx;
+        tile[r][tx] = (k < K && n < N) ? src[k * ld_src + n] : (int8_t)0;
+    }
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4) {
+        const int64_t n = n0 + r, k = k0 + tx;
+        if (n < N && k < K) dst[n * ld_dst + k] = tile[tx][r];
+    }
+}
+
+static bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+} // namespace qnn
+
+using namespace qnn;
+
+extern "C" {
+
+qnn_status qnn_quantize(const float *x, uint8_t *q, size_t n, float scale, int32_t zero_point, int32_t qmin,
+                        int32_t qmax, void *stream)
+{
+    if (!(scale > 0.0f) || __builtin_isinf(scale)) return QNN_EINVAL;
+    if (qmin < 0 || qmax > 255 || qmin > qmax || zero_point < qmin || zero_point > qmax) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (!x || !q) return QNN_EINVAL;
+    const float lo = (float)(qmin - zero_point), hi = (float)(qmax - zero_point);
+    if (aligned(x, 16) && aligned(q, 4)) {
+        const int grid = grid_for(n / 4 + 1, kThreads * 4);
+        hipLaunchKernelGGL(quantize_kernel<4>, dim3(grid), dim3(kThreads), 0, as_stream(stream), x, q, n, scale,
+                           zero_point, lo, hi);
+    } else {
+        hipLaunchKernelGGL(quantize_kernel<1>, dim3(grid_for(n, kThreads * 4)), dim3(kThreads), 0, as_stream(stream),
+                           x, q, n, scale, zero_point, lo, hi);
+    }
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_dequantize(const uint8_t *q, float *x, size_t n, float scale, int32_t zero_point, void *stream)
+{
+    if (!(scale > 0.0f) || __builtin_isinf(scale) || zero_point < 0 || zero_point > 255) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (!x || !q) return QNN_EINVAL;
+    if (aligned(x, 16) && aligned(q, 4)) {
+        hipLaunchKernelGGL(dequantize_kernel<4>, dim3(grid_for(n / 4 + 1, kThreads * 4)), dim3(kThreads), 0,
+                           as_stream(stream), q, x, n, scale, zero_point);
+    } else {
+        hipLaunchKernelGGL(dequantize_kernel<1>, dim3(grid_for(n, kThreads * 4)), dim3(kThreads), 0,
+                           as_stream(stream), q, x, n, scale, zero_point);
+    }
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_requantize(const int32_t *acc, uint8_t *y, size_t rows, size_t channels, const int32_t *mult,
+                          const int32_t *shift, int per_channel, int32_t z_out, int32_t act_min, int32_t act_max,
+                          void *stream)
+{
+    if (!acc || !y || !mult || !shift || rows == 0 || channels == 0 || channels > 0x7fffffffu) return QNN_EINVAL;
+    if (bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
+    const size_t total = rows * channels;
+    const bool vec = aligned(acc, 16) && aligned(y, 4) && (channels % 4 == 0) && aligned(mult, 16) && aligned(shift, 16);
+    const hipStream_t s = as_stream(stream);
+    const uint32_t ch = (uint32_t)channels;
+    if (vec) {
+        const int grid = grid_for(total / 4, kThreads * 2);
+        if (per_channel)
+            hipLaunchKernelGGL((requantize_kernel<4, true>), dim3(grid), dim3(kThreads), 0, s, acc, y, total, ch, mult,
+                               shift, z_out, act_min, act_max);
+        else
+            hipLaunchKernelGGL((requantize_kernel<4, false>), dim3(grid), dim3(kThreads), 0, s, acc, y, total, ch,
+                               mult, shift, z_out, act_min, act_max);
+    } else {
+        const int grid = grid_for(total, kThreads * 4);
+        if (per_channel)
+            hipLaunchKernelGGL((requantize_kernel<1, true>), dim3(grid), dim3(kThreads), 0, s, acc, y, total, ch, mult,
+                               shift, z_out, act_min, act_max);
+        else
+            hipLaunchKernelGGL((requantize_kernel<1, false>), dim3(grid), dim3(kThreads), 0, s, acc, y, total, ch,
+                               mult, shift, z_out, act_min, act_max);
+    }
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_qadd(const uint8_t *a, int32_t z_a, int32_t mult_a, int32_t shift_a, const uint8_t *b, int32_t z_b,
+                    int32_t mult_b, int32_t shift_b, int32_t left_shift, int32_t mult_o, int32_t shift_o,
+                    int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *y, size_t n, void *stream)
+{
+    if (left_shift < 0 || left_shift > 22 || z_a < 0 || z_a > 255 || z_b < 0 || z_b > 255) return QNN_EINVAL;
+    if (bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
+    auto bad_shift = [](int32_t s) { return s < -31 || s > 31; };
+    if (bad_shift(shift_a) || bad_shift(shift_b) || bad_shift(shift_o)) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (!a || !b || !y) return QNN_EINVAL;
+    QaddArgs g = {z_a, mult_a, shift_a, z_b, mult_b, shift_b, left_shift, mult_o, shift_o, z_out, act_min, act_max};
+    if (aligned(a, 16) && aligned(b, 16) && aligned(y, 16))
+        hipLaunchKernelGGL(qadd_kernel<16>, dim3(grid_for(n / 16 + 1, kThreads * 2)), dim3(kThreads), 0,
+                           as_stream(stream), a, b, y, n, g);
+    else
+        hipLaunchKernelGGL(qadd_kernel<1>, dim3(grid_for(n, kThreads * 4)), dim3(kThreads), 0, as_stream(stream), a, b,
+                           y, n, g);
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_pack_b(const int8_t *src, int64_t ld_src, int64_t K, int64_t N, int8_t *dst, int64_t ld_dst,
+                      void *stream)
+{
+    if (!src || !dst || K <= 0 || N <= 0 || ld_src < N || ld_dst < K) return QNN_EINVAL;
+    if ((N + 63) / 64 > 0x7fffffff || (K + 63) / 64 > 65535) return QNN_EINVAL;
+    dim3 grid((unsigned)((N + 63) / 64), (unsigned)((K + 63) / 64));
+    hipLaunchKernelGGL(pack_b_kernel, grid, dim3(kThreads), 0, as_stream(stream), src, ld_src, K, N, dst, ld_dst);
+    return launch_status(hipGetLastError());
+}
+
+} // extern "C"

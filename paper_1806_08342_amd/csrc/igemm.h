@@ -1,0 +1,348 @@
+// Implicit-GEMM kernel for the dense quantized layers (GEMM / fully connected, 1x1, 3x3, 7x7
+// convolutions) on gfx950 int8 MFMA.
+//
+//   acc[m][n] = sum_k xs[m][k] * w[k][n],  xs = x - 128 (the MFMA int8 operands are signed)
+//   a         = acc + bias[n] + (128 - z_x) * sum_k w[k][n]          (eq. 5-6 with z_w = 0)
+//   out       = clamp(z_out + RESCALE(a))
+//
+// m runs over output pixels (n, ho, wo) and k over (kh, kw, ci), gathered on the fly from
+// the NHWC image; taps outside the image are filled with the code z_x, so the single
+// column-sum correction is valid at the border too.  The weight column sums are formed
+// from the B fragments while they stream through the registers (v_dot4 with a vector of
+// ones), not in a separate pass.
+//
+// Tile: BM x BN outputs per workgroup, K in steps of 64; WM x WN waves, each owning a
+// (BM/WM) x (BN/WN) sub-tile built from 32x32x32 MFMAs.  Both operands are staged in LDS as
+// rows of 64 bytes whose four 16-byte chunks are XOR-swizzled with the row index, so that
+// the 16-byte fragment reads of 32 consecutive rows and the 16-byte staging writes are both
+// bank-conflict free.
+#pragma once
+
+#include "qnn_device.h"
+
+namespace qnn {
+
+using i32x4 = int32_t __attribute__((ext_vector_type(4)));
+using i32x16 = int32_t __attribute__((ext_vector_type(16)));
+using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
+using u32x2 = uint32_t __attribute__((ext_vector_type(2)));
+
+enum { A_MATRIX = 0, A_CONV = 1 };
+enum { B_INT8 = 0, B_INT4 = 1, B_INT8_ROWS = 2 };
+
+struct IgemmArgs {
+    const uint8_t *A;
+    int64_t lda; // A_MATRIX: row pitch
+    // A_CONV geometry
+    int H, W, Cin, Ho, Wo, kw, sh, sw, ph, pw;
+    uint32_t magic_cin, magic_kw; // ceil(2^32 / d): floor(k / d) = mulhi(k, magic) for k < 2^16
+    const uint8_t *B;
+    int64_t ldb; // elements
+    int64_t M;
+    int32_t N, K;
+    int32_t z_a;
+    const int32_t *bias, *mult, *shift;
+    int32_t z_out, lo_rel, hi_rel; // clamp range relative to z_out
+    uint8_t *C;
+    int64_t ldc;
+    int32_t c_vec16;  // C and ldc are 16-byte aligned
+    int32_t small_acc; // |acc| and the zero-point correction are each below 2^28
+};
+
+__device__ __forceinline__ uint32_t fast_div(uint32_t k, uint32_t d, uint32_t magic)
+{
+    return d == 1 ? k : __umulhi(k, magic);
+}
+
+// swizzled byte offset of 16-byte chunk c (0..3) of a 64-byte tile row
+__device__ __forceinline__ int lds_chunk_offset(int row, int c)
+{
+    return row * 64 + (((c ^ (row >> 1) ^ (row >> 3)) & 3) << 4);
+}
+
+template <int VEC> struct PieceLoader;
+template <> struct PieceLoader<16> {
+    static __device__ __forceinline__ void load(const uint8_t *p, uint32_t *w, int piece)
+    {
+        (void)piece;
+        u32x4 v = *reinterpret_cast<const u32x4 *>(p);
+        w[0] = v.x, w[1] = v.y, w[2] = v.z, w[3] = v.w;
+    }
+};
+template <> struct PieceLoader<8> {
+    static __device__ __forceinline__ void load(const uint8_t *p, uint32_t *w, int piece)
+    {
+        u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+        w[2 * piece] = v.x, w[2 * piece + 1] = v.y;
+    }
+};
+template <> struct PieceLoader<4> {
+    static __device__ __forceinline__ void load(const uint8_t *p, uint32_t *w, int piece)
+    {
+        w[piece] = *reinterpret_cast<const uint32_t *>(p);
+    }
+};
+template <> struct PieceLoader<1> {
+    static __device__ __forceinline__ void load(const uint8_t *p, uint32_t *w, int piece)
+    {
+        const int sh = (piece & 3) * 8;
+        w[piece >> 2] = (w[piece >> 2] & ~(0xffu << sh)) | ((uint32_t)(*p) << sh);
+    }
+};
+
+struct ARow {
+    const uint8_t *base; // A_MATRIX: row start; A_CONV: image start
+    int hi0, wi0;
+    bool valid;
+};
+
+// 16 consecutive k (one chunk) of one A row, as 4 dwords of uint8 codes
+template <int A_MODE, int VEC>
+__device__ __forceinline__ void load_a_chunk(const IgemmArgs &g, const ARow &r, int kc, uint32_t fill, uint32_t *w)
+{
+    w[0] = w[1] = w[2] = w[3] = fill;
+    if (!r.valid) return;
+#pragma unroll
+    for (int p = 0; p < 16 / VEC; ++p) {
+        const int k = kc + p * VEC;
+        if (k >= g.K) break;
+        if constexpr (A_MODE == A_MATRIX) {
+            PieceLoader<VEC>::load(r.base + k, w, p);
+        } else {
+            const uint32_t tap = fast_div((uint32_t)k, (uint32_t)g.Cin, g.magic_cin);
+            const int ci = k - (int)tap * g.Cin;
+            const uint32_t ta = fast_div(tap, (uint32_t)g.kw, g.magic_kw);
+            const int tb = (int)tap - (int)ta * g.kw;
+            const int hi = r.hi0 + (int)ta, wi = r.wi0 + tb;
+            if (hi >= 0 && hi < g.H && wi >= 0 && wi < g.W)
+                PieceLoader<VEC>::load(r.base + ((int64_t)hi * g.W + wi) * g.Cin + ci, w, p);
+            // else: stays at the fill code z_x
+        }
+    }
+}
+
+// 16 consecutive k of one B column as 4 dwords of int8 (B_INT4: the values times 16)
+template <int B_MODE, int VEC>
+__device__ __forceinline__ void load_b_chunk(const IgemmArgs &g, int n, int kc, uint32_t *w)
+{
+    w[0] = w[1] = w[2] = w[3] = 0u;
+    if (n >= g.N) return;
+    if constexpr (B_MODE == B_INT8) {
+        const uint8_t *col = g.B + (int64_t)n * g.ldb;
+#pragma unroll
+        for (int p = 0; p < 16 / VEC; ++p) {
+            const int k = kc + p * VEC;
+            if (k >= g.K) break;
+            PieceLoader<VEC>::load(col + k, w, p);
+        }
+    } else if constexpr (B_MODE == B_INT8_ROWS) {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int k = kc + p;
+            if (k >= g.K) break;
+            PieceLoader<1>::load(g.B + (int64_t)k * g.ldb + n, w, p);
+        }
+    } else { // nibble pairs, element 2j in the low nibble of byte j
+        const uint8_t *col = g.B + (((int64_t)n * g.ldb) >> 1);
+        if constexpr (VEC >= 8) {
+            uint32_t raw[4] = {0u, 0u, 0u, 0u}; // VEC elements = VEC/2 bytes per piece
+#pragma unroll
+            for (int p = 0; p < 16 / VEC; ++p) {
+                const int k = kc + p * VEC;
+                if (k >= g.K) break;
+                PieceLoader<VEC / 2>::load(col + (k >> 1), raw, p);
+            }
+#pragma unroll
+            for (int d = 0; d < 2; ++d) { // raw[d] holds elements 8d .. 8d+7
+                const uint32_t even = (raw[d] << 4) & 0xF0F0F0F0u; // e0 e2 e4 e6, each times 16
+                const uint32_t odd = raw[d] & 0xF0F0F0F0u;          // e1 e3 e5 e7
+                w[2 * d] = (even & 0xFFu) | ((odd & 0xFFu) << 8) | ((even & 0xFF00u) << 8) | ((odd & 0xFF00u) << 16);
+                w[2 * d + 1] = ((even >> 16) & 0xFFu) | (((odd >> 16) & 0xFFu) << 8) | (((even >> 24) & 0xFFu) << 16) |
+                               ((odd >> 24) << 24);
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                const int k = kc + p;
+                if (k >= g.K) break;
+                const uint32_t byte = col[k >> 1];
+                const uint32_t v = ((byte >> ((k & 1) * 4)) & 0xFu) << 4;
+                w[p >> 2] |= v << ((p & 3) * 8);
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int A_MODE, int B_MODE, int VEC>
+__global__ void __launch_bounds__(WM *WN * 64) igemm_kernel(const IgemmArgs g)
+{
+    constexpr int NT = WM * WN * 64;
+    constexpr int BK = 64;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int A_CHUNKS = BM * 4 / NT, B_CHUNKS = BN * 4 / NT;
+    static_assert(BM * 4 % NT == 0 && BN * 4 % NT == 0, "staging assumes whole chunks per thread");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 MFMA tiles");
+    constexpr int OUT_PITCH = BN + 16;
+    constexpr int STAGE_BYTES = (BM + BN) * BK;
+    constexpr int SMEM_BYTES = (2 * STAGE_BYTES > BM * OUT_PITCH) ? 2 * STAGE_BYTES : BM * OUT_PITCH;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wave_m = wave / WN, wave_n = wave % WN;
+
+    const int tiles_n = (g.N + BN - 1) / BN;
+    const int64_t tile = blockIdx.x;
+    const int64_t m0 = (tile / tiles_n) * BM;
+    const int n0 = (int)(tile % tiles_n) * BN;
+
+    // ---- rows of A and columns of B this thread stages (the same ones at every k step)
+    const int chunk_c = tid & 3;
+    ARow arow[A_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+        const int64_t m = m0 + (tid >> 2) + i * (NT / 4);
+        arow[i].valid = m < g.M;
+        arow[i].hi0 = arow[i].wi0 = 0;
+        if (A_MODE == A_MATRIX) {
+            arow[i].base = g.A + m * g.lda;
+        } else {
+            const int64_t img = m / ((int64_t)g.Ho * g.Wo);
+            const int rem = (int)(m - img * ((int64_t)g.Ho * g.Wo));
+            const int ho = rem / g.Wo, wo = rem - ho * g.Wo;
+            arow[i].base = g.A + img * ((int64_t)g.H * g.W * g.Cin);
+            arow[i].hi0 = ho * g.sh - g.ph;
+            arow[i].wi0 = wo * g.sw - g.pw;
+        }
+    }
+    const uint32_t fill_a = (uint32_t)g.z_a * 0x01010101u;
+
+    uint32_t stage_a[A_CHUNKS][4], stage_b[B_CHUNKS][4];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) load_a_chunk<A_MODE, VEC>(g, arow[i], k0 + chunk_c * 16, fill_a, stage_a[i]);
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i)
+            load_b_chunk<B_MODE, VEC>(g, n0 + (tid >> 2) + i * (NT / 4), k0 + chunk_c * 16, stage_b[i]);
+    };
+    auto commit = [&](int buf) {
+        uint8_t *sa = smem + buf * STAGE_BYTES;
+        uint8_t *sb = sa + BM * BK;
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const int row = (tid >> 2) + i * (NT / 4);
+            u32x4 v = {stage_a[i][0] ^ 0x80808080u, stage_a[i][1] ^ 0x80808080u, stage_a[i][2] ^ 0x80808080u,
+                       stage_a[i][3] ^ 0x80808080u}; // uint8 code -> signed code - 128
+            *reinterpret_cast<u32x4 *>(sa + lds_chunk_offset(row, chunk_c)) = v;
+        }
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            const int row = (tid >> 2) + i * (NT / 4);
+            u32x4 v = {stage_b[i][0], stage_b[i][1], stage_b[i][2], stage_b[i][3]};
+            *reinterpret_cast<u32x4 *>(sb + lds_chunk_offset(row, chunk_c)) = v;
+        }
+    };
+
+    i32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    int32_t colsum[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) colsum[j] = 0;
+
+    const int ktiles = (g.K + BK - 1) / BK;
+    fetch(0);
+    commit(0);
+    __syncthreads();
+
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    for (int kt = 0; kt < ktiles; ++kt) {
+        const bool more = kt + 1 < ktiles;
+        if (more) fetch((kt + 1) * BK);
+        const uint8_t *sa = smem + (kt & 1) * STAGE_BYTES;
+        const uint8_t *sb = sa + BM * BK;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            i32x4 fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const i32x4 *>(
+                    sa + lds_chunk_offset(wave_m * WTM + i * 32 + frag_row, ks * 2 + frag_half));
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                fb[j] = *reinterpret_cast<const i32x4 *>(
+                    sb + lds_chunk_offset(wave_n * WTN + j * 32 + frag_row, ks * 2 + frag_half));
+#pragma unroll
+                for (int d = 0; d < 4; ++d) colsum[j] = __builtin_amdgcn_sdot4(fb[j][d], 0x01010101, colsum[j], false);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) commit((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: zero-point correction, bias, rescale, clamp; bytes staged in LDS
+    // (the last __syncthreads above guarantees nobody still reads the operand tiles)
+    uint8_t *so = smem;
+    bool fast_ok = g.small_acc != 0;
+    int32_t corr[TN];
+    RescaleParams rp[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wave_n * WTN + j * 32 + frag_row;
+        int32_t cs = colsum[j] + __shfl_xor(colsum[j], 32);
+        if (B_MODE == B_INT4) cs >>= 4;
+        int32_t b = 0, mu = 0, sf = 0;
+        if (n < g.N) {
+            b = g.bias ? g.bias[n] : 0;
+            mu = g.mult[n];
+            sf = g.shift[n];
+        }
+        corr[j] = b + (128 - g.z_a) * cs;
+        rp[j] = make_rescale(mu, sf);
+        fast_ok = fast_ok && sf >= 0 && b > -(1 << 28) && b < (1 << 28);
+    }
+    const bool fast = __all(fast_ok);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int32_t a = acc[i][j][r];
+                if (B_MODE == B_INT4) a >>= 4; // weights were staged times 16; exact
+                a += corr[j];
+                const int32_t v = fast ? rescale_fast(a, rp[j]) : rescale_general(a, rp[j]);
+                const int32_t y = clamp_i32(g.lo_rel, g.hi_rel, v) + g.z_out;
+                const int row = wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+                const int col = wave_n * WTN + j * 32 + frag_row;
+                so[row * OUT_PITCH + col] = (uint8_t)y;
+            }
+    __syncthreads();
+
+    constexpr int ROW_CHUNKS = BN / 16;
+    for (int q = tid; q < BM * ROW_CHUNKS; q += NT) {
+        const int row = q / ROW_CHUNKS, cc = q % ROW_CHUNKS;
+        const int64_t m = m0 + row;
+        const int n = n0 + cc * 16;
+        if (m >= g.M || n >= g.N) continue;
+        uint8_t *dst = g.C + m * g.ldc + n;
+        const uint8_t *src = so + row * OUT_PITCH + cc * 16;
+        if (g.c_vec16 && n + 16 <= g.N) {
+            *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
+        } else {
+            for (int e = 0; e < 16 && n + e < g.N; ++e) dst[e] = src[e];
+        }
+    }
+}
+
+} // namespace qnn

@@ -1,0 +1,139 @@
+// Entry points of the dense quantized layers: qnn_qgemm and qnn_qconv2d both run the
+// implicit-GEMM MFMA kernel of igemm.h; this file validates arguments, picks the tile
+// configuration and the staging vector width, and launches.
+#include "igemm.h"
+
+namespace qnn {
+
+static uint32_t magic_for(uint32_t d) { return d <= 1 ? 0u : (uint32_t)(((1ull << 32) + d - 1) / d); }
+
+static bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+template <int BM, int BN, int WM, int WN, int A_MODE, int B_MODE, int VEC>
+static void launch_one(const IgemmArgs &g, hipStream_t s)
+{
+    const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+    hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, A_MODE, B_MODE, VEC>), dim3((unsigned)tiles), dim3(WM * WN * 64), 0,
+                       s, g);
+}
+
+template <int BM, int BN, int WM, int WN, int A_MODE>
+static void launch_tile(const IgemmArgs &g, int b_mode, int vec, hipStream_t s)
+{
+    if (b_mode == B_INT8) {
+        if (vec == 16) launch_one<BM, BN, WM, WN, A_MODE, B_INT8, 16>(g, s);
+        else if (vec == 8) launch_one<BM, BN, WM, WN, A_MODE, B_INT8, 8>(g, s);
+        else launch_one<BM, BN, WM, WN, A_MODE, B_INT8, 1>(g, s);
+    } else if (b_mode == B_INT4) {
+        if (vec == 16) launch_one<BM, BN, WM, WN, A_MODE, B_INT4, 16>(g, s);
+        else if (vec == 8) launch_one<BM, BN, WM, WN, A_MODE, B_INT4, 8>(g, s);
+        else launch_one<BM, BN, WM, WN, A_MODE, B_INT4, 1>(g, s);
+    } else {
+        if constexpr (A_MODE == A_MATRIX) launch_one<BM, BN, WM, WN, A_MATRIX, B_INT8_ROWS, 1>(g, s);
+    }
+}
+
+// Shared back end.  `vec` is the widest staging vector (in k elements) that the alignment
+// of A, B and K allows.
+static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s)
+{
+    const int64_t max_tiles = 0x7fffffff;
+    g.small_acc = g.K <= 16384;
+    g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
+    const bool small = g.N <= 64 || g.M <= 64;
+    const int64_t bm = small ? 64 : 128, bn = small ? 64 : 128;
+    if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return QNN_EINVAL;
+    if (small) {
+        if (a_mode == A_MATRIX) launch_tile<64, 64, 2, 2, A_MATRIX>(g, b_mode, vec, s);
+        else launch_tile<64, 64, 2, 2, A_CONV>(g, b_mode, vec, s);
+    } else {
+        if (a_mode == A_MATRIX) launch_tile<128, 128, 2, 2, A_MATRIX>(g, b_mode, vec, s);
+        else launch_tile<128, 128, 2, 2, A_CONV>(g, b_mode, vec, s);
+    }
+    return launch_status(hipGetLastError());
+}
+
+static int pick_vec(int64_t k_like, std::initializer_list<const void *> ptrs, std::initializer_list<int64_t> pitches,
+                    int weight_bits)
+{
+    // candidate widths in elements; a 4-bit element is half a byte
+    for (int vec : {16, 8}) {
+        const int64_t a_bytes = vec;                                  // activations: 1 byte per element
+        const int64_t b_bytes = weight_bits == 4 ? vec / 2 : vec;     // weights
+        bool ok = (k_like % vec) == 0;
+        int idx = 0;
+        for (const void *p : ptrs) ok = ok && aligned_to(p, idx++ == 0 ? a_bytes : b_bytes);
+        for (int64_t pitch : pitches) ok = ok && (pitch % vec) == 0;
+        if (ok) return vec;
+    }
+    return 1;
+}
+
+} // namespace qnn
+
+using namespace qnn;
+
+extern "C" {
+
+qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
+                     int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
+                     const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
+                     void *stream)
+{
+    if (!A || !B || !mult || !shift || !C) return QNN_EINVAL;
+    if (M <= 0 || N <= 0 || K <= 0 || K > 65536 || N > 0x7fffffff || lda < K || ldc < N) return QNN_EINVAL;
+    if (z_a < 0 || z_a > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
+    if (weight_bits != 8 && weight_bits != 4) return QNN_EINVAL;
+    if (b_layout != QNN_B_COLUMNS_CONTIGUOUS && b_layout != QNN_B_ROWS_CONTIGUOUS) return QNN_EINVAL;
+    if (b_layout == QNN_B_COLUMNS_CONTIGUOUS ? ldb < K : ldb < N) return QNN_EINVAL;
+    if (weight_bits == 4 && (b_layout != QNN_B_COLUMNS_CONTIGUOUS || (K % 2) || (ldb % 2))) return QNN_EINVAL;
+
+    IgemmArgs g = {};
+    g.A = A, g.lda = lda;
+    g.B = static_cast<const uint8_t *>(B), g.ldb = ldb;
+    g.M = M, g.N = (int32_t)N, g.K = (int32_t)K, g.z_a = z_a;
+    g.bias = bias, g.mult = mult, g.shift = shift;
+    g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
+    g.C = C, g.ldc = ldc;
+    int b_mode = weight_bits == 4 ? B_INT4 : (b_layout == QNN_B_ROWS_CONTIGUOUS ? B_INT8_ROWS : B_INT8);
+    int vec = 1;
+    if (b_mode != B_INT8_ROWS) vec = pick_vec(K, {A, B}, {lda, ldb}, weight_bits);
+    return run_igemm(g, A_MATRIX, b_mode, vec, as_stream(stream));
+}
+
+qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
+                       int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias,
+                       const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
+                       uint8_t *y, void *stream)
+{
+    if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
+    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0) return QNN_EINVAL;
+    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return QNN_EINVAL;
+    if (H + 2 * (int64_t)pad_h < kh || W + 2 * (int64_t)pad_w < kw) return QNN_EINVAL;
+    const int64_t K = (int64_t)kh * kw * Cin;
+    if (K > 65536 || z_x < 0 || z_x > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
+    if (weight_bits != 8 && weight_bits != 4) return QNN_EINVAL;
+    if (weight_bits == 4 && (Cin % 2)) return QNN_EINVAL;
+    const int Ho = (H + 2 * pad_h - kh) / stride_h + 1, Wo = (W + 2 * pad_w - kw) / stride_w + 1;
+
+    IgemmArgs g = {};
+    g.A = x;
+    g.H = H, g.W = W, g.Cin = Cin, g.Ho = Ho, g.Wo = Wo, g.kw = kw;
+    g.sh = stride_h, g.sw = stride_w, g.ph = pad_h, g.pw = pad_w;
+    g.magic_cin = magic_for((uint32_t)Cin), g.magic_kw = magic_for((uint32_t)kw);
+    g.B = static_cast<const uint8_t *>(w), g.ldb = K;
+    g.M = (int64_t)N * Ho * Wo, g.N = Cout, g.K = (int32_t)K, g.z_a = z_x;
+    g.bias = bias, g.mult = mult, g.shift = shift;
+    g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
+    g.C = y, g.ldc = Cout;
+    const int b_mode = weight_bits == 4 ? B_INT4 : B_INT8;
+    const bool pointwise = kh == 1 && kw == 1 && stride_h == 1 && stride_w == 1 && pad_h == 0 && pad_w == 0;
+    if (pointwise) { // a 1x1 convolution over NHWC is a plain matrix product
+        g.lda = Cin;
+        return run_igemm(g, A_MATRIX, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
+    }
+    // pieces must not straddle a tap: the vector width divides Cin
+    return run_igemm(g, A_CONV, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
+}
+
+} // extern "C"

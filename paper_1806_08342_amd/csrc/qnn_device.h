@@ -1,0 +1,76 @@
+// Shared device-side pieces of the gfx950 kernels: launch checking and the exact
+// fixed-point rescale that every epilogue uses.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/qnn.h"
+
+namespace qnn {
+
+// records the HIP error text for qnn_last_error() and maps it to QNN_ELAUNCH
+qnn_status launch_status(hipError_t e);
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline bool bad_out_range(int32_t z_out, int32_t act_min, int32_t act_max)
+{
+    return act_min < 0 || act_max > 255 || act_min > act_max || z_out < 0 || z_out > 255;
+}
+
+// Per-channel constants of the rescale, prepared once per lane and reused for
+// every accumulator of that channel.
+struct RescaleParams {
+    int32_t mult;
+    int32_t rshift;   // max(shift, 0)
+    int32_t lshift;   // max(-shift, 0)
+    int32_t half;     // 2^(rshift-1), 0 when rshift == 0
+    int32_t sgn_mask; // -1 when rshift > 0 else 0
+};
+
+__device__ __forceinline__ RescaleParams make_rescale(int32_t mult, int32_t shift)
+{
+    RescaleParams p;
+    p.mult = mult;
+    p.rshift = shift > 0 ? shift : 0;
+    p.lshift = shift < 0 ? -shift : 0;
+    p.half = p.rshift ? (1 << (p.rshift - 1)) : 0;
+    p.sgn_mask = p.rshift ? -1 : 0;
+    return p;
+}
+
+// General form: any int32 a, any mult, shift in [-31, 31].
+__device__ __forceinline__ int32_t rescale_general(int32_t a, const RescaleParams &p)
+{
+    if (p.lshift) {
+        int64_t t = (int64_t)a << p.lshift;
+        t = t > INT32_MAX ? INT32_MAX : t;
+        t = t < INT32_MIN ? INT32_MIN : t;
+        a = (int32_t)t;
+    }
+    // nearest(a*mult / 2^31), ties toward +inf: floor((a*mult + 2^30) / 2^31) in exact 64-bit
+    int64_t prod = (int64_t)a * (int64_t)p.mult + (int64_t(1) << 30);
+    int32_t h = (int32_t)(prod >> 31);
+    if (a == INT32_MIN && p.mult == INT32_MIN) h = INT32_MAX;
+    // nearest(h / 2^n), ties away from zero: (h + 2^(n-1) - [h < 0]) >> n, in 64 bits
+    int64_t t = (int64_t)h + (int64_t)p.half + (int64_t)((h >> 31) & p.sgn_mask);
+    return (int32_t)(t >> p.rshift);
+}
+
+// Fast form, valid when shift >= 0 and |a| < 2^30: then |h| <= |a| < 2^30 and
+// h + 2^(n-1) cannot leave int32, so the second stage runs in 32 bits.
+__device__ __forceinline__ int32_t rescale_fast(int32_t a, const RescaleParams &p)
+{
+    int64_t prod = (int64_t)a * (int64_t)p.mult + (int64_t(1) << 30);
+    int32_t h = (int32_t)(prod >> 31);
+    int32_t t = h + p.half + ((h >> 31) & p.sgn_mask);
+    return t >> p.rshift;
+}
+
+__device__ __forceinline__ int32_t clamp_i32(int32_t lo, int32_t hi, int32_t v)
+{
+    return v < lo ? lo : (v > hi ? hi : v);
+}
+
+} // namespace qnn
