@@ -70,8 +70,10 @@ def _edge_acc(rng, rows, ch):
     acc = rng.integers(-2 ** 20, 2 ** 20, (rows, ch)).astype(np.int64)
     flat = acc.reshape(-1)
     edges = [2 ** 31 - 1, -2 ** 31, -2 ** 31 + 1, 0, 1, -1, 2 ** 30, -2 ** 30, 2 ** 30 - 1, 12345678, -12345678]
-    flat[: len(edges)] = edges
-    flat[len(edges): 2 * len(edges)] = edges[::-1]
+    n1 = min(len(edges), flat.size)
+    flat[:n1] = edges[:n1]
+    n2 = max(0, min(len(edges), flat.size - n1))
+    flat[n1: n1 + n2] = edges[::-1][:n2]
     return acc.astype(np.int32)
 
 
@@ -84,6 +86,7 @@ def test_requantize_matches_oracle(rows, ch):
     mult[-1] = 2 ** 31 - 1
     shift = rng.integers(0, 32, ch).astype(np.int32)
     shift[: min(ch, 3)] = [0, 31, -3][: min(ch, 3)]
+    mult[-1] = 2 ** 31 - 1
     if ch > 8:
         shift[5:8] = [-31, -1, 1]
         mult[8] = 0
