@@ -1,0 +1,289 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized conv / GEMM hot path on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W
+
+Primary workload (the one the headline metric is quoted on): the quantized GEMM sweep of
+configuration 2 -- uint8 A with zero-point 128 times per-column int8 B, int32 accumulation,
+zero-point correction, per-column fixed-point rescale to uint8 -- over all 64 triples of
+{256,1024,4096,8192}^3 plus the skinny shapes M in {1..64}, N = K = 4096.  One step is one
+pass over all 71 products; `value` is effective int8 TOPS = 2*sum(MNK) / time with all
+operands resident in HBM.  The same run then times the conv stacks of configurations 3-5
+(images/s, per-layer roofline fractions) and the streaming kernels, and the CPU oracle on a
+bounded sample, and prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5033.0  # dense int8 MFMA, 256 CU x 2.4 GHz x 8192 ops/clk/CU
+PEAK_HBM_GBS = 8000.0
+
+
+def _device_uint8(torch, shape, seed):
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(seed)
+    return torch.randint(0, 256, shape, dtype=torch.uint8, device="cuda:0", generator=g)
+
+
+def _dev(torch, a):
+    import numpy as np
+
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+# ----------------------------------------------------------------------------- GEMM sweep
+
+def build_gemm_sweep(torch, qnn, workloads, synth):
+    full, skinny = workloads.gemm_sweep()
+    shapes = full + skinny
+    weights, acts, cases = {}, {}, []
+    for i, (M, N, K) in enumerate(shapes):
+        if (N, K) not in weights:
+            c = synth.gemm_case(1, N, K, workloads.seed_for(2, len(weights)), qnn, with_a=False)
+            weights[(N, K)] = dict(Bt=_dev(torch, c["Bt"]), mult=_dev(torch, c["mult"]), shift=_dev(torch, c["shift"]),
+                                   z_a=c["z_a"], z_out=c["z_out"])
+        if (M, K) not in acts:
+            acts[(M, K)] = _device_uint8(torch, (M, K), workloads.seed_for(2, 500 + len(acts)))
+        w = weights[(N, K)]
+        cases.append(dict(M=M, N=N, K=K, A=acts[(M, K)], w=w, C=torch.empty((M, N), dtype=torch.uint8, device="cuda:0"),
+                          plan=qnn.qgemm_plan(M, N, K), ops=2.0 * M * N * K))
+    return cases
+
+
+def run_gemm(qnn, c):
+    w = c["w"]
+    qnn.qgemm(c["A"], w["z_a"], w["Bt"], w["mult"], w["shift"], w["z_out"], 0, 255, out=c["C"])
+
+
+def time_gemm_sweep(torch, qnn, cases, steps, warmup):
+    for _ in range(warmup):
+        for c in cases:
+            run_gemm(qnn, c)
+    torch.cuda.synchronize()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in cases]
+          for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        for i, c in enumerate(cases):
+            ev[s][i][0].record()
+            run_gemm(qnn, c)
+            ev[s][i][1].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    per_case_ms = [sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)) / steps for i in range(len(cases))]
+    return elapsed, per_case_ms
+
+
+# ----------------------------------------------------------------------------- conv stacks
+
+def time_kernel(torch, fn, reps=5, warm=2):
+    for _ in range(warm):
+        fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps * 1e-3  # seconds per launch
+
+
+def time_stack(torch, qnn, workloads, synth, layers, batch, config_id, reps):
+    from workloads import shapes as shp
+
+    total_t = total_bound = 0.0
+    total_macs = 0
+    rows = []
+    for idx, l in enumerate(shp.unique_shapes(layers)):
+        seed = workloads.seed_for(config_id, idx)
+        if l.kind == "qadd":
+            n = batch * l.H * l.W * l.Cout
+            c = synth.qadd_case((1,), seed, qnn, act=l.act)
+            a = _device_uint8(torch, (n,), seed)
+            b = _device_uint8(torch, (n,), seed + 1)
+            y = torch.empty_like(a)
+            fn = lambda: qnn.qadd(a, c["z_a"], b, c["z_b"], c["params"], c["z_out"], c["act_min"], c["act_max"], out=y)
+        else:
+            in_range = (-2.0, 2.2) if l.Cin == 3 and l.kind == "conv" else (0.0, 6.0)
+            c = synth.conv_case(l, batch, seed, qnn, in_range=in_range, with_x=False)
+            x = _device_uint8(torch, (batch, l.H, l.W, l.Cin), seed)
+            w = _dev(torch, c.get("w_packed", c["w"]))
+            mult, shift, bias = _dev(torch, c["mult"]), _dev(torch, c["shift"]), _dev(torch, c["bias"])
+            y = torch.empty((batch, l.Ho, l.Wo, l.Cout), dtype=torch.uint8, device="cuda:0")
+            if l.kind == "dw":
+                fn = lambda: qnn.qdwconv2d(x, c["z_x"], w, c["stride"], c["pad"], mult, shift, c["z_out"],
+                                           c["act_min"], c["act_max"], bias=bias, out=y)
+            else:
+                fn = lambda: qnn.qconv2d(x, c["z_x"], w, c["stride"], c["pad"], mult, shift, c["z_out"],
+                                         c["act_min"], c["act_max"], bias=bias, weight_bits=l.weight_bits, out=y)
+        t = time_kernel(torch, fn, reps=reps)
+        macs, nbytes = l.macs(batch), l.bytes(batch)
+        t_mfma, t_hbm = 2.0 * macs / (PEAK_INT8_TOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
+        bound = max(t_mfma, t_hbm)
+        rows.append(dict(layer=l.name, kind=l.kind, count=l.count, us=round(t * 1e6, 2), tops=round(2e-12 * macs / t, 2),
+                         gbs=round(nbytes / t * 1e-9, 1), bound="mfma" if t_mfma > t_hbm else "hbm",
+                         frac=round(bound / t, 3)))
+        total_t += t * l.count
+        total_bound += bound * l.count
+        total_macs += macs * l.count
+        del fn
+    return dict(batch=batch, images_per_s=round(batch / total_t, 1), ms=round(total_t * 1e3, 4),
+                tops=round(2e-12 * total_macs / total_t, 2), frac_of_sum_of_bounds=round(total_bound / total_t, 3),
+                layers=rows)
+
+
+def time_streaming(torch, qnn):
+    """quantize / dequantize / requantize / qadd on configuration 5's 256x224x224x3 tensor size"""
+    n = 256 * 224 * 224 * 3
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(5)
+    x = torch.randn(n, dtype=torch.float32, device="cuda:0", generator=g)
+    s, z = qnn.choose_qparams(float(x.min()), float(x.max()))
+    q = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    back = torch.empty_like(x)
+    out = {}
+    t = time_kernel(torch, lambda: qnn.quantize(x, s, z, out=q), reps=10)
+    out["quantize"] = dict(us=round(t * 1e6, 1), gbs=round(5.0 * n / t * 1e-9, 1), frac=round(5.0 * n / t / 8e12, 3))
+    t = time_kernel(torch, lambda: qnn.dequantize(q, s, z, out=back), reps=10)
+    out["dequantize"] = dict(us=round(t * 1e6, 1), gbs=round(5.0 * n / t * 1e-9, 1), frac=round(5.0 * n / t / 8e12, 3))
+    rows, ch = n // 256, 256
+    acc = torch.randint(-200000, 200000, (rows, ch), dtype=torch.int32, device="cuda:0", generator=g)
+    mult, shift = qnn.quantize_multipliers([0.0007 * (1 + 0.01 * i) for i in range(ch)])
+    mult, shift = _dev(torch, mult), _dev(torch, shift)
+    y = torch.empty((rows, ch), dtype=torch.uint8, device="cuda:0")
+    t = time_kernel(torch, lambda: qnn.requantize(acc, mult, shift, True, 128, 0, 255, out=y), reps=10)
+    out["requantize"] = dict(us=round(t * 1e6, 1), gbs=round(5.0 * n / t * 1e-9, 1), frac=round(5.0 * n / t / 8e12, 3))
+    b = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda:0", generator=g)
+    p = qnn.qadd_params(0.02, 0.031, 0.04)
+    t = time_kernel(torch, lambda: qnn.qadd(q, 120, b, 131, p, 0, 0, 255, out=y.view(-1)), reps=10)
+    out["qadd"] = dict(us=round(t * 1e6, 1), gbs=round(3.0 * n / t * 1e-9, 1), frac=round(3.0 * n / t / 8e12, 3))
+    return out
+
+
+# ----------------------------------------------------------------------------- CPU baseline
+
+def cpu_baseline():
+    """The oracle as it stands, on the host cores, on a bounded slice of the sweep's
+    4096 x 4096 x 4096 product (rows chosen for roughly 15 s of CPU work)."""
+    import numpy as np
+
+    import oracle
+    import workloads
+    from workloads import synth
+
+    N = K = 4096
+    c = synth.gemm_case(256, N, K, workloads.seed_for(2, 999), oracle)
+    t0 = time.perf_counter()
+    oracle.qgemm(c["A"], c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
+    dt = time.perf_counter() - t0
+    rate = 256.0 * N * K / dt
+    rows = int(min(4096, max(256, (15.0 * rate / (N * K)) // 256 * 256)))
+    A = np.random.Generator(np.random.PCG64(workloads.seed_for(2, 998))).integers(0, 256, (rows, K), dtype=np.uint8)
+    t0 = time.perf_counter()
+    oracle.qgemm(A, c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
+    dt = time.perf_counter() - t0
+    return dict(value=round(2e-12 * rows * N * K / dt, 5), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
+                sample=f"first {rows} rows of the 4096x4096x4096 quantized GEMM of the sweep ({dt:.1f} s)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-secondary", action="store_true", help="skip the conv stacks and streaming kernels")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", action="store_true", help="include per-layer rows of the conv stacks in the JSON")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every box has one; the path needs no exchange between GPUs); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_1806_08342_amd as qnn
+    import workloads
+    from workloads import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    qnn.load_library()  # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+
+    cases = build_gemm_sweep(torch, qnn, workloads, synth)
+    elapsed, per_case_ms = time_gemm_sweep(torch, qnn, cases, args.steps, args.warmup)
+    ops_per_step = sum(c["ops"] for c in cases)
+    value = ops_per_step * args.steps / elapsed * 1e-12
+
+    # dominant kernel = the tile configuration with the largest share of the step
+    by_plan = {}
+    for c, ms in zip(cases, per_case_ms):
+        d = by_plan.setdefault(c["plan"], dict(ms=0.0, ops=0.0, launches=0))
+        d["ms"] += ms
+        d["ops"] += c["ops"]
+        d["launches"] += 1
+    dom = max(by_plan, key=lambda k: by_plan[k]["ms"])
+    d = by_plan[dom]
+    achieved = d["ops"] / (d["ms"] * 1e-3) * 1e-12
+    roofline = dict(bound="mfma", kernel=f"igemm_kernel<{dom}> (int8 32x32x32 MFMA)", achieved=round(achieved, 1),
+                    peak=PEAK_INT8_TOPS, unit="TOP/s", frac=round(achieved / PEAK_INT8_TOPS, 4),
+                    launches_per_step=d["launches"], avg_launch_us=round(d["ms"] * 1e3 / d["launches"], 2),
+                    ops_per_launch=d["ops"] / d["launches"], traffic=None)
+    big = {f"{c['M']}x{c['N']}x{c['K']}": round(c["ops"] / (ms * 1e-3) * 1e-12, 1)
+           for c, ms in zip(cases, per_case_ms) if (c["M"], c["N"], c["K"]) in
+           [(1024,) * 3, (4096,) * 3, (8192,) * 3, (256, 8192, 8192), (64, 4096, 4096), (1, 4096, 4096)]}
+
+    result = {
+        "metric": "effective int8 TOPS (quantized GEMM sweep, uint8 x int8 -> int32 -> uint8)",
+        "value": round(value, 2),
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8 (uint8 activations, int8 weights, int32 accumulate)",
+        "data": "synthetic (seeded; shapes and value distributions of BASELINE configuration 2)",
+        "config": {"workload": "config2 quantized GEMM sweep: 64 triples of {256,1024,4096,8192}^3 + M in {1..64} x 4096 x 4096",
+                   "gemms_per_step": len(cases), "ops_per_step": ops_per_step},
+        "frac_of_int8_peak": round(value / PEAK_INT8_TOPS, 4),
+        "roofline": roofline,
+        "tops_by_shape": big,
+    }
+    if not args.no_secondary:
+        sec = {}
+        sec["streaming"] = time_streaming(torch, qnn)
+        sec["mobilenet_v1_b64"] = time_stack(torch, qnn, workloads, synth, workloads.mobilenet_v1(), 64, 3, 5)
+        sec["mobilenet_v1_b1"] = time_stack(torch, qnn, workloads, synth, workloads.mobilenet_v1(), 1, 3, 5)
+        sec["resnet50_b256"] = time_stack(torch, qnn, workloads, synth, workloads.resnet50(), 256, 4, 3)
+        sec["mobilenet_v2_int4_b32"] = time_stack(torch, qnn, workloads, synth, workloads.mobilenet_v2(4), 32, 5, 5)
+        layer_dump = {}
+        for k, v in sec.items():
+            if isinstance(v, dict) and "layers" in v:
+                layer_dump[k] = v.pop("layers")
+        result["secondary"] = sec
+        if args.layers:
+            result["layers"] = layer_dump
+        else:
+            os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+            with open(os.path.join(ROOT, "gpurun_out", "bench_layers.json"), "w") as f:
+                json.dump(layer_dump, f, indent=1)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

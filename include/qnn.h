@@ -105,6 +105,11 @@ qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, 
                      const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
                      void *stream);
 
+/* Name of the tile configuration ("<BM>x<BN>") that qnn_qgemm and the convolution entry points
+ * select for an M x N x K product (M = output pixels, N = output channels, K = kh*kw*Cin);
+ * for logging and profiling.  HOST string owned by the library; "" for non-positive sizes. */
+const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K);
+
 /* Transpose a K x N int8 matrix with contiguous rows (src[k*ld_src + n]) into the
  * columns-contiguous layout (dst[n*ld_dst + k]) that qnn_qgemm runs fastest on.
  * src, dst: DEVICE int8; ld_src >= N, ld_dst >= K. */

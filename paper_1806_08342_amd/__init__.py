@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     qconv2d,
     qdwconv2d,
     qgemm,
+    qgemm_plan,
     quantize,
     quantize_multiplier,
     quantize_multipliers,
@@ -28,6 +29,6 @@ from .binding import (  # noqa: F401
 
 __all__ = [
     "QnnError", "act_range", "choose_qparams", "dequantize", "library_path", "load_library", "pack_b", "pack_int4",
-    "qadd", "qadd_params", "qconv2d", "qdwconv2d", "qgemm", "quantize", "quantize_multiplier",
+    "qadd", "qadd_params", "qconv2d", "qdwconv2d", "qgemm", "qgemm_plan", "quantize", "quantize_multiplier",
     "quantize_multipliers", "quantize_weights", "requantize",
 ]

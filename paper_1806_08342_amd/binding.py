@@ -19,7 +19,7 @@ STATUS = {0: "QNN_OK", 1: "QNN_EINVAL", 2: "QNN_EUNSUPPORTED", 3: "QNN_ELAUNCH"}
 B_COLUMNS_CONTIGUOUS, B_ROWS_CONTIGUOUS = 0, 1
 
 EXPORTS = [
-    "qnn_last_error", "qnn_version", "qnn_quantize", "qnn_dequantize", "qnn_requantize", "qnn_qgemm", "qnn_pack_b",
+    "qnn_last_error", "qnn_version", "qnn_qgemm_plan", "qnn_quantize", "qnn_dequantize", "qnn_requantize", "qnn_qgemm", "qnn_pack_b",
     "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
     "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4",
 ]
@@ -47,6 +47,8 @@ def load_library():
     lib = C.CDLL(_LIB_PATH)
     lib.qnn_last_error.restype = C.c_char_p
     lib.qnn_version.restype = C.c_char_p
+    lib.qnn_qgemm_plan.restype = C.c_char_p
+    lib.qnn_qgemm_plan.argtypes = [C.c_int64, C.c_int64, C.c_int64]
     vp, i32, i64, sz, f32, f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float, C.c_double
     ci = C.c_int
     sigs = {
@@ -149,6 +151,11 @@ def pack_int4(v):
     out = np.empty(v.shape[:-1] + (v.shape[-1] // 2,), dtype=np.uint8)
     _check("qnn_pack_int4", load_library().qnn_pack_int4(v.ctypes.data, v.size, out.ctypes.data))
     return out
+
+
+def qgemm_plan(M, N, K):
+    """Tile configuration the dense kernels pick for an M x N x K product."""
+    return load_library().qnn_qgemm_plan(int(M), int(N), int(K)).decode()
 
 
 # ---------------------------------------------------------------- device kernels

@@ -33,6 +33,14 @@ static void launch_tile(const IgemmArgs &g, int b_mode, int vec, hipStream_t s)
     }
 }
 
+enum TileConfig { TILE_64x64 = 0, TILE_128x128 = 1 };
+
+static TileConfig choose_tile(int64_t M, int64_t N, int64_t K)
+{
+    (void)K;
+    return (N <= 64 || M <= 64) ? TILE_64x64 : TILE_128x128;
+}
+
 // Shared back end.  `vec` is the widest staging vector (in k elements) that the alignment
 // of A, B and K allows.
 static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s)
@@ -40,10 +48,10 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
     const int64_t max_tiles = 0x7fffffff;
     g.small_acc = g.K <= 16384;
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
-    const bool small = g.N <= 64 || g.M <= 64;
-    const int64_t bm = small ? 64 : 128, bn = small ? 64 : 128;
+    const TileConfig cfg = choose_tile(g.M, g.N, g.K);
+    const int64_t bm = cfg == TILE_64x64 ? 64 : 128, bn = bm;
     if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return QNN_EINVAL;
-    if (small) {
+    if (cfg == TILE_64x64) {
         if (a_mode == A_MATRIX) launch_tile<64, 64, 2, 2, A_MATRIX>(g, b_mode, vec, s);
         else launch_tile<64, 64, 2, 2, A_CONV>(g, b_mode, vec, s);
     } else {
@@ -52,6 +60,8 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
     }
     return launch_status(hipGetLastError());
 }
+
+static const char *tile_name(TileConfig c) { return c == TILE_64x64 ? "64x64" : "128x128"; }
 
 static int pick_vec(int64_t k_like, std::initializer_list<const void *> ptrs, std::initializer_list<int64_t> pitches,
                     int weight_bits)
@@ -74,6 +84,12 @@ static int pick_vec(int64_t k_like, std::initializer_list<const void *> ptrs, st
 using namespace qnn;
 
 extern "C" {
+
+const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return "";
+    return tile_name(choose_tile(M, N, K));
+}
 
 qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
                      int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,

@@ -30,7 +30,7 @@ def _act_kind(act):
     return {"none": 0, "relu": 1, "relu6": 2}[act]
 
 
-def conv_case(layer, batch, seed, h, in_range=(0.0, 6.0)):
+def conv_case(layer, batch, seed, h, in_range=(0.0, 6.0), with_x=True):
     """Inputs of one quantized conv / depthwise layer (configurations 1 and 3-5).
 
     Activations uniform uint8; weights uniform int8 in [-127,127] (or 4-bit in [-7,7], nibble
@@ -41,7 +41,6 @@ def conv_case(layer, batch, seed, h, in_range=(0.0, 6.0)):
     rng = _rng(seed)
     dw = layer.kind == "dw"
     s_x, z_x = h.choose_qparams(*in_range)
-    x = rng.integers(0, 256, (batch, layer.H, layer.W, layer.Cin), dtype=np.uint8)
     bits = layer.weight_bits
     wmax = 127 if bits == 8 else 7
     if dw:
@@ -65,6 +64,9 @@ def conv_case(layer, batch, seed, h, in_range=(0.0, 6.0)):
     s_o, z_o = h.choose_qparams(*out_range)
     mult, shift = h.quantize_multipliers(s_x * delta_c / s_o)
     lo, hi = h.act_range(_act_kind(layer.act), s_o, z_o)
+    # the activations are drawn last so that with_x=False (device-side generation in the
+    # benchmark) leaves every parameter above unchanged
+    x = rng.integers(0, 256, (batch, layer.H, layer.W, layer.Cin), dtype=np.uint8) if with_x else None
     case = dict(kind=layer.kind, x=x, z_x=z_x, s_x=s_x, w=w, bias=bias, mult=mult, shift=shift, z_out=z_o, s_out=s_o,
                 act_min=lo, act_max=hi, stride=(layer.stride, layer.stride), pad=(layer.pad, layer.pad),
                 weight_bits=bits, delta_c=delta_c)
@@ -89,13 +91,12 @@ def single_conv_case(layer, seed, h):
                 act_min=lo, act_max=hi, stride=(1, 1), pad=(1, 1), weight_bits=8, delta_c=delta_c)
 
 
-def gemm_case(M, N, K, seed, h, weight_bits=8):
+def gemm_case(M, N, K, seed, h, weight_bits=8, with_a=True):
     """Configuration 2: A uniform uint8 with z_a = 128, s_a = 0.02; B from fp32 N(0, 0.05) quantized
     per column symmetric; output scale 8 sigma / 255 with z_out = 128 so results spread over uint8.
     B is returned with each column contiguous ([N, K])."""
     rng = _rng(seed)
     s_a, z_a = 0.02, 128
-    A = rng.integers(0, 256, (M, K), dtype=np.uint8)
     if weight_bits == 8:
         # N(0, 0.05) quantized with Delta_c = max|b_c| / 127: drawn in one step as the rounded,
         # clipped normal in code units (the max of K normals is about 3.5-4.3 sigma)
@@ -108,6 +109,7 @@ def gemm_case(M, N, K, seed, h, weight_bits=8):
     sigma_y = s_a * _SIGMA_U8 * 0.05 * math.sqrt(K)
     s_o, z_o = 8.0 * sigma_y / 255.0, 128
     mult, shift = h.quantize_multipliers(s_a * delta_c.astype(np.float64) / s_o)
+    A = rng.integers(0, 256, (M, K), dtype=np.uint8) if with_a else None
     case = dict(A=A, z_a=z_a, Bt=Bt, mult=mult, shift=shift, z_out=z_o, act_min=0, act_max=255, bias=None,
                 weight_bits=weight_bits)
     if weight_bits == 4:
