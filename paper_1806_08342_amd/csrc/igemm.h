@@ -173,6 +173,92 @@ __device__ __forceinline__ void load_b_chunk(const IgemmArgs &g, int n, int kc, 
     }
 }
 
+
+// Epilogue shared by the dense kernels: zero-point correction (eq. 5-6), bias, fixed-point
+// rescale, clamp; the uint8 tile is staged in LDS so that the global stores are 16-byte
+// rows.  `so` must not be read by anyone else any more (callers synchronise before).
+template <int BM, int BN, int WM, int WN, bool WEIGHTS_X16, int TM, int TN>
+__device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (&acc)[TM][TN], int32_t (&colsum)[TN],
+                                                    uint8_t *so, int64_t m0, int n0)
+{
+    constexpr int NT = WM * WN * 64;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int OUT_PITCH = BN + 16;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wave_m = wave / WN, wave_n = wave % WN;
+    const int frag_row = lane & 31, frag_half = lane >> 5;
+    bool fast_ok = g.small_acc != 0;
+    int32_t corr[TN];
+    RescaleParams rp[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wave_n * WTN + j * 32 + frag_row;
+        int32_t cs = colsum[j] + __shfl_xor(colsum[j], 32);
+        if (WEIGHTS_X16) cs >>= 4;
+        int32_t b = 0, mu = 0, sf = 0;
+        if (n < g.N) {
+            b = g.bias ? g.bias[n] : 0;
+            mu = g.mult[n];
+            sf = g.shift[n];
+        }
+        corr[j] = b + (128 - g.z_a) * cs;
+        rp[j] = make_rescale(mu, sf);
+        fast_ok = fast_ok && sf >= 0 && b > -(1 << 28) && b < (1 << 28);
+    }
+    const bool fast = __all(fast_ok);
+    // one accumulator -> one byte in the LDS output tile
+    auto finish = [&](int i, int j, int r, auto rescale) {
+        int32_t a = acc[i][j][r];
+        if (WEIGHTS_X16) a >>= 4; // weights were staged times 16; exact
+        a += corr[j];
+        const int32_t y = clamp_i32(g.lo_rel, g.hi_rel, rescale(a, rp[j])) + g.z_out;
+        const int row = wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+        const int col = wave_n * WTN + j * 32 + frag_row;
+        so[row * OUT_PITCH + col] = (uint8_t)y;
+    };
+    if (fast) {
+#pragma clang loop unroll(full)
+        for (int i = 0; i < TM; ++i)
+#pragma clang loop unroll(full)
+            for (int j = 0; j < TN; ++j)
+#pragma clang loop unroll(full)
+                for (int r = 0; r < 16; ++r)
+                    finish(i, j, r, [](int32_t a, const RescaleParams &p) { return rescale_fast(a, p); });
+    } else {
+#pragma clang loop unroll(full)
+        for (int i = 0; i < TM; ++i)
+#pragma clang loop unroll(full)
+            for (int j = 0; j < TN; ++j)
+#pragma clang loop unroll(full)
+                for (int r = 0; r < 16; ++r)
+                    finish(i, j, r, [](int32_t a, const RescaleParams &p) { return rescale_general(a, p); });
+    }
+    __syncthreads();
+
+    constexpr int ROW_CHUNKS = BN / 16;
+    for (int q = tid; q < BM * ROW_CHUNKS; q += NT) {
+        const int row = q / ROW_CHUNKS, cc = q % ROW_CHUNKS;
+        const int64_t m = m0 + row;
+        const int n = n0 + cc * 16;
+        if (m >= g.M || n >= g.N) continue;
+        uint8_t *dst = g.C + m * g.ldc + n;
+        const uint8_t *src = so + row * OUT_PITCH + cc * 16;
+        if (g.c_vec16 && n + 16 <= g.N) {
+            *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
+        } else {
+            for (int e = 0; e < 16 && n + e < g.N; ++e) dst[e] = src[e];
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, bool WEIGHTS_X16, int TM, int TN>
+__device__ __forceinline__ void igemm_epilogue(const IgemmArgs &g, i32x16 (&acc)[TM][TN], int32_t (&colsum)[TN],
+                                               uint8_t *so, int64_t m0, int n0)
+{
+    igemm_epilogue_impl<BM, BN, WM, WN, WEIGHTS_X16, TM, TN>(g, acc, colsum, so, m0, n0);
+}
+
 template <int BM, int BN, int WM, int WN, int A_MODE, int B_MODE, int VEC>
 __global__ void __launch_bounds__(WM *WN * 64) igemm_kernel(const IgemmArgs g)
 {
@@ -290,59 +376,8 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_kernel(const IgemmArgs g)
         __syncthreads();
     }
 
-    // ---- epilogue: zero-point correction, bias, rescale, clamp; bytes staged in LDS
-    // (the last __syncthreads above guarantees nobody still reads the operand tiles)
-    uint8_t *so = smem;
-    bool fast_ok = g.small_acc != 0;
-    int32_t corr[TN];
-    RescaleParams rp[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wave_n * WTN + j * 32 + frag_row;
-        int32_t cs = colsum[j] + __shfl_xor(colsum[j], 32);
-        if (B_MODE == B_INT4) cs >>= 4;
-        int32_t b = 0, mu = 0, sf = 0;
-        if (n < g.N) {
-            b = g.bias ? g.bias[n] : 0;
-            mu = g.mult[n];
-            sf = g.shift[n];
-        }
-        corr[j] = b + (128 - g.z_a) * cs;
-        rp[j] = make_rescale(mu, sf);
-        fast_ok = fast_ok && sf >= 0 && b > -(1 << 28) && b < (1 << 28);
-    }
-    const bool fast = __all(fast_ok);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int32_t a = acc[i][j][r];
-                if (B_MODE == B_INT4) a >>= 4; // weights were staged times 16; exact
-                a += corr[j];
-                const int32_t v = fast ? rescale_fast(a, rp[j]) : rescale_general(a, rp[j]);
-                const int32_t y = clamp_i32(g.lo_rel, g.hi_rel, v) + g.z_out;
-                const int row = wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
-                const int col = wave_n * WTN + j * 32 + frag_row;
-                so[row * OUT_PITCH + col] = (uint8_t)y;
-            }
-    __syncthreads();
-
-    constexpr int ROW_CHUNKS = BN / 16;
-    for (int q = tid; q < BM * ROW_CHUNKS; q += NT) {
-        const int row = q / ROW_CHUNKS, cc = q % ROW_CHUNKS;
-        const int64_t m = m0 + row;
-        const int n = n0 + cc * 16;
-        if (m >= g.M || n >= g.N) continue;
-        uint8_t *dst = g.C + m * g.ldc + n;
-        const uint8_t *src = so + row * OUT_PITCH + cc * 16;
-        if (g.c_vec16 && n + 16 <= g.N) {
-            *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
-        } else {
-            for (int e = 0; e < 16 && n + e < g.N; ++e) dst[e] = src[e];
-        }
-    }
+    // the last __syncthreads above guarantees nobody still reads the operand tiles
+    igemm_epilogue<BM, BN, WM, WN, B_MODE == B_INT4>(g, acc, colsum, smem, m0, n0);
 }
 
 } // namespace qnn

@@ -1,7 +1,10 @@
 // Entry points of the dense quantized layers: qnn_qgemm and qnn_qconv2d both run the
 // implicit-GEMM MFMA kernel of igemm.h; this file validates arguments, picks the tile
 // configuration and the staging vector width, and launches.
-#include "igemm.h"
+#include <cstdlib>
+#include <cstring>
+
+#include "igemm_dma.h"
 
 namespace qnn {
 
@@ -33,35 +36,76 @@ static void launch_tile(const IgemmArgs &g, int b_mode, int vec, hipStream_t s)
     }
 }
 
-enum TileConfig { TILE_64x64 = 0, TILE_128x128 = 1 };
+enum TileConfig { TILE_64x64 = 0, TILE_128x128 = 1, TILE_DMA_128x128 = 2, TILE_DMA_256x256 = 3, TILE_COUNT };
 
-static TileConfig choose_tile(int64_t M, int64_t N, int64_t K)
+static const char *const kTileNames[TILE_COUNT] = {"64x64", "128x128", "dma128x128", "dma256x256"};
+
+// Tile choice.  `dma_ok`: int8 weights with contiguous columns and 16-byte aligned chunks.
+static TileConfig choose_tile(int64_t M, int64_t N, int64_t K, bool dma_ok)
 {
+    if (const char *force = std::getenv("QNN_FORCE_TILE")) { // tuning aid: force one configuration
+        for (int t = 0; t < TILE_COUNT; ++t)
+            if (std::strcmp(force, kTileNames[t]) == 0 && (t < TILE_DMA_128x128 || dma_ok)) return (TileConfig)t;
+    }
     (void)K;
+    if (dma_ok) {
+        const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+        if (M >= 512 && N >= 512 && tiles256 >= 192) return TILE_DMA_256x256;
+        if (M >= 128 && N >= 128) return TILE_DMA_128x128;
+    }
     return (N <= 64 || M <= 64) ? TILE_64x64 : TILE_128x128;
+}
+
+template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE>
+static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s)
+{
+    constexpr int kLds = NSTAGE * (BM + BN) * 64;
+    auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE>;
+    static bool configured = false; // per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (g.N + BN - 1) / BN;
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const int per_xcd = (int)((tiles + 7) / 8);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(per_xcd * 8)), dim3(WM * WN * 64), kLds, s, g, tiles_m, tiles_n, per_xcd);
+    return hipGetLastError();
 }
 
 // Shared back end.  `vec` is the widest staging vector (in k elements) that the alignment
 // of A, B and K allows.
 static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s)
 {
-    const int64_t max_tiles = 0x7fffffff;
+    const int64_t max_tiles = 0x7ffffff;
     g.small_acc = g.K <= 16384;
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
-    const TileConfig cfg = choose_tile(g.M, g.N, g.K);
-    const int64_t bm = cfg == TILE_64x64 ? 64 : 128, bn = bm;
+    const bool dma_ok = b_mode == B_INT8 && vec == 16;
+    const TileConfig cfg = choose_tile(g.M, g.N, g.K, dma_ok);
+    const int64_t bm = cfg == TILE_64x64 ? 64 : (cfg == TILE_DMA_256x256 ? 256 : 128), bn = bm;
     if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return QNN_EINVAL;
-    if (cfg == TILE_64x64) {
+    switch (cfg) {
+    case TILE_64x64:
         if (a_mode == A_MATRIX) launch_tile<64, 64, 2, 2, A_MATRIX>(g, b_mode, vec, s);
         else launch_tile<64, 64, 2, 2, A_CONV>(g, b_mode, vec, s);
-    } else {
+        break;
+    case TILE_128x128:
         if (a_mode == A_MATRIX) launch_tile<128, 128, 2, 2, A_MATRIX>(g, b_mode, vec, s);
         else launch_tile<128, 128, 2, 2, A_CONV>(g, b_mode, vec, s);
+        break;
+    case TILE_DMA_128x128:
+        return launch_status(a_mode == A_MATRIX ? launch_dma<128, 128, 2, 2, A_MATRIX, 4>(g, s)
+                                                : launch_dma<128, 128, 2, 2, A_CONV, 4>(g, s));
+    case TILE_DMA_256x256:
+        return launch_status(a_mode == A_MATRIX ? launch_dma<256, 256, 2, 2, A_MATRIX, 4>(g, s)
+                                                : launch_dma<256, 256, 2, 2, A_CONV, 4>(g, s));
+    default:
+        return QNN_EINVAL;
     }
     return launch_status(hipGetLastError());
 }
-
-static const char *tile_name(TileConfig c) { return c == TILE_64x64 ? "64x64" : "128x128"; }
 
 static int pick_vec(int64_t k_like, std::initializer_list<const void *> ptrs, std::initializer_list<int64_t> pitches,
                     int weight_bits)
@@ -88,7 +132,8 @@ extern "C" {
 const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 0 || N <= 0 || K <= 0) return "";
-    return tile_name(choose_tile(M, N, K));
+    // reported for the aligned int8 case (what the benchmark shapes are)
+    return kTileNames[choose_tile(M, N, K, (K % 16) == 0)];
 }
 
 qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,

@@ -285,3 +285,53 @@ def test_qdwconv2d_matches_oracle(shape, batch):
         got = host(qnn.qdwconv2d(dev(c["x"]), z_x, dev(c["w"]), c["stride"], c["pad"], dev(c["mult"]), dev(c["shift"]),
                                  c["z_out"], c["act_min"], c["act_max"], bias=dev(c["bias"])))
         assert_same(got, want, f"dwconv {shape} batch {batch} z_x={z_x}")
+
+
+# ------------------------------------------------ pipelined (LDS-DMA) tile configurations
+
+@pytest.fixture
+def force_tile(monkeypatch):
+    def _set(name):
+        monkeypatch.setenv("QNN_FORCE_TILE", name)
+    return _set
+
+
+@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "128x128", "64x64"])
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (256, 256, 256), (300, 270, 208), (1000, 520, 1040), (17, 33, 16),
+                                   (515, 700, 80)])
+def test_qgemm_forced_tiles_match_oracle(force_tile, tile, M, N, K):
+    force_tile(tile)
+    rng = np.random.default_rng(1300 + M + N + K)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    bias, mult, shift = _gemm_params(rng, N, K)
+    for z_a in (77, 128):
+        want = oracle.qgemm(A, z_a, Bt, mult, shift, 128, 0, 255, bias=bias)
+        got = host(qnn.qgemm(dev(A), z_a, dev(Bt), dev(mult), dev(shift), 128, 0, 255, bias=dev(bias)))
+        assert_same(got, want, f"qgemm tile={tile} {M}x{N}x{K} z_a={z_a}")
+
+
+@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256"])
+@pytest.mark.parametrize("shape", [(14, 14, 64, 96, 3, 1, 1), (15, 13, 32, 160, 3, 2, 1), (9, 9, 48, 40, 5, 1, 2),
+                                   (16, 16, 128, 256, 1, 2, 0), (12, 12, 16, 300, 3, 1, 0)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_qconv2d_forced_dma_tiles_match_oracle(force_tile, tile, shape):
+    force_tile(tile)
+    H, W, Cin, Cout, k, s, p = shape
+    layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu")
+    c = synth.conv_case(layer, 3, 1400 + sum(shape), oracle)
+    for z_x in (c["z_x"], 255):
+        c["z_x"] = z_x
+        _run_conv(c, f"conv tile={tile} {shape} z_x={z_x}")
+
+
+def test_qgemm_default_plan_large_shape_sampled_rows():
+    # 4096 x 3072 x 512 selects the 256x256 pipelined tile by itself (192 tiles); compare whole rows
+    # at the top, in the middle and at the bottom of the matrix
+    M, N, K = 4096, 3072, 512
+    assert qnn.qgemm_plan(M, N, K) == "dma256x256"
+    c = synth.gemm_case(M, N, K, workloads.seed_for(2, 77), oracle)
+    got = host(qnn.qgemm(dev(c["A"]), c["z_a"], dev(c["Bt"]), dev(c["mult"]), dev(c["shift"]), c["z_out"], 0, 255))
+    rows = np.r_[0:64, 2000:2064, 4032:4096]
+    want = oracle.qgemm(c["A"][rows], c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
+    assert_same(got[rows], want, "qgemm 4096x3072x512 sampled rows")
