@@ -82,7 +82,7 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
     const int64_t max_tiles = 0x7ffffff;
     g.small_acc = g.K <= 16384;
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
-    const bool dma_ok = b_mode == B_INT8 && vec == 16;
+    const bool dma_ok = b_mode == B_INT8 && vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23);
     const TileConfig cfg = choose_tile(g.M, g.N, g.K, dma_ok);
     const int64_t bm = cfg == TILE_64x64 ? 64 : (cfg == TILE_DMA_256x256 ? 256 : 128), bn = bm;
     if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return QNN_EINVAL;
@@ -133,7 +133,7 @@ const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 0 || N <= 0 || K <= 0) return "";
     // reported for the aligned int8 case (what the benchmark shapes are)
-    return kTileNames[choose_tile(M, N, K, (K % 16) == 0)];
+    return kTileNames[choose_tile(M, N, K, (K % 64) == 0)];
 }
 
 qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,

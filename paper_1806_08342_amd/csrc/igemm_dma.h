@@ -11,11 +11,11 @@
 // fetches, for row p/4 of its segment, the logical chunk (p%4) ^ swizzle(row): the XOR
 // swizzle of the tile is applied on the global-address side.
 //
-// Requirements (checked by the dispatcher): every 16-byte chunk is 16-byte aligned
-// (K, pitches and base pointers multiples of 16; for convolutions Cin % 16 == 0).
-// Rows beyond M / columns beyond N are clamped to the last valid one (their results are
-// never stored); chunks beyond K read a constant chunk: zero for the weights, the code z_x
-// for out-of-image taps of the activations.
+// Requirements (checked by the dispatcher): every 16-byte chunk is 16-byte aligned (pitches
+// and base pointers multiples of 16; for convolutions Cin % 16 == 0), K % 64 == 0, and the
+// byte offsets inside one tile fit 32 bits.  Rows beyond M / columns beyond N are clamped to
+// the last valid one (their results are never stored); out-of-image taps of a convolution
+// read a constant chunk holding the code z_x.
 #pragma once
 
 #include "igemm.h"
@@ -83,14 +83,18 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
     const int n0 = (in_group / rows_here) * BN;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform: keeps LDS bases in SGPRs
     const int wave_m = wave / WN, wave_n = wave % WN;
 
     // ---- per-lane source description of the chunks this lane fetches at every K-step
+    // A_MATRIX and B: a wave-uniform base pointer plus a 32-bit per-lane offset that does not
+    // change from K-step to K-step (the K advance goes into the uniform part).
     const uint8_t *a_src[A_LOADS];
     int a_koff[A_LOADS], a_hi0[A_LOADS], a_wi0[A_LOADS];
-    const uint8_t *b_src[B_LOADS];
-    int b_koff[B_LOADS];
+    uint32_t a_lane_off[A_LOADS], b_lane_off[B_LOADS];
+    const uint8_t *const a_tile = g.A + m0 * g.lda;                 // A_MATRIX only
+    const uint8_t *const b_tile = g.B + (int64_t)n0 * g.ldb;
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
         const int row = (wave * A_LOADS + j) * 16 + (lane >> 2);
@@ -98,8 +102,10 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
         int64_t m = m0 + row;
         m = m < g.M ? m : g.M - 1;
         a_hi0[j] = a_wi0[j] = 0;
+        a_lane_off[j] = 0;
+        a_src[j] = nullptr;
         if constexpr (A_MODE == A_MATRIX) {
-            a_src[j] = g.A + m * g.lda;
+            a_lane_off[j] = (uint32_t)((m - m0) * g.lda) + (uint32_t)a_koff[j];
         } else {
             const int64_t img = m / ((int64_t)g.Ho * g.Wo);
             const int rem = (int)(m - img * ((int64_t)g.Ho * g.Wo));
@@ -112,25 +118,30 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
 #pragma unroll
     for (int j = 0; j < B_LOADS; ++j) {
         const int row = (wave * B_LOADS + j) * 16 + (lane >> 2);
-        b_koff[j] = (((lane & 3) ^ (row >> 1) ^ (row >> 3)) & 3) * 16;
+        const int b_koff = (((lane & 3) ^ (row >> 1) ^ (row >> 3)) & 3) * 16;
         int n = n0 + row;
         n = n < g.N ? n : g.N - 1;
-        b_src[j] = g.B + (int64_t)n * g.ldb;
+        b_lane_off[j] = (uint32_t)((int64_t)(n - n0) * g.ldb) + (uint32_t)b_koff;
     }
     const uint8_t *fill_a = &g_fill_table.v[g.z_a][0];
-    const uint8_t *fill_b = &g_fill_table.v[0][0];
+    const int ktiles = g.K / BK; // the dispatcher guarantees K % 64 == 0
 
-    auto issue_stage = [&](int kt) {
+    // load number `idx` (0 .. LOADS-1) of K-step kt: A segments first, then B segments.
+    // K-steps past the end re-fetch the last one into a buffer nobody reads any more
+    // (harmless, and it keeps the number of loads per K-step uniform for the vmcnt waits).
+    auto issue_load = [&](int kt, int idx) {
         uint8_t *stage = smem + (kt % NSTAGE) * STAGE_BYTES;
-        const int k0 = kt * BK;
-#pragma unroll
-        for (int j = 0; j < A_LOADS; ++j) {
-            const int k = k0 + a_koff[j];
-            const uint8_t *src = fill_a;
-            if (k < g.K) {
-                if constexpr (A_MODE == A_MATRIX) {
-                    src = a_src[j] + k;
-                } else {
+        const int kt_eff = kt < ktiles ? kt : ktiles - 1;
+        const int k0 = kt_eff * BK;
+        if (idx < A_LOADS) {
+            const int j = idx;
+            const uint8_t *src;
+            if constexpr (A_MODE == A_MATRIX) {
+                src = (a_tile + k0) + a_lane_off[j]; // K % 64 == 0: no tail
+            } else {
+                const int k = k0 + a_koff[j];
+                src = fill_a;
+                if (k < g.K) {
                     const uint32_t tap = fast_div((uint32_t)k, (uint32_t)g.Cin, g.magic_cin);
                     const int ci = k - (int)tap * g.Cin;
                     const uint32_t ta = fast_div(tap, (uint32_t)g.kw, g.magic_kw);
@@ -140,13 +151,14 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
                 }
             }
             dma16(src, stage + (wave * A_LOADS + j) * 1024);
+        } else {
+            const int j = idx - A_LOADS;
+            dma16((b_tile + k0) + b_lane_off[j], stage + BM * BK + (wave * B_LOADS + j) * 1024);
         }
+    };
+    auto issue_stage = [&](int kt) {
 #pragma unroll
-        for (int j = 0; j < B_LOADS; ++j) {
-            const int k = k0 + b_koff[j];
-            const uint8_t *src = k < g.K ? b_src[j] + k : fill_b;
-            dma16(src, stage + BM * BK + (wave * B_LOADS + j) * 1024);
-        }
+        for (int idx = 0; idx < LOADS; ++idx) issue_load(kt, idx);
     };
 
     i32x16 acc[TM][TN];
@@ -160,7 +172,6 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
 #pragma unroll
     for (int j = 0; j < TN; ++j) colsum[j] = 0;
 
-    const int ktiles = (g.K + BK - 1) / BK;
     const int frag_row = lane & 31, frag_half = lane >> 5;
     int a_off[TM][2], b_off[TN][2]; // LDS byte offsets of this lane's fragments within a stage
 #pragma unroll
@@ -171,51 +182,102 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
         for (int j = 0; j < TN; ++j)
             b_off[j][ks] = BM * BK + lds_chunk_offset(wave_n * WTN + j * 32 + frag_row, ks * 2 + frag_half);
     }
-    auto read_frags = [&](const uint8_t *stage, int ks, i32x4 (&fa)[TM], i32x4 (&fb)[TN]) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const i32x4 *>(stage + a_off[i][ks]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const i32x4 *>(stage + b_off[j][ks]);
+    // One "piece" p of a fragment set: pieces 0..TM-1 are the A fragments, TM..TM+TN-1 the B fragments
+    auto read_piece = [&](const uint8_t *stage, int ks, int p, i32x4 (&fa)[TM], i32x4 (&fb)[TN]) {
+        if (p < TM) fa[p] = *reinterpret_cast<const i32x4 *>(stage + a_off[p][ks]);
+        else fb[p - TM] = *reinterpret_cast<const i32x4 *>(stage + b_off[p - TM][ks]);
     };
-    auto mma = [&](i32x4 (&fa)[TM], i32x4 (&fb)[TN]) {
+    // weight column sums (only needed when z_a != 128): wave row wave_m covers the K sub-steps
+    // ks with ks % WM == wave_m; the partial sums are combined in the epilogue
+    const bool need_colsum = g.z_a != 128;
+    auto add_colsum = [&](i32x4 (&fb)[TN]) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int d = 0; d < 4; ++d) colsum[j] = __builtin_amdgcn_sdot4(fb[j][d], 0x01010101, colsum[j], false);
+    };
+    constexpr int PIECES = TM + TN, MMAS = TM * TN;
+    // MFMAs of one K sub-step with the LDS reads of the next fragment set (and optionally the
+    // DMA loads of a later stage) spread evenly between them, so that neither the LDS nor
+    // the texture-address queue sees a burst that would stall MFMA issue
+    auto mma_interleaved = [&](i32x4 (&fa)[TM], i32x4 (&fb)[TN], const uint8_t *next_stage, int next_ks,
+                               i32x4 (&na)[TM], i32x4 (&nb)[TN], bool do_read, int dma_kt) {
+        i32x4 xs[TM];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const i32x4 xs = fa[i] ^ (int32_t)0x80808080; // uint8 code -> signed (code - 128)
+        for (int i = 0; i < TM; ++i) xs[i] = fa[i] ^ (int32_t)0x80808080; // uint8 code -> signed (code - 128)
+        int piece = 0, load = 0;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xs, fb[j], acc[i][j], 0, 0, 0);
-        }
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xs[i], fb[j], acc[i][j], 0, 0, 0);
+                const int done = i * TN + j + 1;
+                // after every MMAS/PIECES MFMAs issue one fragment read (and one DMA load)
+                if (do_read && piece < PIECES && done * PIECES >= (piece + 1) * MMAS) {
+                    read_piece(next_stage, next_ks, piece, na, nb);
+                    ++piece;
+                }
+                if (dma_kt >= 0 && load < LOADS && done * LOADS >= (load + 1) * MMAS) {
+                    issue_load(dma_kt, load);
+                    ++load;
+                }
+            }
     };
 
     // ---- prologue: NSTAGE-1 stages in flight
 #pragma unroll
-    for (int s = 0; s < NSTAGE - 1; ++s)
-        if (s < ktiles) issue_stage(s);
+    for (int s = 0; s < NSTAGE - 1; ++s) issue_stage(s);
     // stage 0 has landed when at most the later stages' loads are outstanding
-    if (ktiles >= NSTAGE - 1) wait_vmcnt<(NSTAGE - 2) * LOADS>();
-    else wait_vmcnt<0>();
+    wait_vmcnt<(NSTAGE - 2) * LOADS>();
     block_barrier();
 
     i32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-    read_frags(smem, 0, fa0, fb0);
+#pragma unroll
+    for (int p = 0; p < PIECES; ++p) read_piece(smem, 0, p, fa0, fb0);
     for (int kt = 0; kt < ktiles; ++kt) {
         const uint8_t *stage = smem + (kt % NSTAGE) * STAGE_BYTES;
-        read_frags(stage, 1, fa1, fb1);
-        mma(fa0, fb0);
-        if (kt + 1 < ktiles) {
-            // stage kt+1 must have landed: only stage kt+2 .. may still be in flight
-            if (kt + NSTAGE - 1 <= ktiles) wait_vmcnt<(NSTAGE - 3) * LOADS>();
-            else wait_vmcnt<0>();
-            block_barrier(); // also: every wave is done reading stage kt-1, whose buffer is refilled next
-            if (kt + NSTAGE - 1 < ktiles) issue_stage(kt + NSTAGE - 1);
-            read_frags(smem + ((kt + 1) % NSTAGE) * STAGE_BYTES, 0, fa0, fb0);
+        // sub-step 0: MFMAs on (fa0, fb0) while (fa1, fb1) are read from the same stage
+        if (need_colsum && (0 % WM) == wave_m) add_colsum(fb0);
+        mma_interleaved(fa0, fb0, stage, 1, fa1, fb1, true, -1);
+#pragma unroll
+        for (int q = 0; q < PIECES; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, MMAS / PIECES, 0); // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);             // DS read
         }
-        mma(fa1, fb1);
+        // stage kt+1 must have landed: only the NSTAGE-3 stages issued after it may be in flight
+        // (every K-step issues exactly LOADS loads, real or fill, so the count is uniform)
+        wait_vmcnt<(NSTAGE - 3) * LOADS>();
+        block_barrier(); // also: every wave is done reading stage kt-1, whose buffer is refilled next
+        // sub-step 1: MFMAs on (fa1, fb1) while the first fragments of stage kt+1 are read and the
+        // loads of stage kt+NSTAGE-1 are issued (past the last stage: stale data, never used)
+        if (need_colsum && (1 % WM) == wave_m) add_colsum(fb1);
+        mma_interleaved(fa1, fb1, smem + ((kt + 1) % NSTAGE) * STAGE_BYTES, 0, fa0, fb0, true, kt + NSTAGE - 1);
+        if constexpr (LOADS == PIECES) {
+#pragma unroll
+            for (int q = 0; q < PIECES; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, MMAS / PIECES, 0); // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);             // DS read
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);             // VMEM read (LDS DMA)
+            }
+        }
     }
+    wait_vmcnt<0>(); // drain the fill loads of the last K-steps before the tile memory is reused
     block_barrier(); // all fragment reads done before the tile memory is reused for the output
+    if constexpr (WM > 1) {
+        if (need_colsum) { // every wave row holds the sums of its own K sub-steps only
+            int32_t *part = reinterpret_cast<int32_t *>(smem) + BM * (BN + 16) / 4; // past the output tile
+#pragma unroll
+            for (int j = 0; j < TN; ++j) part[(wave * TN + j) * 64 + lane] = colsum[j];
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                int32_t t = 0;
+#pragma unroll
+                for (int wm = 0; wm < WM; ++wm) t += part[((wm * WN + wave_n) * TN + j) * 64 + lane];
+                colsum[j] = t;
+            }
+        }
+    }
     igemm_epilogue<BM, BN, WM, WN, false>(g, acc, colsum, smem, m0, n0);
 }
 
