@@ -188,15 +188,16 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
     const int lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / WN, wave_n = wave % WN;
     const int frag_row = lane & 31, frag_half = lane >> 5;
-    bool fast_ok = g.small_acc != 0;
+    bool fast_ok = g.small_acc != 0, fused_ok = g.small_acc != 0;
     int32_t corr[TN];
     RescaleParams rp[TN];
+    FusedRescale fr[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int n = n0 + wave_n * WTN + j * 32 + frag_row;
         int32_t cs = colsum[j] + __shfl_xor(colsum[j], 32);
         if (WEIGHTS_X16) cs >>= 4;
-        int32_t b = 0, mu = 0, sf = 0;
+        int32_t b = 0, mu = 0, sf = 1;
         if (n < g.N) {
             b = g.bias ? g.bias[n] : 0;
             mu = g.mult[n];
@@ -204,20 +205,41 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
         }
         corr[j] = b + (128 - g.z_a) * cs;
         rp[j] = make_rescale(mu, sf);
-        fast_ok = fast_ok && sf >= 0 && b > -(1 << 28) && b < (1 << 28);
+        const bool small_bias = b > -(1 << 28) && b < (1 << 28);
+        fast_ok = fast_ok && sf >= 0 && small_bias;
+        fused_ok = fused_ok && sf >= 1 && sf <= 21 && mu >= 0 && small_bias;
+        const int nn = (sf >= 1 && sf <= 21) ? sf : 1;
+        fr[j].mult = mu;
+        fr[j].corr2 = 2 * corr[j];
+        fr[j].half_z = (1 << (nn - 1)) + (g.z_out << nn);
+        fr[j].n = nn;
     }
-    const bool fast = __all(fast_ok);
+    const bool fast = __all(fast_ok), fused = __all(fused_ok);
+    const int32_t act_lo = g.lo_rel + g.z_out, act_hi = g.hi_rel + g.z_out;
+    auto out_byte = [&](int i, int j, int r) -> uint8_t * {
+        const int row = wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+        const int col = wave_n * WTN + j * 32 + frag_row;
+        return so + row * OUT_PITCH + col;
+    };
     // one accumulator -> one byte in the LDS output tile
     auto finish = [&](int i, int j, int r, auto rescale) {
         int32_t a = acc[i][j][r];
         if (WEIGHTS_X16) a >>= 4; // weights were staged times 16; exact
         a += corr[j];
-        const int32_t y = clamp_i32(g.lo_rel, g.hi_rel, rescale(a, rp[j])) + g.z_out;
-        const int row = wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
-        const int col = wave_n * WTN + j * 32 + frag_row;
-        so[row * OUT_PITCH + col] = (uint8_t)y;
+        *out_byte(i, j, r) = (uint8_t)(clamp_i32(g.lo_rel, g.hi_rel, rescale(a, rp[j])) + g.z_out);
     };
-    if (fast) {
+    if (fused) {
+#pragma clang loop unroll(full)
+        for (int i = 0; i < TM; ++i)
+#pragma clang loop unroll(full)
+            for (int j = 0; j < TN; ++j)
+#pragma clang loop unroll(full)
+                for (int r = 0; r < 16; ++r) {
+                    int32_t a = acc[i][j][r];
+                    if (WEIGHTS_X16) a >>= 4;
+                    *out_byte(i, j, r) = (uint8_t)clamp_i32(act_lo, act_hi, rescale_fused(a, fr[j]));
+                }
+    } else if (fast) {
 #pragma clang loop unroll(full)
         for (int i = 0; i < TM; ++i)
 #pragma clang loop unroll(full)

@@ -99,8 +99,8 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
         return launch_status(a_mode == A_MATRIX ? launch_dma<128, 128, 2, 2, A_MATRIX, 4>(g, s)
                                                 : launch_dma<128, 128, 2, 2, A_CONV, 4>(g, s));
     case TILE_DMA_256x256:
-        return launch_status(a_mode == A_MATRIX ? launch_dma<256, 256, 2, 2, A_MATRIX, 4>(g, s)
-                                                : launch_dma<256, 256, 2, 2, A_CONV, 4>(g, s));
+        return launch_status(a_mode == A_MATRIX ? launch_dma<256, 256, 4, 2, A_MATRIX, 4>(g, s)
+                                                : launch_dma<256, 256, 4, 2, A_CONV, 4>(g, s));
     default:
         return QNN_EINVAL;
     }

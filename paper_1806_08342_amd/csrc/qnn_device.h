@@ -68,6 +68,23 @@ __device__ __forceinline__ int32_t rescale_fast(int32_t a, const RescaleParams &
     return t >> p.rshift;
 }
 
+// Fused fast form used by the GEMM epilogues, valid when 1 <= shift <= 21, mult >= 0,
+// |acc + corr| < 2^30 and 0 <= z_out <= 255:
+//   a2 = 2*(acc + corr);  h = hi32(a2*mult + 2^31)                 (= nearest(a*mult/2^31), ties up)
+//   q  = (h + half_z + (h >> 31)) >> n,  half_z = 2^(n-1) + (z_out << n)   (= z_out + nearest(h/2^n), ties away)
+// so the result already includes z_out and only needs the clamp to [act_min, act_max].
+struct FusedRescale {
+    int32_t mult, corr2, half_z, n;
+};
+
+__device__ __forceinline__ int32_t rescale_fused(int32_t acc, const FusedRescale &p)
+{
+    const int32_t a2 = (int32_t)(((uint32_t)acc << 1) + (uint32_t)p.corr2);
+    const int64_t prod = (int64_t)a2 * (int64_t)p.mult + (int64_t(1) << 31);
+    const int32_t h = (int32_t)(prod >> 32);
+    return (h + p.half_z + (h >> 31)) >> p.n;
+}
+
 __device__ __forceinline__ int32_t clamp_i32(int32_t lo, int32_t hi, int32_t v)
 {
     return v < lo ? lo : (v > hi ? hi : v);
