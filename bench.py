@@ -87,15 +87,24 @@ def time_gemm_sweep(torch, qnn, cases, steps, warmup):
 # ----------------------------------------------------------------------------- conv stacks
 
 def time_kernel(torch, fn, reps=5, warm=2):
+    """Seconds per launch.  The launches are captured into one HIP graph and the graph is replayed,
+    so that short kernels are timed at GPU speed and not at the speed of the Python launch loop."""
     for _ in range(warm):
         fn()
+    torch.cuda.synchronize()
+    n = max(reps, 10)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(n):
+            fn()
+    graph.replay()
+    torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
-    for _ in range(reps):
-        fn()
+    graph.replay()
     b.record()
     torch.cuda.synchronize()
-    return a.elapsed_time(b) / reps * 1e-3  # seconds per launch
+    return a.elapsed_time(b) / n * 1e-3
 
 
 def time_stack(torch, qnn, workloads, synth, layers, batch, config_id, reps):
@@ -242,6 +251,11 @@ def main():
     big = {f"{c['M']}x{c['N']}x{c['K']}": round(c["ops"] / (ms * 1e-3) * 1e-12, 1)
            for c, ms in zip(cases, per_case_ms) if (c["M"], c["N"], c["K"]) in
            [(1024,) * 3, (4096,) * 3, (8192,) * 3, (256, 8192, 8192), (64, 4096, 4096), (1, 4096, 4096)]}
+
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "bench_gemm.json"), "w") as f:
+        json.dump([dict(M=c["M"], N=c["N"], K=c["K"], plan=c["plan"], us=round(ms * 1e3, 2),
+                        tops=round(c["ops"] / (ms * 1e-3) * 1e-12, 1)) for c, ms in zip(cases, per_case_ms)], f, indent=0)
 
     result = {
         "metric": "effective int8 TOPS (quantized GEMM sweep, uint8 x int8 -> int32 -> uint8)",

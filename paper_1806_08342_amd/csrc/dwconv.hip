@@ -22,87 +22,131 @@ struct DwArgs {
     int N, H, W, C, Ho, Wo, kh, kw, sh, sw, ph, pw;
     int32_t z_x, z_out, lo_rel, hi_rel;
     int64_t total_work; // lanes of work
-    int wruns;          // runs of RW output pixels per output row
+    int wruns, hruns;   // patches of RW x RH output pixels per image row / column
 };
 
 __device__ __forceinline__ int32_t sbyte(uint32_t v, int j) { return (int32_t)(int8_t)(v >> (8 * j)); }
 __device__ __forceinline__ int32_t ubyte(uint32_t v, int j) { return (int32_t)((v >> (8 * j)) & 0xffu); }
 
-// KH x KW kernel, stride S (same in h and w), RW outputs per lane, 4 channels per lane
-template <int KH, int KW, int S, int RW>
-__global__ void __launch_bounds__(256) dwconv_c4_kernel(const DwArgs g)
+// 3x3 kernel, stride S (same in h and w).  One lane owns 4 consecutive channels and an
+// RH x RW patch of output pixels; the ((RH-1)S+3) x ((RW-1)S+3) input window is loaded once
+// (one dword = 4 channels per pixel), each byte is unpacked once and multiplied into every
+// output of the patch that uses it.  The accumulators start at bias - z_x * sum(w) and taps
+// outside the image read as the code z_x, which is the expansion of eq. 5-6 (z_w = 0) with
+// the border padded by the code of real zero.
+template <int S, int RH, int RW>
+__global__ void __launch_bounds__(256) dwconv3x3_kernel(const DwArgs g)
 {
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= g.total_work) return;
     const int cgroups = g.C >> 2;
     const int cg = (int)(gid % cgroups);
     int64_t t = gid / cgroups;
-    const int run = (int)(t % g.wruns);
+    const int pw = (int)(t % g.wruns);
     t /= g.wruns;
-    const int ho = (int)(t % g.Ho);
-    const int n = (int)(t / g.Ho);
+    const int ph = (int)(t % g.hruns);
+    const int n = (int)(t / g.hruns);
     const int c0 = cg * 4;
-    const int wo0 = run * RW;
+    const int ho0 = ph * RH, wo0 = pw * RW;
 
-    // per-channel constants
-    int32_t wt[KH][KW][4];
+    // weights as sign-extended ints, and their per-channel sums
+    int32_t wt[3][3][4];
+    int32_t wsum[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int a = 0; a < KH; ++a)
+    for (int a = 0; a < 3; ++a)
 #pragma unroll
-        for (int b = 0; b < KW; ++b) {
-            const uint32_t wv = *reinterpret_cast<const uint32_t *>(g.w + ((int64_t)a * KW + b) * g.C + c0);
+        for (int b = 0; b < 3; ++b) {
+            const uint32_t wv = *reinterpret_cast<const uint32_t *>(g.w + ((int64_t)a * 3 + b) * g.C + c0);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wt[a][b][j] = sbyte(wv, j);
+            for (int j = 0; j < 4; ++j) {
+                wt[a][b][j] = sbyte(wv, j);
+                wsum[j] += wt[a][b][j];
+            }
         }
-    int32_t acc[RW][4];
+    int32_t acc[RH][RW][4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int32_t b = g.bias ? g.bias[c0 + j] : 0;
+        const int32_t init = (g.bias ? g.bias[c0 + j] : 0) - g.z_x * wsum[j];
 #pragma unroll
-        for (int p = 0; p < RW; ++p) acc[p][j] = b;
+        for (int r = 0; r < RH; ++r)
+#pragma unroll
+            for (int p = 0; p < RW; ++p) acc[r][p][j] = init;
     }
 
-    constexpr int COLS = (RW - 1) * S + KW;
-    const int hi0 = ho * S - g.ph, wi0 = wo0 * S - g.pw;
+    constexpr int ROWS = (RH - 1) * S + 3, COLS = (RW - 1) * S + 3;
+    const int hi0 = ho0 * S - g.ph, wi0 = wo0 * S - g.pw;
     const uint8_t *img = g.x + (int64_t)n * g.H * g.W * g.C + c0;
+    const uint32_t fill = (uint32_t)g.z_x * 0x01010101u;
 #pragma unroll
-    for (int a = 0; a < KH; ++a) {
-        const int hi = hi0 + a;
+    for (int row = 0; row < ROWS; ++row) {
+        const int hi = hi0 + row;
         const bool row_ok = hi >= 0 && hi < g.H;
+        const uint8_t *line = img + (int64_t)hi * g.W * g.C;
+        uint32_t v[COLS];
 #pragma unroll
         for (int col = 0; col < COLS; ++col) {
             const int wi = wi0 + col;
-            int32_t xv[4] = {0, 0, 0, 0}; // (x - z_x); a tap outside the image contributes 0
-            if (row_ok && wi >= 0 && wi < g.W) {
-                const uint32_t v = *reinterpret_cast<const uint32_t *>(img + ((int64_t)hi * g.W + wi) * g.C);
+            v[col] = fill;
+            if (row_ok && wi >= 0 && wi < g.W) v[col] = *reinterpret_cast<const uint32_t *>(line + (int64_t)wi * g.C);
+        }
 #pragma unroll
-                for (int j = 0; j < 4; ++j) xv[j] = ubyte(v, j) - g.z_x;
-            }
+        for (int col = 0; col < COLS; ++col) {
+            int32_t xv[4];
 #pragma unroll
-            for (int p = 0; p < RW; ++p) {
-                const int b = col - p * S;
-                if (b >= 0 && b < KW) {
+            for (int j = 0; j < 4; ++j) xv[j] = ubyte(v[col], j);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[p][j] += xv[j] * wt[a][b][j];
+            for (int r = 0; r < RH; ++r) {
+                const int a = row - r * S; // kernel row of this input row for output row r
+                if (a < 0 || a > 2) continue;
+#pragma unroll
+                for (int p = 0; p < RW; ++p) {
+                    const int b = col - p * S;
+                    if (b < 0 || b > 2) continue;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[r][p][j] += xv[j] * wt[a][b][j];
                 }
             }
         }
     }
 
     RescaleParams rp[4];
+    FusedRescale fr[4];
+    bool fused_ok = true;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) rp[j] = make_rescale(g.mult[c0 + j], g.shift[c0 + j]);
-    uint8_t *out = g.y + (((int64_t)n * g.Ho + ho) * g.Wo + wo0) * g.C + c0;
-#pragma unroll
-    for (int p = 0; p < RW; ++p) {
-        if (wo0 + p >= g.Wo) break;
-        uint32_t packed = 0;
+    for (int j = 0; j < 4; ++j) {
+        const int32_t mu = g.mult[c0 + j], sf = g.shift[c0 + j];
+        rp[j] = make_rescale(mu, sf);
+        fused_ok = fused_ok && sf >= 1 && sf <= 21 && mu >= 0;
+        const int nn = (sf >= 1 && sf <= 21) ? sf : 1;
+        fr[j].mult = mu, fr[j].corr2 = 0, fr[j].half_z = (1 << (nn - 1)) + (g.z_out << nn), fr[j].n = nn;
+    }
+    // |acc| <= |bias| + 9 * 255 * 128 * 2: the fused form needs |acc| < 2^30, i.e. a sane bias
+    if (g.bias) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int32_t v = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(acc[p][j], rp[j])) + g.z_out;
-            packed |= (uint32_t)v << (8 * j);
+            const int32_t b = g.bias[c0 + j];
+            fused_ok = fused_ok && b > -(1 << 29) && b < (1 << 29);
         }
-        *reinterpret_cast<uint32_t *>(out + (int64_t)p * g.C) = packed;
+    }
+    const bool fused = __all(fused_ok);
+    const int32_t act_lo = g.lo_rel + g.z_out, act_hi = g.hi_rel + g.z_out;
+#pragma unroll
+    for (int r = 0; r < RH; ++r) {
+        if (ho0 + r >= g.Ho) break;
+        uint8_t *out = g.y + (((int64_t)n * g.Ho + ho0 + r) * g.Wo + wo0) * g.C + c0;
+#pragma unroll
+        for (int p = 0; p < RW; ++p) {
+            if (wo0 + p >= g.Wo) break;
+            uint32_t packed = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int32_t y;
+                if (fused) y = clamp_i32(act_lo, act_hi, rescale_fused(acc[r][p][j], fr[j]));
+                else y = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(acc[r][p][j], rp[j])) + g.z_out;
+                packed |= (uint32_t)y << (8 * j);
+            }
+            *reinterpret_cast<uint32_t *>(out + (int64_t)p * g.C) = packed;
+        }
     }
 }
 
@@ -157,19 +201,20 @@ extern "C" qnn_status qnn_qdwconv2d(const uint8_t *x, int N, int H, int W, int C
     auto al4 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; };
     const bool c4 = (C % 4 == 0) && al4(x) && al4(w) && al4(y) && kh == 3 && kw == 3 && stride_h == stride_w &&
                     (stride_h == 1 || stride_h == 2);
-    constexpr int RW = 4;
+    constexpr int RH = 2, RW = 4;
     if (c4) {
         g.wruns = (g.Wo + RW - 1) / RW;
-        g.total_work = (int64_t)N * g.Ho * g.wruns * (C / 4);
+        g.hruns = (g.Ho + RH - 1) / RH;
+        g.total_work = (int64_t)N * g.hruns * g.wruns * (C / 4);
     } else {
         g.total_work = (int64_t)N * g.Ho * g.Wo * C;
     }
     const int64_t blocks = (g.total_work + 255) / 256;
     if (blocks > 0x7fffffff) return QNN_EINVAL;
     if (c4 && stride_h == 1)
-        hipLaunchKernelGGL((dwconv_c4_kernel<3, 3, 1, RW>), dim3((unsigned)blocks), dim3(256), 0, s, g);
+        hipLaunchKernelGGL((dwconv3x3_kernel<1, RH, RW>), dim3((unsigned)blocks), dim3(256), 0, s, g);
     else if (c4)
-        hipLaunchKernelGGL((dwconv_c4_kernel<3, 3, 2, RW>), dim3((unsigned)blocks), dim3(256), 0, s, g);
+        hipLaunchKernelGGL((dwconv3x3_kernel<2, RH, RW>), dim3((unsigned)blocks), dim3(256), 0, s, g);
     else
         hipLaunchKernelGGL(dwconv_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, g);
     return launch_status(hipGetLastError());
