@@ -116,16 +116,15 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const DwArgs g)
     for (int j = 0; j < 4; ++j) {
         const int32_t mu = g.mult[c0 + j], sf = g.shift[c0 + j];
         rp[j] = make_rescale(mu, sf);
-        fused_ok = fused_ok && sf >= 1 && sf <= 21 && mu >= 0;
-        const int nn = (sf >= 1 && sf <= 21) ? sf : 1;
-        fr[j].mult = mu, fr[j].corr2 = 0, fr[j].half_z = (1 << (nn - 1)) + (g.z_out << nn), fr[j].n = nn;
+        fused_ok = fused_ok && sf >= 1 && sf <= 21;
+        fr[j] = make_fused(mu, sf, 0, g.z_out);
     }
-    // |acc| <= |bias| + 9 * 255 * 128 * 2: the fused form needs |acc| < 2^30, i.e. a sane bias
+    // |acc| <= |bias| + 2 * 9 * 255 * 128: the fused form needs |acc| < 2^29, i.e. a sane bias
     if (g.bias) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int32_t b = g.bias[c0 + j];
-            fused_ok = fused_ok && b > -(1 << 29) && b < (1 << 29);
+            fused_ok = fused_ok && b > -(1 << 28) && b < (1 << 28);
         }
     }
     const bool fused = __all(fused_ok);
@@ -141,7 +140,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const DwArgs g)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 int32_t y;
-                if (fused) y = clamp_i32(act_lo, act_hi, rescale_fused(acc[r][p][j], fr[j]));
+                if (fused) y = med3_i32(rescale_fused(acc[r][p][j], fr[j]), act_lo, act_hi);
                 else y = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(acc[r][p][j], rp[j])) + g.z_out;
                 packed |= (uint32_t)y << (8 * j);
             }

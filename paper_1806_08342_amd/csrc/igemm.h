@@ -46,7 +46,7 @@ struct IgemmArgs {
     uint8_t *C;
     int64_t ldc;
     int32_t c_vec16;  // C and ldc are 16-byte aligned
-    int32_t small_acc; // |acc| and the zero-point correction are each below 2^28
+    int32_t small_acc; // 2: |acc| and the zero-point correction are each below 2^27; 1: below 2^28; 0: unknown
 };
 
 __device__ __forceinline__ uint32_t fast_div(uint32_t k, uint32_t d, uint32_t magic)
@@ -177,9 +177,34 @@ __device__ __forceinline__ void load_b_chunk(const IgemmArgs &g, int n, int kc, 
 // Epilogue shared by the dense kernels: zero-point correction (eq. 5-6), bias, fixed-point
 // rescale, clamp; the uint8 tile is staged in LDS so that the global stores are 16-byte
 // rows.  `so` must not be read by anyone else any more (callers synchronise before).
+// Per-channel epilogue parameters of the TN column tiles a lane owns; fetched at kernel start
+// so that their global-memory latency is hidden behind the main loop.
+template <int TN> struct ChannelParams {
+    int32_t bias[TN], mult[TN], shift[TN];
+};
+
+template <int BN, int WN, int TN>
+__device__ __forceinline__ ChannelParams<TN> load_channel_params(const IgemmArgs &g, int n0)
+{
+    constexpr int WTN = BN / WN;
+    const int lane = threadIdx.x & 63, wave_n = (threadIdx.x >> 6) % WN;
+    ChannelParams<TN> p;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wave_n * WTN + j * 32 + (lane & 31);
+        p.bias[j] = 0, p.mult[j] = 0, p.shift[j] = 1;
+        if (n < g.N) {
+            p.bias[j] = g.bias ? g.bias[n] : 0;
+            p.mult[j] = g.mult[n];
+            p.shift[j] = g.shift[n];
+        }
+    }
+    return p;
+}
+
 template <int BM, int BN, int WM, int WN, bool WEIGHTS_X16, int TM, int TN>
 __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (&acc)[TM][TN], int32_t (&colsum)[TN],
-                                                    uint8_t *so, int64_t m0, int n0)
+                                                    const ChannelParams<TN> &cp, uint8_t *so, int64_t m0, int n0)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -188,73 +213,67 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
     const int lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / WN, wave_n = wave % WN;
     const int frag_row = lane & 31, frag_half = lane >> 5;
-    bool fast_ok = g.small_acc != 0, fused_ok = g.small_acc != 0;
+    bool fast_ok = g.small_acc >= 1, fused_ok = g.small_acc >= 2;
     int32_t corr[TN];
     RescaleParams rp[TN];
     FusedRescale fr[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wave_n * WTN + j * 32 + frag_row;
         int32_t cs = colsum[j] + __shfl_xor(colsum[j], 32);
         if (WEIGHTS_X16) cs >>= 4;
-        int32_t b = 0, mu = 0, sf = 1;
-        if (n < g.N) {
-            b = g.bias ? g.bias[n] : 0;
-            mu = g.mult[n];
-            sf = g.shift[n];
-        }
+        const int32_t b = cp.bias[j], mu = cp.mult[j], sf = cp.shift[j];
         corr[j] = b + (128 - g.z_a) * cs;
         rp[j] = make_rescale(mu, sf);
-        const bool small_bias = b > -(1 << 28) && b < (1 << 28);
-        fast_ok = fast_ok && sf >= 0 && small_bias;
-        fused_ok = fused_ok && sf >= 1 && sf <= 21 && mu >= 0 && small_bias;
-        const int nn = (sf >= 1 && sf <= 21) ? sf : 1;
-        fr[j].mult = mu;
-        fr[j].corr2 = 2 * corr[j];
-        fr[j].half_z = (1 << (nn - 1)) + (g.z_out << nn);
-        fr[j].n = nn;
+        // |acc + corr| < 2^30 for the 64-bit fast form, < 2^29 for the fused 32-bit form
+        fast_ok = fast_ok && sf >= 0 && b > -(1 << 28) && b < (1 << 28);
+        fused_ok = fused_ok && sf >= 1 && sf <= 21 && b > -(1 << 27) && b < (1 << 27);
+        fr[j] = make_fused(mu, sf, corr[j], g.z_out);
     }
     const bool fast = __all(fast_ok), fused = __all(fused_ok);
     const int32_t act_lo = g.lo_rel + g.z_out, act_hi = g.hi_rel + g.z_out;
-    auto out_byte = [&](int i, int j, int r) -> uint8_t * {
-        const int row = wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
-        const int col = wave_n * WTN + j * 32 + frag_row;
-        return so + row * OUT_PITCH + col;
+
+    // A lane holds, for one column, the rows 8q + 4*half + {0,1,2,3} (q = 0..3) of each 32x32
+    // tile.  The four bytes of a row group are packed into a dword and the 4x4 byte blocks are
+    // transposed across the four lanes of a quad (two DPP exchanges + byte permutes), so that
+    // every lane ends up with 4 consecutive columns of ONE row and the LDS tile is written
+    // with conflict-free dword stores instead of byte stores.
+    const int quad_lane = lane & 3;
+    const uint32_t sel1 = (quad_lane & 1) ? 0x03070105u : 0x06020400u;
+    const uint32_t sel2 = (quad_lane & 2) ? 0x03020706u : 0x05040100u;
+    auto store_group = [&](int i, int j, int q, const int32_t (&y)[4]) {
+        uint32_t x = (uint32_t)y[0] | ((uint32_t)y[1] << 8) | ((uint32_t)y[2] << 16) | ((uint32_t)y[3] << 24);
+        // exchange with lane ^ 1, then with lane ^ 2 (quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E)
+        uint32_t o = (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);
+        x = __builtin_amdgcn_perm(o, x, sel1);
+        o = (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true);
+        x = __builtin_amdgcn_perm(o, x, sel2);
+        const int row = wave_m * WTM + i * 32 + 8 * q + 4 * frag_half + quad_lane;
+        const int col = wave_n * WTN + j * 32 + (frag_row & ~3);
+        *reinterpret_cast<uint32_t *>(so + row * OUT_PITCH + col) = x;
     };
-    // one accumulator -> one byte in the LDS output tile
-    auto finish = [&](int i, int j, int r, auto rescale) {
-        int32_t a = acc[i][j][r];
-        if (WEIGHTS_X16) a >>= 4; // weights were staged times 16; exact
-        a += corr[j];
-        *out_byte(i, j, r) = (uint8_t)(clamp_i32(g.lo_rel, g.hi_rel, rescale(a, rp[j])) + g.z_out);
+    auto run = [&](auto one) {
+#pragma clang loop unroll(full)
+        for (int i = 0; i < TM; ++i)
+#pragma clang loop unroll(full)
+            for (int j = 0; j < TN; ++j)
+#pragma clang loop unroll(full)
+                for (int q = 0; q < 4; ++q) {
+                    int32_t y[4];
+#pragma clang loop unroll(full)
+                    for (int e = 0; e < 4; ++e) {
+                        int32_t a = acc[i][j][4 * q + e];
+                        if (WEIGHTS_X16) a >>= 4; // weights were staged times 16; exact
+                        y[e] = one(a, j);
+                    }
+                    store_group(i, j, q, y);
+                }
     };
     if (fused) {
-#pragma clang loop unroll(full)
-        for (int i = 0; i < TM; ++i)
-#pragma clang loop unroll(full)
-            for (int j = 0; j < TN; ++j)
-#pragma clang loop unroll(full)
-                for (int r = 0; r < 16; ++r) {
-                    int32_t a = acc[i][j][r];
-                    if (WEIGHTS_X16) a >>= 4;
-                    *out_byte(i, j, r) = (uint8_t)clamp_i32(act_lo, act_hi, rescale_fused(a, fr[j]));
-                }
+        run([&](int32_t a, int j) { return med3_i32(rescale_fused(a, fr[j]), act_lo, act_hi); });
     } else if (fast) {
-#pragma clang loop unroll(full)
-        for (int i = 0; i < TM; ++i)
-#pragma clang loop unroll(full)
-            for (int j = 0; j < TN; ++j)
-#pragma clang loop unroll(full)
-                for (int r = 0; r < 16; ++r)
-                    finish(i, j, r, [](int32_t a, const RescaleParams &p) { return rescale_fast(a, p); });
+        run([&](int32_t a, int j) { return clamp_i32(g.lo_rel, g.hi_rel, rescale_fast(a + corr[j], rp[j])) + g.z_out; });
     } else {
-#pragma clang loop unroll(full)
-        for (int i = 0; i < TM; ++i)
-#pragma clang loop unroll(full)
-            for (int j = 0; j < TN; ++j)
-#pragma clang loop unroll(full)
-                for (int r = 0; r < 16; ++r)
-                    finish(i, j, r, [](int32_t a, const RescaleParams &p) { return rescale_general(a, p); });
+        run([&](int32_t a, int j) { return clamp_i32(g.lo_rel, g.hi_rel, rescale_general(a + corr[j], rp[j])) + g.z_out; });
     }
     __syncthreads();
 
@@ -276,9 +295,9 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
 
 template <int BM, int BN, int WM, int WN, bool WEIGHTS_X16, int TM, int TN>
 __device__ __forceinline__ void igemm_epilogue(const IgemmArgs &g, i32x16 (&acc)[TM][TN], int32_t (&colsum)[TN],
-                                               uint8_t *so, int64_t m0, int n0)
+                                               const ChannelParams<TN> &cp, uint8_t *so, int64_t m0, int n0)
 {
-    igemm_epilogue_impl<BM, BN, WM, WN, WEIGHTS_X16, TM, TN>(g, acc, colsum, so, m0, n0);
+    igemm_epilogue_impl<BM, BN, WM, WN, WEIGHTS_X16, TM, TN>(g, acc, colsum, cp, so, m0, n0);
 }
 
 template <int BM, int BN, int WM, int WN, int A_MODE, int B_MODE, int VEC>
@@ -325,6 +344,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_kernel(const IgemmArgs g)
         }
     }
     const uint32_t fill_a = (uint32_t)g.z_a * 0x01010101u;
+    const ChannelParams<TN> cparams = load_channel_params<BN, WN, TN>(g, n0);
 
     uint32_t stage_a[A_CHUNKS][4], stage_b[B_CHUNKS][4];
     auto fetch = [&](int k0) {
@@ -399,7 +419,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_kernel(const IgemmArgs g)
     }
 
     // the last __syncthreads above guarantees nobody still reads the operand tiles
-    igemm_epilogue<BM, BN, WM, WN, B_MODE == B_INT4>(g, acc, colsum, smem, m0, n0);
+    igemm_epilogue<BM, BN, WM, WN, B_MODE == B_INT4>(g, acc, colsum, cparams, smem, m0, n0);
 }
 
 } // namespace qnn

@@ -36,22 +36,39 @@ static void launch_tile(const IgemmArgs &g, int b_mode, int vec, hipStream_t s)
     }
 }
 
-enum TileConfig { TILE_64x64 = 0, TILE_128x128 = 1, TILE_DMA_128x128 = 2, TILE_DMA_256x256 = 3, TILE_COUNT };
+enum TileConfig {
+    TILE_64x64 = 0,
+    TILE_128x128,
+    TILE_DMA_128x128,
+    TILE_DMA_256x256,
+    TILE_DMA_256x64,
+    TILE_DMA_128x128_S3,
+    TILE_DMA_256x64_S3,
+    TILE_COUNT
+};
 
-static const char *const kTileNames[TILE_COUNT] = {"64x64", "128x128", "dma128x128", "dma256x256"};
+static const char *const kTileNames[TILE_COUNT] = {"64x64",     "128x128",      "dma128x128",  "dma256x256",
+                                                   "dma256x64", "dma128x128s3", "dma256x64s3"};
+static const int kTileM[TILE_COUNT] = {64, 128, 128, 256, 256, 128, 256};
+static const int kTileN[TILE_COUNT] = {64, 128, 128, 256, 64, 128, 64};
 
-// Tile choice.  `dma_ok`: int8 weights with contiguous columns and 16-byte aligned chunks.
+// Tile choice.  `dma_ok`: int8 weights with contiguous columns, 16-byte aligned chunks, K % 64 == 0.
+//  - large products: 256x256 tiles (8 waves, 4 LDS stages, one workgroup per CU);
+//  - few output channels: 256x64 tiles; otherwise 128x128 tiles;
+//  - short K (<= 256): 3 LDS stages instead of 4, so that more workgroups fit a CU and one
+//    workgroup's epilogue overlaps another one's loads and MFMAs.
 static TileConfig choose_tile(int64_t M, int64_t N, int64_t K, bool dma_ok)
 {
     if (const char *force = std::getenv("QNN_FORCE_TILE")) { // tuning aid: force one configuration
         for (int t = 0; t < TILE_COUNT; ++t)
             if (std::strcmp(force, kTileNames[t]) == 0 && (t < TILE_DMA_128x128 || dma_ok)) return (TileConfig)t;
     }
-    (void)K;
     if (dma_ok) {
         const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-        if (M >= 512 && N >= 512 && tiles256 >= 192) return TILE_DMA_256x256;
-        if (M >= 128 && N >= 128) return TILE_DMA_128x128;
+        const bool short_k = K <= 256;
+        if (M >= 512 && N >= 512 && tiles256 >= 192 && !short_k) return TILE_DMA_256x256;
+        if (N <= 64 && M >= 256) return short_k ? TILE_DMA_256x64_S3 : TILE_DMA_256x64;
+        if (M >= 128 && N >= 128) return short_k ? TILE_DMA_128x128_S3 : TILE_DMA_128x128;
     }
     return (N <= 64 || M <= 64) ? TILE_64x64 : TILE_128x128;
 }
@@ -59,7 +76,8 @@ static TileConfig choose_tile(int64_t M, int64_t N, int64_t K, bool dma_ok)
 template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE>
 static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s)
 {
-    constexpr int kLds = NSTAGE * (BM + BN) * 64;
+    constexpr int kStages = NSTAGE * (BM + BN) * 64, kOut = BM * (BN + 16) + 4 * WM * WN * (BN / WN / 32) * 64;
+    constexpr int kLds = kStages > kOut ? kStages : kOut; // operand ring, reused for the output tile + column sums
     auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE>;
     static bool configured = false; // per instantiation
     if (!configured) {
@@ -80,27 +98,32 @@ static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s)
 static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s)
 {
     const int64_t max_tiles = 0x7ffffff;
-    g.small_acc = g.K <= 16384;
+    g.small_acc = g.K <= 8192 ? 2 : (g.K <= 16384 ? 1 : 0); // |acc| <= K * 2^14
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
     const bool dma_ok = b_mode == B_INT8 && vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23);
     const TileConfig cfg = choose_tile(g.M, g.N, g.K, dma_ok);
-    const int64_t bm = cfg == TILE_64x64 ? 64 : (cfg == TILE_DMA_256x256 ? 256 : 128), bn = bm;
+    const int64_t bm = kTileM[cfg], bn = kTileN[cfg];
     if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return QNN_EINVAL;
+    const bool mat = a_mode == A_MATRIX;
     switch (cfg) {
     case TILE_64x64:
-        if (a_mode == A_MATRIX) launch_tile<64, 64, 2, 2, A_MATRIX>(g, b_mode, vec, s);
+        if (mat) launch_tile<64, 64, 2, 2, A_MATRIX>(g, b_mode, vec, s);
         else launch_tile<64, 64, 2, 2, A_CONV>(g, b_mode, vec, s);
         break;
     case TILE_128x128:
-        if (a_mode == A_MATRIX) launch_tile<128, 128, 2, 2, A_MATRIX>(g, b_mode, vec, s);
+        if (mat) launch_tile<128, 128, 2, 2, A_MATRIX>(g, b_mode, vec, s);
         else launch_tile<128, 128, 2, 2, A_CONV>(g, b_mode, vec, s);
         break;
     case TILE_DMA_128x128:
-        return launch_status(a_mode == A_MATRIX ? launch_dma<128, 128, 2, 2, A_MATRIX, 4>(g, s)
-                                                : launch_dma<128, 128, 2, 2, A_CONV, 4>(g, s));
+        return launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 4>(g, s));
+    case TILE_DMA_128x128_S3:
+        return launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 3>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 3>(g, s));
     case TILE_DMA_256x256:
-        return launch_status(a_mode == A_MATRIX ? launch_dma<256, 256, 4, 2, A_MATRIX, 4>(g, s)
-                                                : launch_dma<256, 256, 4, 2, A_CONV, 4>(g, s));
+        return launch_status(mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 256, 4, 2, A_CONV, 4>(g, s));
+    case TILE_DMA_256x64:
+        return launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 4>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 4>(g, s));
+    case TILE_DMA_256x64_S3:
+        return launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 3>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 3>(g, s));
     default:
         return QNN_EINVAL;
     }

@@ -124,24 +124,25 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
         b_lane_off[j] = (uint32_t)((int64_t)(n - n0) * g.ldb) + (uint32_t)b_koff;
     }
     const uint8_t *fill_a = &g_fill_table.v[g.z_a][0];
+    const ChannelParams<TN> cparams = load_channel_params<BN, WN, TN>(g, n0);
     const int ktiles = g.K / BK; // the dispatcher guarantees K % 64 == 0
 
     // load number `idx` (0 .. LOADS-1) of K-step kt: A segments first, then B segments.
-    // K-steps past the end re-fetch the last one into a buffer nobody reads any more
-    // (harmless, and it keeps the number of loads per K-step uniform for the vmcnt waits).
+    // K-steps past the end fetch one constant 16-byte chunk instead (into a buffer nobody reads
+    // any more): no extra memory traffic, and the number of loads per K-step stays uniform,
+    // which the vmcnt-based waits rely on.
     auto issue_load = [&](int kt, int idx) {
         uint8_t *stage = smem + (kt % NSTAGE) * STAGE_BYTES;
-        const int kt_eff = kt < ktiles ? kt : ktiles - 1;
-        const int k0 = kt_eff * BK;
+        const bool live = kt < ktiles; // wave-uniform
+        const int k0 = kt * BK;
         if (idx < A_LOADS) {
             const int j = idx;
-            const uint8_t *src;
+            const uint8_t *src = fill_a;
             if constexpr (A_MODE == A_MATRIX) {
-                src = (a_tile + k0) + a_lane_off[j]; // K % 64 == 0: no tail
+                if (live) src = (a_tile + k0) + a_lane_off[j]; // K % 64 == 0: no tail
             } else {
                 const int k = k0 + a_koff[j];
-                src = fill_a;
-                if (k < g.K) {
+                if (live) {
                     const uint32_t tap = fast_div((uint32_t)k, (uint32_t)g.Cin, g.magic_cin);
                     const int ci = k - (int)tap * g.Cin;
                     const uint32_t ta = fast_div(tap, (uint32_t)g.kw, g.magic_kw);
@@ -153,7 +154,8 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
             dma16(src, stage + (wave * A_LOADS + j) * 1024);
         } else {
             const int j = idx - A_LOADS;
-            dma16((b_tile + k0) + b_lane_off[j], stage + BM * BK + (wave * B_LOADS + j) * 1024);
+            const uint8_t *src = live ? (b_tile + k0) + b_lane_off[j] : fill_a;
+            dma16(src, stage + BM * BK + (wave * B_LOADS + j) * 1024);
         }
     };
     auto issue_stage = [&](int kt) {
@@ -213,11 +215,11 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xs[i], fb[j], acc[i][j], 0, 0, 0);
                 const int done = i * TN + j + 1;
                 // after every MMAS/PIECES MFMAs issue one fragment read (and one DMA load)
-                if (do_read && piece < PIECES && done * PIECES >= (piece + 1) * MMAS) {
+                while (do_read && piece < PIECES && done * PIECES >= (piece + 1) * MMAS) {
                     read_piece(next_stage, next_ks, piece, na, nb);
                     ++piece;
                 }
-                if (dma_kt >= 0 && load < LOADS && done * LOADS >= (load + 1) * MMAS) {
+                while (dma_kt >= 0 && load < LOADS && done * LOADS >= (load + 1) * MMAS) {
                     issue_load(dma_kt, load);
                     ++load;
                 }
@@ -246,6 +248,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
         }
         // stage kt+1 must have landed: only the NSTAGE-3 stages issued after it may be in flight
         // (every K-step issues exactly LOADS loads, real or fill, so the count is uniform)
+        static_assert(NSTAGE >= 3, "the refilled buffer must not be the one still being read");
         wait_vmcnt<(NSTAGE - 3) * LOADS>();
         block_barrier(); // also: every wave is done reading stage kt-1, whose buffer is refilled next
         // sub-step 1: MFMAs on (fa1, fb1) while the first fragments of stage kt+1 are read and the
@@ -278,7 +281,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
             }
         }
     }
-    igemm_epilogue<BM, BN, WM, WN, false>(g, acc, colsum, smem, m0, n0);
+    igemm_epilogue<BM, BN, WM, WN, false>(g, acc, colsum, cparams, smem, m0, n0);
 }
 
 } // namespace qnn

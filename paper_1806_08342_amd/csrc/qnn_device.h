@@ -68,21 +68,42 @@ __device__ __forceinline__ int32_t rescale_fast(int32_t a, const RescaleParams &
     return t >> p.rshift;
 }
 
-// Fused fast form used by the GEMM epilogues, valid when 1 <= shift <= 21, mult >= 0,
-// |acc + corr| < 2^30 and 0 <= z_out <= 255:
-//   a2 = 2*(acc + corr);  h = hi32(a2*mult + 2^31)                 (= nearest(a*mult/2^31), ties up)
-//   q  = (h + half_z + (h >> 31)) >> n,  half_z = 2^(n-1) + (z_out << n)   (= z_out + nearest(h/2^n), ties away)
-// so the result already includes z_out and only needs the clamp to [act_min, act_max].
+// Fused fast form used by the conv / GEMM epilogues, valid when 1 <= shift <= 21,
+// |acc + corr| < 2^29 and 0 <= z_out <= 255.  With a = acc + corr, n = shift:
+//   H = hi32(4a * mult)                      then  nearest(a*mult/2^31), ties up  = (H + 1) >> 1
+//   t = H + 1, s = t >> 31 (0 or -1)         and   z_out + nearest(h/2^n), ties away from zero
+//   q = (t + 2s + 2*half_z) >> (n + 1),  half_z = 2^(n-1) + (z_out << n)
+// (two nested floor divisions by powers of two collapse into one).  Only full-rate 32-bit
+// operations; the result already includes z_out and only needs the clamp.
 struct FusedRescale {
-    int32_t mult, corr2, half_z, n;
+    int32_t mult, corr4, c2, n1; // corr4 = 4*corr, c2 = 2*half_z, n1 = n + 1
 };
+
+__device__ __forceinline__ FusedRescale make_fused(int32_t mult, int32_t shift, int32_t corr, int32_t z_out)
+{
+    const int nn = (shift >= 1 && shift <= 21) ? shift : 1; // callers check the range; keep shifts defined
+    FusedRescale f;
+    f.mult = mult;
+    f.corr4 = (int32_t)((uint32_t)corr << 2);
+    f.c2 = 2 * ((1 << (nn - 1)) + (z_out << nn));
+    f.n1 = nn + 1;
+    return f;
+}
 
 __device__ __forceinline__ int32_t rescale_fused(int32_t acc, const FusedRescale &p)
 {
-    const int32_t a2 = (int32_t)(((uint32_t)acc << 1) + (uint32_t)p.corr2);
-    const int64_t prod = (int64_t)a2 * (int64_t)p.mult + (int64_t(1) << 31);
-    const int32_t h = (int32_t)(prod >> 32);
-    return (h + p.half_z + (h >> 31)) >> p.n;
+    const int32_t a4 = (int32_t)(((uint32_t)acc << 2) + (uint32_t)p.corr4);
+    const int32_t t = __mulhi(a4, p.mult) + 1;
+    const int32_t w = ((t >> 31) << 1) + t;
+    return (w + p.c2) >> p.n1;
+}
+
+// median of three = clamp(lo, hi, v) for lo <= hi, one instruction
+__device__ __forceinline__ int32_t med3_i32(int32_t v, int32_t lo, int32_t hi)
+{
+    int32_t r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
 }
 
 __device__ __forceinline__ int32_t clamp_i32(int32_t lo, int32_t hi, int32_t v)
