@@ -213,6 +213,8 @@ def main():
     ap.add_argument("--no-secondary", action="store_true", help="skip the conv stacks and streaming kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", action="store_true", help="include per-layer rows of the conv stacks in the JSON")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every box has one; the path needs no exchange between GPUs); "
@@ -294,6 +296,13 @@ def main():
             os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
             with open(os.path.join(ROOT, "gpurun_out", "bench_layers.json"), "w") as f:
                 json.dump(layer_dump, f, indent=1)
+    if args.calibrate_copy:
+        src = _device_uint8(torch, (1 << 30,), 12345)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        result["calibration_copy_bytes"] = 1 << 30
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline()
     print(json.dumps(result))
