@@ -3,10 +3,10 @@
 // 18 integer operations per output byte: the kernel is bound by HBM traffic and by the
 // vector ALU, not by the matrix cores, so it does not use MFMA.  Channels are the
 // contiguous axis: one lane owns 4 consecutive channels (one dword of activations, one
-// dword of weights per tap) and a run of RW consecutive output pixels along W, so that the
-// kh x (RW*stride + kw - stride) input window is loaded once and reused by all RW outputs;
-// consecutive lanes own consecutive channel groups, which makes every load and store of a
-// wave a contiguous run of channels.
+// dword of weights per tap) and a small patch of output pixels, so that the input window is
+// loaded and unpacked once and reused by every output of the patch; consecutive lanes own
+// consecutive channel groups, which makes every load and store of a wave a contiguous run
+// of channels.
 //
 //   acc[c] = sum_{a,b} (x[hi][wi][c] - z_x) * w[a][b][c]    taps outside the image skipped
 //   out    = clamp(z_out + RESCALE(acc + bias[c]; mult[c], shift[c]))            (eq. 4-6, z_w = 0)
