@@ -26,6 +26,10 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5033.0  # dense int8 MFMA, 256 CU x 2.4 GHz x 8192 ops/clk/CU
 PEAK_HBM_GBS = 8000.0
+# vector ALU: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz full-rate 32-bit integer operations per second
+PEAK_VALU_LANE_OPS = 256 * 64 * 2.4e9
+# the exact fixed-point rescale + clamp + uint8 packing costs about 10 full-rate operations per output byte
+EPILOGUE_OPS_PER_OUTPUT = 10.0
 
 
 def _device_uint8(torch, shape, seed):
@@ -138,10 +142,13 @@ def time_stack(torch, qnn, workloads, synth, layers, batch, config_id, reps):
         t = time_kernel(torch, fn, reps=reps)
         macs, nbytes = l.macs(batch), l.bytes(batch)
         t_mfma, t_hbm = 2.0 * macs / (PEAK_INT8_TOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
+        outputs = batch * l.Ho * l.Wo * l.Cout if l.kind != "qadd" else batch * l.H * l.W * l.Cout
+        alu_ops = EPILOGUE_OPS_PER_OUTPUT + (18.0 if l.kind == "dw" else 0.0)  # depthwise: + 9 MACs as unpack + mad
+        t_alu = outputs * alu_ops / PEAK_VALU_LANE_OPS
         bound = max(t_mfma, t_hbm)
         rows.append(dict(layer=l.name, kind=l.kind, count=l.count, us=round(t * 1e6, 2), tops=round(2e-12 * macs / t, 2),
                          gbs=round(nbytes / t * 1e-9, 1), bound="mfma" if t_mfma > t_hbm else "hbm",
-                         frac=round(bound / t, 3)))
+                         frac=round(bound / t, 3), frac_alu=round(t_alu / t, 3)))
         total_t += t * l.count
         total_bound += bound * l.count
         total_macs += macs * l.count

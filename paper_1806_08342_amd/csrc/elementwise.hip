@@ -170,7 +170,9 @@ struct QaddArgs {
 // The rescaled value of an input depends only on its 8-bit code, so each block first
 // tabulates RESCALE((v - z) * 2^L) for the 256 codes of a and of b in LDS; the streaming
 // loop is then two table reads, an add and one rescale per element.
-template <int VEC>
+// FUSED: the output rescale may use the 32-bit fused form (1 <= shift_o <= 21 and both tables
+// bounded by 2^28, which shift_a, shift_b >= 0 and left_shift <= 20 guarantee).
+template <int VEC, bool FUSED>
 __global__ void __launch_bounds__(kThreads) qadd_kernel(const uint8_t *__restrict__ a, const uint8_t *__restrict__ b,
                                                         uint8_t *__restrict__ y, size_t n, QaddArgs g)
 {
@@ -185,7 +187,9 @@ __global__ void __launch_bounds__(kThreads) qadd_kernel(const uint8_t *__restric
     const RescaleParams po = make_rescale(g.mult_o, g.shift_o);
     const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    const FusedRescale fo = make_fused(g.mult_o, g.shift_o, 0, g.z_out);
     auto one = [&](uint32_t ca, uint32_t cb) -> uint32_t {
+        if (FUSED) return (uint32_t)med3_i32(rescale_fused(tab_a[ca] + tab_b[cb], fo), g.act_min, g.act_max);
         int64_t u = (int64_t)tab_a[ca] + (int64_t)tab_b[cb];
         u = u > INT32_MAX ? INT32_MAX : (u < INT32_MIN ? INT32_MIN : u);
         return (uint32_t)(clamp_i32(g.act_min - g.z_out, g.act_max - g.z_out, rescale_general((int32_t)u, po)) + g.z_out);
@@ -320,12 +324,17 @@ qnn_status qnn_qadd(const uint8_t *a, int32_t z_a, int32_t mult_a, int32_t shift
     if (n == 0) return QNN_OK;
     if (!a || !b || !y) return QNN_EINVAL;
     QaddArgs g = {z_a, mult_a, shift_a, z_b, mult_b, shift_b, left_shift, mult_o, shift_o, z_out, act_min, act_max};
-    if (aligned(a, 16) && aligned(b, 16) && aligned(y, 16))
-        hipLaunchKernelGGL(qadd_kernel<16>, dim3(grid_for(n / 16 + 1, kThreads * 2)), dim3(kThreads), 0,
-                           as_stream(stream), a, b, y, n, g);
-    else
-        hipLaunchKernelGGL(qadd_kernel<1>, dim3(grid_for(n, kThreads * 4)), dim3(kThreads), 0, as_stream(stream), a, b,
-                           y, n, g);
+    const bool fused = shift_o >= 1 && shift_o <= 21 && shift_a >= 0 && shift_b >= 0 && left_shift <= 20;
+    const hipStream_t s = as_stream(stream);
+    if (aligned(a, 16) && aligned(b, 16) && aligned(y, 16)) {
+        const int grid = grid_for(n / 16 + 1, kThreads * 2);
+        if (fused) hipLaunchKernelGGL((qadd_kernel<16, true>), dim3(grid), dim3(kThreads), 0, s, a, b, y, n, g);
+        else hipLaunchKernelGGL((qadd_kernel<16, false>), dim3(grid), dim3(kThreads), 0, s, a, b, y, n, g);
+    } else {
+        const int grid = grid_for(n, kThreads * 4);
+        if (fused) hipLaunchKernelGGL((qadd_kernel<1, true>), dim3(grid), dim3(kThreads), 0, s, a, b, y, n, g);
+        else hipLaunchKernelGGL((qadd_kernel<1, false>), dim3(grid), dim3(kThreads), 0, s, a, b, y, n, g);
+    }
     return launch_status(hipGetLastError());
 }
 

@@ -5,6 +5,7 @@
 #include <cstring>
 
 #include "igemm_dma.h"
+#include "stemconv.h"
 
 namespace qnn {
 
@@ -44,13 +45,14 @@ enum TileConfig {
     TILE_DMA_256x64,
     TILE_DMA_128x128_S3,
     TILE_DMA_256x64_S3,
+    TILE_DMA_256x128,
     TILE_COUNT
 };
 
 static const char *const kTileNames[TILE_COUNT] = {"64x64",     "128x128",      "dma128x128",  "dma256x256",
-                                                   "dma256x64", "dma128x128s3", "dma256x64s3"};
-static const int kTileM[TILE_COUNT] = {64, 128, 128, 256, 256, 128, 256};
-static const int kTileN[TILE_COUNT] = {64, 128, 128, 256, 64, 128, 64};
+                                                   "dma256x64", "dma128x128s3", "dma256x64s3", "dma256x128"};
+static const int kTileM[TILE_COUNT] = {64, 128, 128, 256, 256, 128, 256, 256};
+static const int kTileN[TILE_COUNT] = {64, 128, 128, 256, 64, 128, 64, 128};
 
 // Tile choice.  `dma_ok`: int8 weights with contiguous columns, 16-byte aligned chunks, K % 64 == 0.
 //  - large products: 256x256 tiles (8 waves, 4 LDS stages, one workgroup per CU);
@@ -63,12 +65,31 @@ static TileConfig choose_tile(int64_t M, int64_t N, int64_t K, bool dma_ok)
         for (int t = 0; t < TILE_COUNT; ++t)
             if (std::strcmp(force, kTileNames[t]) == 0 && (t < TILE_DMA_128x128 || dma_ok)) return (TileConfig)t;
     }
-    if (dma_ok) {
-        const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-        const bool short_k = K <= 256;
-        if (M >= 512 && N >= 512 && tiles256 >= 192 && !short_k) return TILE_DMA_256x256;
-        if (N <= 64 && M >= 256) return short_k ? TILE_DMA_256x64_S3 : TILE_DMA_256x64;
-        if (M >= 128 && N >= 128) return short_k ? TILE_DMA_128x128_S3 : TILE_DMA_128x128;
+    if (dma_ok && M >= 128) {
+        if (K <= 256) { // epilogue-bound: small tiles, several workgroups per CU
+            if (N <= 64) return TILE_DMA_256x64_S3;
+            if (N >= 128) return TILE_DMA_128x128_S3;
+        } else {
+            // pick the configuration with the least padded work: whole waves of workgroups over the
+            // chip, weighted by the measured relative MFMA rate of each configuration
+            struct Cand { TileConfig t; int per_cu; double rate; };
+            static const Cand cands[] = {{TILE_DMA_256x256, 1, 1.00}, {TILE_DMA_256x128, 1, 0.88},
+                                         {TILE_DMA_128x128, 2, 0.72}, {TILE_DMA_256x64, 2, 0.60}};
+            double best = 0.0;
+            TileConfig pick = TILE_COUNT;
+            for (const Cand &c : cands) {
+                const int bm = kTileM[c.t], bn = kTileN[c.t];
+                if (N < bn / 2 || M < bm / 2) continue; // mostly empty tiles
+                const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+                if (tiles < 224) continue; // would leave CUs idle: smaller tiles are better then
+                const int64_t slots = 256 * c.per_cu;
+                const int64_t waves = (tiles + slots - 1) / slots;
+                const double cost = (double)waves * c.per_cu * bm * bn / c.rate; // time of `waves` rounds
+                if (pick == TILE_COUNT || cost < best) best = cost, pick = c.t;
+            }
+            if (pick != TILE_COUNT) return pick;
+            return N <= 64 ? TILE_DMA_256x64 : TILE_DMA_128x128; // under-filled chip: most tiles
+        }
     }
     return (N <= 64 || M <= 64) ? TILE_64x64 : TILE_128x128;
 }
@@ -122,6 +143,8 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
         return launch_status(mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 256, 4, 2, A_CONV, 4>(g, s));
     case TILE_DMA_256x64:
         return launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 4>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 4>(g, s));
+    case TILE_DMA_256x128:
+        return launch_status(mat ? launch_dma<256, 128, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 128, 4, 2, A_CONV, 4>(g, s));
     case TILE_DMA_256x64_S3:
         return launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 3>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 3>(g, s));
     default:
@@ -211,6 +234,28 @@ qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z
     g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
     g.C = y, g.ldc = Cout;
     const int b_mode = weight_bits == 4 ? B_INT4 : B_INT8;
+    // network stems: a handful of input channels, one kernel row = one short contiguous byte run
+    if (weight_bits == 8 && Cin < 16 && kw * Cin <= 32 && stride_w * Cin <= 7 && (kh == 3 || kh == 7) && Cout <= 64 &&
+        ((int64_t)W * Cin) % 4 == 0 && aligned_to(x, 4)) {
+        StemArgs st = {};
+        g.small_acc = 2;
+        g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
+        st.g = g, st.kh = kh, st.run = kw * Cin;
+        st.strips = (Wo + 127) / 128;
+        // a workgroup walks up to 8 output rows (weights are staged once per workgroup), fewer
+        // when that would leave the chip with too few workgroups
+        const int64_t row_strips = (int64_t)N * Ho * st.strips;
+        st.rows_per_wg = (int)(row_strips / 2048 < 1 ? 1 : (row_strips / 2048 > 8 ? 8 : row_strips / 2048));
+        const int64_t blocks = (int64_t)N * ((Ho + st.rows_per_wg - 1) / st.rows_per_wg) * st.strips;
+        if (blocks <= 0x7fffffff) {
+            const hipStream_t s = as_stream(stream);
+            if (kh == 3 && Cout <= 32) hipLaunchKernelGGL((stemconv_kernel<3, 1>), dim3((unsigned)blocks), dim3(256), 0, s, st);
+            else if (kh == 3) hipLaunchKernelGGL((stemconv_kernel<3, 2>), dim3((unsigned)blocks), dim3(256), 0, s, st);
+            else if (Cout <= 32) hipLaunchKernelGGL((stemconv_kernel<7, 1>), dim3((unsigned)blocks), dim3(256), 0, s, st);
+            else hipLaunchKernelGGL((stemconv_kernel<7, 2>), dim3((unsigned)blocks), dim3(256), 0, s, st);
+            return launch_status(hipGetLastError());
+        }
+    }
     const bool pointwise = kh == 1 && kw == 1 && stride_h == 1 && stride_w == 1 && pad_h == 0 && pad_w == 0;
     if (pointwise) { // a 1x1 convolution over NHWC is a plain matrix product
         g.lda = Cin;

@@ -90,7 +90,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
     // ---- per-lane source description of the chunks this lane fetches at every K-step
     // A_MATRIX and B: a wave-uniform base pointer plus a 32-bit per-lane offset that does not
     // change from K-step to K-step (the K advance goes into the uniform part).
-    const uint8_t *a_src[A_LOADS];
+    const uint8_t *a_src[A_LOADS], *a_pix[A_LOADS];
     int a_koff[A_LOADS], a_hi0[A_LOADS], a_wi0[A_LOADS];
     uint32_t a_lane_off[A_LOADS], b_lane_off[B_LOADS];
     const uint8_t *const a_tile = g.A + m0 * g.lda;                 // A_MATRIX only
@@ -103,7 +103,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
         m = m < g.M ? m : g.M - 1;
         a_hi0[j] = a_wi0[j] = 0;
         a_lane_off[j] = 0;
-        a_src[j] = nullptr;
+        a_src[j] = a_pix[j] = nullptr;
         if constexpr (A_MODE == A_MATRIX) {
             a_lane_off[j] = (uint32_t)((m - m0) * g.lda) + (uint32_t)a_koff[j];
         } else {
@@ -113,6 +113,9 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
             a_src[j] = g.A + img * ((int64_t)g.H * g.W * g.Cin);
             a_hi0[j] = ho * g.sh - g.ph;
             a_wi0[j] = wo * g.sw - g.pw;
+            // address of tap (0,0), channel koff of this row's window (may lie outside the image:
+            // only dereferenced after the bounds check)
+            a_pix[j] = a_src[j] + ((int64_t)a_hi0[j] * g.W + a_wi0[j]) * g.Cin + a_koff[j];
         }
     }
 #pragma unroll
@@ -126,6 +129,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
     const uint8_t *fill_a = &g_fill_table.v[g.z_a][0];
     const ChannelParams<TN> cparams = load_channel_params<BN, WN, TN>(g, n0);
     const int ktiles = g.K / BK; // the dispatcher guarantees K % 64 == 0
+    const bool tap_uniform = A_MODE == A_CONV && (g.Cin % BK) == 0;
 
     // load number `idx` (0 .. LOADS-1) of K-step kt: A segments first, then B segments.
     // K-steps past the end fetch one constant 16-byte chunk instead (into a buffer nobody reads
@@ -142,7 +146,17 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
                 if (live) src = (a_tile + k0) + a_lane_off[j]; // K % 64 == 0: no tail
             } else {
                 const int k = k0 + a_koff[j];
-                if (live) {
+                if (live && tap_uniform) {
+                    // Cin % 64 == 0: the whole K-step lies inside one tap, so the tap decomposition
+                    // is wave-uniform (scalar unit) and only the bounds check is per lane
+                    const uint32_t tap = fast_div((uint32_t)k0, (uint32_t)g.Cin, g.magic_cin);
+                    const int ci0 = k0 - (int)tap * g.Cin;
+                    const uint32_t ta = fast_div(tap, (uint32_t)g.kw, g.magic_kw);
+                    const int tb = (int)tap - (int)ta * g.kw;
+                    const int64_t delta = ((int64_t)ta * g.W + tb) * g.Cin + ci0;
+                    const int hi = a_hi0[j] + (int)ta, wi = a_wi0[j] + tb;
+                    if ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W) src = a_pix[j] + delta;
+                } else if (live) {
                     const uint32_t tap = fast_div((uint32_t)k, (uint32_t)g.Cin, g.magic_cin);
                     const int ci = k - (int)tap * g.Cin;
                     const uint32_t ta = fast_div(tap, (uint32_t)g.kw, g.magic_kw);

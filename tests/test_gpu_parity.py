@@ -229,6 +229,10 @@ CONV_SHAPES = [
     (9, 7, 16, 8, 3, 2, 1, "relu", 8),
     (12, 12, 3, 32, 3, 2, 1, "relu6", 8),      # stem-like, Cin = 3 -> byte gather
     (20, 20, 3, 64, 7, 2, 3, "relu", 8),       # 7x7 stem
+    (23, 301, 3, 64, 7, 2, 3, "relu", 8),      # stem wider than one 128-pixel strip, odd sizes
+    (17, 40, 3, 20, 3, 2, 1, "relu6", 8),      # stem with a ragged channel count
+    (9, 140, 3, 32, 3, 1, 1, "none", 8),       # stem-like, stride 1
+    (30, 30, 1, 40, 7, 2, 3, "relu", 8),       # single input channel
     (14, 14, 32, 64, 1, 1, 0, "relu6", 8),     # pointwise
     (14, 14, 64, 96, 1, 2, 0, "none", 8),      # projection shortcut: 1x1 stride 2
     (8, 8, 24, 144, 1, 1, 0, "relu6", 8),      # Cin multiple of 8 only
@@ -296,7 +300,7 @@ def force_tile(monkeypatch):
     return _set
 
 
-@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma128x128s3", "dma256x64s3", "128x128", "64x64"])
+@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma256x64s3", "128x128", "64x64"])
 @pytest.mark.parametrize("M,N,K", [(128, 128, 64), (256, 256, 256), (300, 270, 192), (1000, 520, 1088), (17, 33, 16),
                                    (515, 700, 64), (700, 64, 128), (300, 50, 320)])
 def test_qgemm_forced_tiles_match_oracle(force_tile, tile, M, N, K):
@@ -311,7 +315,7 @@ def test_qgemm_forced_tiles_match_oracle(force_tile, tile, M, N, K):
         assert_same(got, want, f"qgemm tile={tile} {M}x{N}x{K} z_a={z_a}")
 
 
-@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma128x128s3", "dma256x64s3"])
+@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma256x64s3"])
 @pytest.mark.parametrize("shape", [(14, 14, 64, 96, 3, 1, 1), (15, 13, 64, 160, 3, 2, 1), (9, 9, 128, 40, 5, 1, 2),
                                    (16, 16, 128, 256, 1, 2, 0), (12, 12, 192, 300, 3, 1, 0), (20, 20, 64, 64, 3, 1, 1)],
                          ids=lambda s: "x".join(map(str, s)))
