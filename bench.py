@@ -58,14 +58,15 @@ def build_gemm_sweep(torch, qnn, workloads, synth):
         if (M, K) not in acts:
             acts[(M, K)] = _device_uint8(torch, (M, K), workloads.seed_for(2, 500 + len(acts)))
         w = weights[(N, K)]
-        cases.append(dict(M=M, N=N, K=K, A=acts[(M, K)], w=w, C=torch.empty((M, N), dtype=torch.uint8, device="cuda:0"),
-                          plan=qnn.qgemm_plan(M, N, K), ops=2.0 * M * N * K))
+        C = torch.empty((M, N), dtype=torch.uint8, device="cuda:0")
+        cases.append(dict(M=M, N=N, K=K, A=acts[(M, K)], w=w, C=C, plan=qnn.qgemm_plan(M, N, K), ops=2.0 * M * N * K,
+                          launch=qnn.prepare_qgemm(acts[(M, K)], w["z_a"], w["Bt"], w["mult"], w["shift"], w["z_out"],
+                                                   0, 255, C)))
     return cases
 
 
 def run_gemm(qnn, c):
-    w = c["w"]
-    qnn.qgemm(c["A"], w["z_a"], w["Bt"], w["mult"], w["shift"], w["z_out"], 0, 255, out=c["C"])
+    c["launch"]()  # arguments marshalled once (binding.prepare_qgemm); same C-ABI call as qnn.qgemm
 
 
 def time_gemm_sweep(torch, qnn, cases, steps, warmup):
@@ -73,18 +74,19 @@ def time_gemm_sweep(torch, qnn, cases, steps, warmup):
         for c in cases:
             run_gemm(qnn, c)
     torch.cuda.synchronize()
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in cases]
-          for _ in range(steps)]
+    # one HIP event between consecutive launches (on the stream the kernels run on): the time from
+    # event i to event i+1 is launch i's duration
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(cases) + 1)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(steps):
         for i, c in enumerate(cases):
-            ev[s][i][0].record()
+            ev[s][i].record()
             run_gemm(qnn, c)
-            ev[s][i][1].record()
+        ev[s][len(cases)].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    per_case_ms = [sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)) / steps for i in range(len(cases))]
+    per_case_ms = [sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(steps)) / steps for i in range(len(cases))]
     return elapsed, per_case_ms
 
 

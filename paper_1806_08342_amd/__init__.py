@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     load_library,
     pack_b,
     pack_int4,
+    prepare_qgemm,
     qadd,
     qadd_params,
     qconv2d,
@@ -28,7 +29,7 @@ from .binding import (  # noqa: F401
 )
 
 __all__ = [
-    "QnnError", "act_range", "choose_qparams", "dequantize", "library_path", "load_library", "pack_b", "pack_int4",
+    "QnnError", "act_range", "choose_qparams", "dequantize", "library_path", "load_library", "pack_b", "pack_int4", "prepare_qgemm",
     "qadd", "qadd_params", "qconv2d", "qdwconv2d", "qgemm", "qgemm_plan", "quantize", "quantize_multiplier",
     "quantize_multipliers", "quantize_weights", "requantize",
 ]

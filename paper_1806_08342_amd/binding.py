@@ -209,6 +209,35 @@ def qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, bias=None, weight_bit
     return Cm
 
 
+def prepare_qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, out, bias=None, weight_bits=8,
+                  b_layout=B_COLUMNS_CONTIGUOUS):
+    """Marshal the arguments of `qgemm` once and return a zero-argument callable that enqueues the
+    product on the current stream.  For launch-bound loops: the per-call Python work shrinks to one
+    foreign call.  The tensors must stay alive and unchanged in shape while the callable is used."""
+    torch = _torch()
+    M, K = A.shape
+    if weight_bits == 4:
+        N, ldb, bp = B.shape[0], B.shape[1] * 2, _dev(B, torch.uint8, "B")
+    elif b_layout == B_COLUMNS_CONTIGUOUS:
+        (N, ldb), bp = B.shape, _dev(B, torch.int8, "B")
+    else:
+        ldb = N = B.shape[1]
+        bp = _dev(B, torch.int8, "B")
+    fn = load_library().qnn_qgemm
+    args = (_dev(A, torch.uint8, "A"), K, z_a, bp, ldb, b_layout, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
+            _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max,
+            _dev(out, torch.uint8, "C"), N)
+    keep = (A, B, mult, shift, bias, out)
+    current_stream = torch.cuda.current_stream
+
+    def launch(_keep=keep):
+        rc = fn(*args, current_stream().cuda_stream)
+        if rc != 0:
+            _check("qnn_qgemm", rc)
+
+    return launch
+
+
 def pack_b(B_rows):
     """int8 [K,N] with contiguous rows -> int8 [N,K] (the layout qgemm runs fastest on)."""
     torch = _torch()

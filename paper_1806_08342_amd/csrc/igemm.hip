@@ -5,6 +5,7 @@
 #include <cstring>
 
 #include "igemm_dma.h"
+#include "skinny.h"
 #include "stemconv.h"
 
 namespace qnn {
@@ -121,6 +122,24 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
     const int64_t max_tiles = 0x7ffffff;
     g.small_acc = g.K <= 8192 ? 2 : (g.K <= 16384 ? 1 : 0); // |acc| <= K * 2^14
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
+    // few rows: weight-streaming kernel (one workgroup per 16 output columns, K split over 8 waves)
+    if (a_mode == A_MATRIX && g.M <= 64 && vec == 16 && (g.K % 64) == 0 && b_mode != B_INT8_ROWS &&
+        std::getenv("QNN_FORCE_TILE") == nullptr) {
+        const unsigned blocks = (unsigned)((g.N + 15) / 16);
+        const int mt = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : 4);
+        const bool i4 = b_mode == B_INT4;
+        if (mt == 1) {
+            if (i4) hipLaunchKernelGGL((skinny_gemm_kernel<1, true>), dim3(blocks), dim3(512), 0, s, g);
+            else hipLaunchKernelGGL((skinny_gemm_kernel<1, false>), dim3(blocks), dim3(512), 0, s, g);
+        } else if (mt == 2) {
+            if (i4) hipLaunchKernelGGL((skinny_gemm_kernel<2, true>), dim3(blocks), dim3(512), 0, s, g);
+            else hipLaunchKernelGGL((skinny_gemm_kernel<2, false>), dim3(blocks), dim3(512), 0, s, g);
+        } else {
+            if (i4) hipLaunchKernelGGL((skinny_gemm_kernel<4, true>), dim3(blocks), dim3(512), 0, s, g);
+            else hipLaunchKernelGGL((skinny_gemm_kernel<4, false>), dim3(blocks), dim3(512), 0, s, g);
+        }
+        return launch_status(hipGetLastError());
+    }
     const bool dma_ok = b_mode == B_INT8 && vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23);
     const TileConfig cfg = choose_tile(g.M, g.N, g.K, dma_ok);
     const int64_t bm = kTileM[cfg], bn = kTileN[cfg];
@@ -178,6 +197,7 @@ extern "C" {
 const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 0 || N <= 0 || K <= 0) return "";
+    if (M <= 64 && (K % 64) == 0) return "skinny16";
     // reported for the aligned int8 case (what the benchmark shapes are)
     return kTileNames[choose_tile(M, N, K, (K % 64) == 0)];
 }

@@ -330,12 +330,38 @@ def test_qconv2d_forced_dma_tiles_match_oracle(force_tile, tile, shape):
 
 
 def test_qgemm_default_plan_large_shape_sampled_rows():
-    # 4096 x 3072 x 512 selects the 256x256 pipelined tile by itself (192 tiles); compare whole rows
+    # 4096 x 4096 x 512 selects the 256x256 pipelined tile by itself (256 tiles); compare whole rows
     # at the top, in the middle and at the bottom of the matrix
-    M, N, K = 4096, 3072, 512
+    M, N, K = 4096, 4096, 512
     assert qnn.qgemm_plan(M, N, K) == "dma256x256"
     c = synth.gemm_case(M, N, K, workloads.seed_for(2, 77), oracle)
     got = host(qnn.qgemm(dev(c["A"]), c["z_a"], dev(c["Bt"]), dev(c["mult"]), dev(c["shift"]), c["z_out"], 0, 255))
     rows = np.r_[0:64, 2000:2064, 4032:4096]
     want = oracle.qgemm(c["A"][rows], c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
-    assert_same(got[rows], want, "qgemm 4096x3072x512 sampled rows")
+    assert_same(got[rows], want, "qgemm 4096x4096x512 sampled rows")
+
+
+# ------------------------------------------------------------ few-row (weight streaming) kernel
+
+@pytest.mark.parametrize("M,N,K", [(1, 16, 64), (5, 50, 192), (16, 33, 64), (17, 100, 1024), (33, 257, 576), (64, 48, 4096),
+                                   (48, 1000, 128)])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_qgemm_few_rows_matches_oracle(M, N, K, bits):
+    assert qnn.qgemm_plan(M, N, K) == "skinny16"
+    rng = np.random.default_rng(1500 + M + N + K + bits)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    if bits == 8:
+        Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+        B = Bt
+        real = 10 ** rng.uniform(-4.2, -3.2, N) / np.sqrt(K / 64.0)
+    else:
+        Bt = rng.integers(-8, 8, (N, K)).astype(np.int8)
+        B = oracle.pack_int4(Bt)
+        real = 10 ** rng.uniform(-3.0, -2.2, N) / np.sqrt(K / 64.0)
+    mult, shift = oracle.quantize_multipliers(real)
+    shift[0] = 0
+    bias = rng.integers(-20000, 20000, N).astype(np.int32)
+    for z_a in (0, 128, 201):
+        want = oracle.qgemm(A, z_a, B, mult, shift, 120, 5, 250, bias=bias, weight_bits=bits)
+        got = host(qnn.qgemm(dev(A), z_a, dev(B), dev(mult), dev(shift), 120, 5, 250, bias=dev(bias), weight_bits=bits))
+        assert_same(got, want, f"few-row qgemm {M}x{N}x{K} bits={bits} z_a={z_a}")
