@@ -47,13 +47,14 @@ enum TileConfig {
     TILE_DMA_128x128_S3,
     TILE_DMA_256x64_S3,
     TILE_DMA_256x128,
+    TILE_DMA_64x64,
     TILE_COUNT
 };
 
 static const char *const kTileNames[TILE_COUNT] = {"64x64",     "128x128",      "dma128x128",  "dma256x256",
-                                                   "dma256x64", "dma128x128s3", "dma256x64s3", "dma256x128"};
-static const int kTileM[TILE_COUNT] = {64, 128, 128, 256, 256, 128, 256, 256};
-static const int kTileN[TILE_COUNT] = {64, 128, 128, 256, 64, 128, 64, 128};
+                                                   "dma256x64", "dma128x128s3", "dma256x64s3", "dma256x128", "dma64x64"};
+static const int kTileM[TILE_COUNT] = {64, 128, 128, 256, 256, 128, 256, 256, 64};
+static const int kTileN[TILE_COUNT] = {64, 128, 128, 256, 64, 128, 64, 128, 64};
 
 // Tile choice.  `dma_ok`: int8 weights with contiguous columns, 16-byte aligned chunks, K % 64 == 0.
 //  - large products: 256x256 tiles (8 waves, 4 LDS stages, one workgroup per CU);
@@ -89,7 +90,9 @@ static TileConfig choose_tile(int64_t M, int64_t N, int64_t K, bool dma_ok)
                 if (pick == TILE_COUNT || cost < best) best = cost, pick = c.t;
             }
             if (pick != TILE_COUNT) return pick;
-            return N <= 64 ? TILE_DMA_256x64 : TILE_DMA_128x128; // under-filled chip: most tiles
+            // under-filled chip (less than one workgroup per CU): the K loop of a lone workgroup runs
+            // at the pace of its own latencies, not of the MFMA pipe, so many small tiles win
+            return TILE_DMA_64x64;
         }
     }
     return (N <= 64 || M <= 64) ? TILE_64x64 : TILE_128x128;
@@ -162,6 +165,8 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
         return launch_status(mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 256, 4, 2, A_CONV, 4>(g, s));
     case TILE_DMA_256x64:
         return launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 4>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 4>(g, s));
+    case TILE_DMA_64x64:
+        return launch_status(mat ? launch_dma<64, 64, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<64, 64, 2, 2, A_CONV, 4>(g, s));
     case TILE_DMA_256x128:
         return launch_status(mat ? launch_dma<256, 128, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 128, 4, 2, A_CONV, 4>(g, s));
     case TILE_DMA_256x64_S3:

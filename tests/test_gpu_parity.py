@@ -300,7 +300,7 @@ def force_tile(monkeypatch):
     return _set
 
 
-@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma256x64s3", "128x128", "64x64"])
+@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma64x64", "dma256x64s3", "128x128", "64x64"])
 @pytest.mark.parametrize("M,N,K", [(128, 128, 64), (256, 256, 256), (300, 270, 192), (1000, 520, 1088), (17, 33, 16),
                                    (515, 700, 64), (700, 64, 128), (300, 50, 320)])
 def test_qgemm_forced_tiles_match_oracle(force_tile, tile, M, N, K):
@@ -315,7 +315,7 @@ def test_qgemm_forced_tiles_match_oracle(force_tile, tile, M, N, K):
         assert_same(got, want, f"qgemm tile={tile} {M}x{N}x{K} z_a={z_a}")
 
 
-@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma256x64s3"])
+@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma64x64", "dma256x64s3"])
 @pytest.mark.parametrize("shape", [(14, 14, 64, 96, 3, 1, 1), (15, 13, 64, 160, 3, 2, 1), (9, 9, 128, 40, 5, 1, 2),
                                    (16, 16, 128, 256, 1, 2, 0), (12, 12, 192, 300, 3, 1, 0), (20, 20, 64, 64, 3, 1, 1)],
                          ids=lambda s: "x".join(map(str, s)))
