@@ -1,8 +1,10 @@
 // Entry points of the dense quantized layers: qnn_qgemm and qnn_qconv2d both run the
 // implicit-GEMM MFMA kernel of igemm.h; this file validates arguments, picks the tile
 // configuration and the staging vector width, and launches.
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "igemm_dma.h"
 #include "skinny.h"
@@ -56,21 +58,42 @@ static const char *const kTileNames[TILE_COUNT] = {"64x64",     "128x128",      
 static const int kTileM[TILE_COUNT] = {64, 128, 128, 256, 256, 128, 256, 256, 64};
 static const int kTileN[TILE_COUNT] = {64, 128, 128, 256, 64, 128, 64, 128, 64};
 
+constexpr size_t kWorkspaceBytes = (size_t)64 << 20; // split-K scratch block per device
+
+struct Plan {
+    TileConfig tile;
+    int splits; // > 1: split-K (128x128 and 64x64 pipelined tiles only)
+};
+
+static int env_int(const char *name, int fallback)
+{
+    const char *e = std::getenv(name);
+    return e ? std::atoi(e) : fallback;
+}
+
 // Tile choice.  `dma_ok`: int8 weights with contiguous columns, 16-byte aligned chunks, K % 64 == 0.
-//  - large products: 256x256 tiles (8 waves, 4 LDS stages, one workgroup per CU);
-//  - few output channels: 256x64 tiles; otherwise 128x128 tiles;
+//  - large products: 256x256 tiles (8 waves, 4 LDS stages, one workgroup per CU), or the
+//    256x128 / 128x128 / 256x64 tile that wastes the least work in partly filled rounds;
 //  - short K (<= 256): 3 LDS stages instead of 4, so that more workgroups fit a CU and one
-//    workgroup's epilogue overlaps another one's loads and MFMAs.
-static TileConfig choose_tile(int64_t M, int64_t N, int64_t K, bool dma_ok)
+//    workgroup's epilogue overlaps another one's loads and MFMAs;
+//  - products with too few output tiles for 256 CUs: split-K over 128x128 or 64x64 tiles.
+static Plan choose_plan(int64_t M, int64_t N, int64_t K, bool dma_ok)
 {
     if (const char *force = std::getenv("QNN_FORCE_TILE")) { // tuning aid: force one configuration
         for (int t = 0; t < TILE_COUNT; ++t)
-            if (std::strcmp(force, kTileNames[t]) == 0 && (t < TILE_DMA_128x128 || dma_ok)) return (TileConfig)t;
+            if (std::strcmp(force, kTileNames[t]) == 0 && (t < TILE_DMA_128x128 || dma_ok)) {
+                int splits = 1;
+                if (t == TILE_DMA_128x128 || t == TILE_DMA_64x64) splits = env_int("QNN_FORCE_SPLIT", 1);
+                const int ksteps = (int)(K / 64);
+                splits = splits < 1 ? 1 : (splits > ksteps ? ksteps : splits);
+                if ((int64_t)splits * M * N * 4 > (int64_t)kWorkspaceBytes) splits = 1;
+                return Plan{(TileConfig)t, splits};
+            }
     }
     if (dma_ok && M >= 128) {
         if (K <= 256) { // epilogue-bound: small tiles, several workgroups per CU
-            if (N <= 64) return TILE_DMA_256x64_S3;
-            if (N >= 128) return TILE_DMA_128x128_S3;
+            if (N <= 64) return Plan{TILE_DMA_256x64_S3, 1};
+            if (N >= 128) return Plan{TILE_DMA_128x128_S3, 1};
         } else {
             // pick the configuration with the least padded work: whole waves of workgroups over the
             // chip, weighted by the measured relative MFMA rate of each configuration
@@ -89,21 +112,87 @@ static TileConfig choose_tile(int64_t M, int64_t N, int64_t K, bool dma_ok)
                 const double cost = (double)waves * c.per_cu * bm * bn / c.rate; // time of `waves` rounds
                 if (pick == TILE_COUNT || cost < best) best = cost, pick = c.t;
             }
-            if (pick != TILE_COUNT) return pick;
-            // under-filled chip (less than one workgroup per CU): the K loop of a lone workgroup runs
-            // at the pace of its own latencies, not of the MFMA pipe, so many small tiles win
-            return TILE_DMA_64x64;
+            if (pick != TILE_COUNT) return Plan{pick, 1};
+            // Under-filled chip: a lone workgroup's K loop runs at the pace of its own latencies, not
+            // of the MFMA pipe, so many small tiles win.  With very few tiles and a long K, the K-steps
+            // of each tile are divided over several workgroups as well (measured break-even points:
+            // the second pass and the partial sums cost about as much as 16 K-steps).
+            const int ksteps = (int)(K / 64);
+            const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128), tiles64 = ((M + 63) / 64) * ((N + 63) / 64);
+            Plan plan{TILE_DMA_64x64, 1};
+            if (tiles128 <= 128 && tiles128 > 16 && ksteps >= 128) plan = Plan{TILE_DMA_128x128, tiles128 <= 64 ? 4 : 2};
+            else if (tiles64 <= 64 && ksteps >= 32) {
+                const int64_t want = (256 + tiles64 - 1) / tiles64, most = ksteps / 16;
+                plan.splits = (int)(want < most ? want : most);
+            }
+            while (plan.splits > 1 && (int64_t)plan.splits * M * N * 4 > (int64_t)kWorkspaceBytes) --plan.splits;
+            return plan;
         }
     }
-    return (N <= 64 || M <= 64) ? TILE_64x64 : TILE_128x128;
+    return Plan{(N <= 64 || M <= 64) ? TILE_64x64 : TILE_128x128, 1};
 }
 
-template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE>
-static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s)
+// Scratch memory of the split-K path: one fixed block per device, allocated at the first call
+// that needs it and kept until the process ends.  Calls on different streams are ordered with
+// an event (the block is shared); while a stream is being captured into a graph no event is
+// recorded, and no block is allocated if none exists yet (the caller then runs unsplit).
+constexpr int kMaxDevices = 64;
+struct Workspace {
+    int32_t *ptr = nullptr;
+    hipEvent_t done = nullptr;
+    hipStream_t last = nullptr;
+    bool used = false;
+};
+static Workspace g_workspace[kMaxDevices];
+static std::mutex g_workspace_mutex;
+
+static bool stream_is_capturing(hipStream_t s)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return st != hipStreamCaptureStatusNone;
+}
+
+// the device's scratch block, made safe to overwrite from stream `s`; nullptr if unavailable
+static int32_t *acquire_workspace(hipStream_t s, bool capturing)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_workspace_mutex);
+    Workspace &w = g_workspace[dev];
+    if (!w.ptr) {
+        if (capturing) return nullptr; // allocation is not allowed during capture
+        if (hipMalloc(reinterpret_cast<void **>(&w.ptr), kWorkspaceBytes) != hipSuccess ||
+            hipEventCreateWithFlags(&w.done, hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            if (w.ptr) (void)hipFree(w.ptr);
+            w.ptr = nullptr;
+            return nullptr;
+        }
+    }
+    if (!capturing && w.used && w.last != s) (void)hipStreamWaitEvent(s, w.done, 0);
+    return w.ptr;
+}
+
+static void release_workspace(hipStream_t s, bool capturing)
+{
+    if (capturing) return;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return;
+    std::lock_guard<std::mutex> lock(g_workspace_mutex);
+    Workspace &w = g_workspace[dev];
+    if (hipEventRecord(w.done, s) == hipSuccess) w.used = true, w.last = s;
+}
+
+template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false>
+static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = SplitK{1, 0, nullptr})
 {
     constexpr int kStages = NSTAGE * (BM + BN) * 64, kOut = BM * (BN + 16) + 4 * WM * WN * (BN / WN / 32) * 64;
     constexpr int kLds = kStages > kOut ? kStages : kOut; // operand ring, reused for the output tile + column sums
-    auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE>;
+    auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE, SPLIT>;
     static bool configured = false; // per instantiation
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -112,10 +201,16 @@ static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s)
         configured = true;
     }
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (g.N + BN - 1) / BN;
-    const int64_t tiles = (int64_t)tiles_m * tiles_n;
-    const int per_xcd = (int)((tiles + 7) / 8);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(per_xcd * 8)), dim3(WM * WN * 64), kLds, s, g, tiles_m, tiles_n, per_xcd);
-    return hipGetLastError();
+    const int64_t work = (int64_t)tiles_m * tiles_n * sk.splits;
+    const int per_xcd = (int)((work + 7) / 8);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(per_xcd * 8)), dim3(WM * WN * 64), kLds, s, g, tiles_m, tiles_n, per_xcd, sk);
+    hipError_t e = hipGetLastError();
+    if (SPLIT && e == hipSuccess) {
+        const int64_t threads = g.M * (((int64_t)g.N + 3) / 4);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, g, sk);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 // Shared back end.  `vec` is the widest staging vector (in k elements) that the alignment
@@ -143,9 +238,29 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
         }
         return launch_status(hipGetLastError());
     }
+    const bool mat_or_conv = a_mode == A_MATRIX;
     const bool dma_ok = b_mode == B_INT8 && vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23);
-    const TileConfig cfg = choose_tile(g.M, g.N, g.K, dma_ok);
+    const Plan plan = choose_plan(g.M, g.N, g.K, dma_ok);
+    const TileConfig cfg = plan.tile;
     const int64_t bm = kTileM[cfg], bn = kTileN[cfg];
+    if (plan.splits > 1) {
+        const bool capturing = stream_is_capturing(s);
+        SplitK sk;
+        sk.ksteps = (g.K / 64 + plan.splits - 1) / plan.splits;
+        sk.splits = (g.K / 64 + sk.ksteps - 1) / sk.ksteps; // no empty K range
+        sk.partial = acquire_workspace(s, capturing);
+        if (sk.partial && sk.splits > 1) {
+            hipError_t e;
+            if (cfg == TILE_DMA_128x128)
+                e = mat_or_conv ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, true>(g, s, sk)
+                                : launch_dma<128, 128, 2, 2, A_CONV, 4, true>(g, s, sk);
+            else
+                e = mat_or_conv ? launch_dma<64, 64, 2, 2, A_MATRIX, 4, true>(g, s, sk)
+                                : launch_dma<64, 64, 2, 2, A_CONV, 4, true>(g, s, sk);
+            release_workspace(s, capturing);
+            return launch_status(e);
+        }
+    }
     if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return QNN_EINVAL;
     const bool mat = a_mode == A_MATRIX;
     switch (cfg) {
@@ -204,7 +319,11 @@ const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K)
     if (M <= 0 || N <= 0 || K <= 0) return "";
     if (M <= 64 && (K % 64) == 0) return "skinny16";
     // reported for the aligned int8 case (what the benchmark shapes are)
-    return kTileNames[choose_tile(M, N, K, (K % 64) == 0)];
+    const Plan plan = choose_plan(M, N, K, (K % 64) == 0);
+    if (plan.splits <= 1) return kTileNames[plan.tile];
+    static thread_local char name[48];
+    std::snprintf(name, sizeof name, "%s/k%d", kTileNames[plan.tile], plan.splits);
+    return name;
 }
 
 qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,

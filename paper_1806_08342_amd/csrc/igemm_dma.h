@@ -55,9 +55,19 @@ __device__ __forceinline__ void dma16(const uint8_t *src, uint8_t *lds_wave_base
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
 
-template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE>
+// Split-K: when a product has too few output tiles to fill the chip, the K-steps of every tile
+// are divided over `splits` workgroups.  Each writes its int32 partial sums (with its share of
+// the zero-point correction) to plane `split` of `partial` ([splits][M][N]); a second kernel
+// adds the planes and applies bias, rescale and clamp.  Integer sums: any order, same bits.
+struct SplitK {
+    int splits;       // workgroups per output tile (1: no split)
+    int ksteps;       // K-steps of 64 per workgroup (the last one may get fewer, never zero)
+    int32_t *partial; // device memory, splits * M * N int32
+};
+
+template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false>
 __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs g, const int tiles_m, const int tiles_n,
-                                                                const int per_xcd)
+                                                                const int per_xcd, const SplitK sk)
 {
     constexpr int NW = WM * WN, NT = NW * 64, BK = 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -72,8 +82,13 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
     // with its own L2; give every XCD one contiguous band of the tile sequence, and walk the
     // band in groups of 4 tile rows so that concurrently running tiles share A rows / B columns.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int64_t lin = (int64_t)xcd * per_xcd + slot;
-    if (slot >= per_xcd || lin >= (int64_t)tiles_m * tiles_n) return;
+    const int64_t tiles_total = (int64_t)tiles_m * tiles_n;
+    int64_t lin = (int64_t)xcd * per_xcd + slot;
+    if (slot >= per_xcd || lin >= tiles_total * (SPLIT ? sk.splits : 1)) return;
+    // split-K: the workgroups of one K range are neighbours (they share the A rows / B columns
+    // of that range in their XCD's L2)
+    const int split = SPLIT ? (int)(lin / tiles_total) : 0;
+    lin -= split * tiles_total;
     constexpr int GROUP = 4;
     const int64_t group_span = (int64_t)GROUP * tiles_n;
     const int first_row = (int)(lin / group_span) * GROUP;
@@ -127,8 +142,11 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
         b_lane_off[j] = (uint32_t)((int64_t)(n - n0) * g.ldb) + (uint32_t)b_koff;
     }
     const uint8_t *fill_a = &g_fill_table.v[g.z_a][0];
-    const ChannelParams<TN> cparams = load_channel_params<BN, WN, TN>(g, n0);
-    const int ktiles = g.K / BK; // the dispatcher guarantees K % 64 == 0
+    ChannelParams<TN> cparams = {};
+    if constexpr (!SPLIT) cparams = load_channel_params<BN, WN, TN>(g, n0);
+    // K-steps [kt_first, kt_first + ktiles) of the product; the dispatcher guarantees K % 64 == 0
+    const int kt_first = SPLIT ? split * sk.ksteps : 0;
+    const int ktiles = SPLIT ? ((g.K / BK - kt_first) < sk.ksteps ? (g.K / BK - kt_first) : sk.ksteps) : g.K / BK;
     const bool tap_uniform = A_MODE == A_CONV && (g.Cin % BK) == 0;
 
     // load number `idx` (0 .. LOADS-1) of K-step kt: A segments first, then B segments.
@@ -138,7 +156,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
     auto issue_load = [&](int kt, int idx) {
         uint8_t *stage = smem + (kt % NSTAGE) * STAGE_BYTES;
         const bool live = kt < ktiles; // wave-uniform
-        const int k0 = kt * BK;
+        const int k0 = (kt_first + kt) * BK;
         if (idx < A_LOADS) {
             const int j = idx;
             const uint8_t *src = fill_a;
@@ -295,7 +313,70 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
             }
         }
     }
-    igemm_epilogue<BM, BN, WM, WN, false>(g, acc, colsum, cparams, smem, m0, n0);
+    if constexpr (SPLIT) {
+        // partial sums straight from the accumulator layout: per register, 32 lanes write 32
+        // consecutive int32 of one row (128-byte runs)
+        int32_t *plane = sk.partial + (int64_t)split * g.M * g.N;
+#pragma clang loop unroll(full)
+        for (int j = 0; j < TN; ++j) {
+            const int32_t corr = (128 - g.z_a) * (colsum[j] + __shfl_xor(colsum[j], 32));
+            const int col = n0 + wave_n * WTN + j * 32 + frag_row;
+#pragma clang loop unroll(full)
+            for (int i = 0; i < TM; ++i)
+#pragma clang loop unroll(full)
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t row = m0 + wave_m * WTM + i * 32 + 8 * (r >> 2) + 4 * frag_half + (r & 3);
+                    if (row < g.M && col < g.N) plane[row * g.N + col] = acc[i][j][r] + corr;
+                }
+        }
+    } else {
+        igemm_epilogue<BM, BN, WM, WN, false>(g, acc, colsum, cparams, smem, m0, n0);
+    }
+}
+
+// Second pass of split-K: out[m][n] = clamp(z_out + RESCALE(sum_s partial[s][m][n] + bias[n])).
+// One thread per 4 consecutive columns of one row.
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const IgemmArgs g, const SplitK sk)
+{
+    const int64_t groups = ((int64_t)g.N + 3) / 4;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= g.M * groups) return;
+    const int64_t m = idx / groups;
+    const int n = (int)(idx - m * groups) * 4;
+    const int64_t plane = g.M * g.N;
+    const int32_t *p = sk.partial + m * g.N + n;
+    int32_t a[4] = {0, 0, 0, 0};
+    if ((g.N & 3) == 0) { // whole, 16-byte aligned groups
+        for (int s = 0; s < sk.splits; ++s) {
+            const i32x4 v = __builtin_nontemporal_load(reinterpret_cast<const i32x4 *>(p + s * plane));
+            a[0] += v.x, a[1] += v.y, a[2] += v.z, a[3] += v.w;
+        }
+    } else {
+        for (int s = 0; s < sk.splits; ++s)
+            for (int e = 0; e < 4 && n + e < g.N; ++e) a[e] += p[s * plane + e];
+    }
+    const int32_t act_lo = g.lo_rel + g.z_out, act_hi = g.hi_rel + g.z_out;
+    uint32_t packed = 0;
+    int valid = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (n + e >= g.N) break;
+        const int32_t b = g.bias ? g.bias[n + e] : 0, mu = g.mult[n + e], sf = g.shift[n + e];
+        int32_t y;
+        if (g.small_acc >= 2 && sf >= 1 && sf <= 21 && b > -(1 << 27) && b < (1 << 27)) {
+            y = med3_i32(rescale_fused(a[e], make_fused(mu, sf, b, g.z_out)), act_lo, act_hi);
+        } else {
+            y = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(a[e] + b, make_rescale(mu, sf))) + g.z_out;
+        }
+        packed |= (uint32_t)y << (8 * e);
+        ++valid;
+    }
+    uint8_t *dst = g.C + m * g.ldc + n;
+    if (valid == 4 && (reinterpret_cast<uintptr_t>(dst) & 3) == 0) {
+        *reinterpret_cast<uint32_t *>(dst) = packed;
+    } else {
+        for (int e = 0; e < valid; ++e) dst[e] = (uint8_t)(packed >> (8 * e));
+    }
 }
 
 } // namespace qnn

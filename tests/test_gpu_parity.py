@@ -329,6 +329,73 @@ def test_qconv2d_forced_dma_tiles_match_oracle(force_tile, tile, shape):
         _run_conv(c, f"conv tile={tile} {shape} z_x={z_x}")
 
 
+# ------------------------------------------------------------ split-K (few output tiles, long K)
+
+@pytest.mark.parametrize("tile", ["dma128x128", "dma64x64"])
+@pytest.mark.parametrize("splits", [2, 3, 7])
+@pytest.mark.parametrize("M,N,K", [(128, 128, 448), (300, 270, 640), (131, 66, 1088), (256, 63, 8192)])
+def test_qgemm_split_k_matches_oracle(force_tile, monkeypatch, tile, splits, M, N, K):
+    force_tile(tile)
+    monkeypatch.setenv("QNN_FORCE_SPLIT", str(splits))
+    rng = np.random.default_rng(1600 + M + N + K + splits)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    bias, mult, shift = _gemm_params(rng, N, K)
+    shift[0] = 0      # a column on the general rescale path
+    mult[N // 2], shift[N // 2] = 2 ** 30, -1
+    for z_a in (0, 128, 255):
+        want = oracle.qgemm(A, z_a, Bt, mult, shift, 100, 3, 251, bias=bias)
+        got = host(qnn.qgemm(dev(A), z_a, dev(Bt), dev(mult), dev(shift), 100, 3, 251, bias=dev(bias)))
+        assert_same(got, want, f"split-K qgemm tile={tile} splits={splits} {M}x{N}x{K} z_a={z_a}")
+
+
+@pytest.mark.parametrize("tile", ["dma128x128", "dma64x64"])
+@pytest.mark.parametrize("shape", [(14, 14, 64, 96, 3, 1, 1), (9, 9, 128, 40, 5, 1, 2), (7, 7, 512, 130, 3, 1, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_qconv2d_split_k_matches_oracle(force_tile, monkeypatch, tile, shape):
+    force_tile(tile)
+    monkeypatch.setenv("QNN_FORCE_SPLIT", "4")
+    H, W, Cin, Cout, k, s, p = shape
+    layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu6")
+    c = synth.conv_case(layer, 3, 1700 + sum(shape), oracle)
+    for z_x in (c["z_x"], 0):
+        c["z_x"] = z_x
+        _run_conv(c, f"split-K conv tile={tile} {shape} z_x={z_x}")
+
+
+def test_qgemm_default_plan_splits_k_when_tiles_are_few():
+    # 256 x 512 x 8192: 8 tiles of 128x128 would leave most of the chip idle; the plan divides K
+    M, N, K = 256, 512, 8192
+    plan = qnn.qgemm_plan(M, N, K)
+    assert "/k" in plan, plan
+    c = synth.gemm_case(M, N, K, workloads.seed_for(2, 78), oracle)
+    for _ in range(2):  # the second call reuses the scratch block
+        got = host(qnn.qgemm(dev(c["A"]), c["z_a"], dev(c["Bt"]), dev(c["mult"]), dev(c["shift"]), c["z_out"], 0, 255))
+    want = oracle.qgemm(c["A"], c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
+    assert_same(got, want, "qgemm 256x512x8192 default split-K plan")
+
+
+def test_qgemm_split_k_on_two_streams_shares_the_scratch_block():
+    import torch
+    M, N, K = 256, 256, 4096
+    assert "/k" in qnn.qgemm_plan(M, N, K)
+    cases = [synth.gemm_case(M, N, K, workloads.seed_for(2, 80 + i), oracle) for i in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    devs = [{k: dev(c[k]) for k in ("A", "Bt", "mult", "shift")} for c in cases]
+    outs = [[], []]
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for i, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                d, c = devs[i], cases[i]
+                outs[i].append(qnn.qgemm(d["A"], c["z_a"], d["Bt"], d["mult"], d["shift"], c["z_out"], 0, 255))
+    torch.cuda.synchronize()
+    for i, c in enumerate(cases):
+        want = oracle.qgemm(c["A"], c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
+        for rep, o in enumerate(outs[i]):
+            assert_same(host(o), want, f"split-K on stream {i}, call {rep}")
+
+
 def test_qgemm_default_plan_large_shape_sampled_rows():
     # 4096 x 4096 x 512 selects the 256x256 pipelined tile by itself (256 tiles); compare whole rows
     # at the top, in the middle and at the bottom of the matrix
