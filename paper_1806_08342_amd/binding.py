@@ -101,6 +101,16 @@ def _dev(t, dtype, name):
     return C.c_void_p(t.data_ptr())
 
 
+def _dev_rows(t, dtype, name):
+    """Pointer and row pitch (in elements) of a 2-D device tensor whose rows are contiguous but may be
+    spaced apart (a column slice of a wider matrix)."""
+    torch = _torch()
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.dim() == 2 and
+            (t.shape[1] == 1 or t.stride(1) == 1) and (t.shape[0] == 1 or t.stride(0) >= t.shape[1])):
+        raise TypeError(f"{name}: expected a 2-D device tensor of {dtype} with contiguous rows")
+    return C.c_void_p(t.data_ptr()), (t.stride(0) if t.shape[0] > 1 else t.shape[1])
+
+
 # ------------------------------------------------------------------ host helpers
 
 def choose_qparams(xmin, xmax, bits=8):
@@ -188,7 +198,7 @@ def requantize(acc, mult, shift, per_channel, z_out, act_min, act_max, out=None)
 
 def qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8,
           b_layout=B_COLUMNS_CONTIGUOUS, out=None):
-    """A: uint8 [M,K].  B: int8 [N,K] (columns contiguous), int8 [K,N] (rows contiguous), or uint8
+    """A: uint8 [M,K] (rows may be spaced apart: a column slice of a wider matrix; same for `out`).  B: int8 [N,K] (columns contiguous), int8 [K,N] (rows contiguous), or uint8
     [N,K/2] nibble-packed when weight_bits == 4.  Returns uint8 [M,N]."""
     torch = _torch()
     M, K = A.shape
@@ -202,10 +212,12 @@ def qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, bias=None, weight_bit
         ldb = N = B.shape[1]
         bp = _dev(B, torch.int8, "B")
     Cm = torch.empty((M, N), dtype=torch.uint8, device=A.device) if out is None else out
+    ap, lda = _dev_rows(A, torch.uint8, "A")
+    cp, ldc = _dev_rows(Cm, torch.uint8, "C")
     _check("qnn_qgemm", load_library().qnn_qgemm(
-        _dev(A, torch.uint8, "A"), K, z_a, bp, ldb, b_layout, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
+        ap, lda, z_a, bp, ldb, b_layout, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
         _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max,
-        _dev(Cm, torch.uint8, "C"), N, _stream()))
+        cp, ldc, _stream()))
     return Cm
 
 
@@ -224,9 +236,10 @@ def prepare_qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, out, bias=Non
         ldb = N = B.shape[1]
         bp = _dev(B, torch.int8, "B")
     fn = load_library().qnn_qgemm
-    args = (_dev(A, torch.uint8, "A"), K, z_a, bp, ldb, b_layout, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
-            _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max,
-            _dev(out, torch.uint8, "C"), N)
+    ap, lda = _dev_rows(A, torch.uint8, "A")
+    cp, ldc = _dev_rows(out, torch.uint8, "C")
+    args = (ap, lda, z_a, bp, ldb, b_layout, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
+            _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max, cp, ldc)
     keep = (A, B, mult, shift, bias, out)
     current_stream = torch.cuda.current_stream
 

@@ -7,6 +7,7 @@
 #include <mutex>
 
 #include "igemm_dma.h"
+#include "shortk.h"
 #include "skinny.h"
 #include "stemconv.h"
 
@@ -213,6 +214,69 @@ static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = Spli
     return e;
 }
 
+// Short reduction (K <= 256): weight-stationary kernel of shortk.h.  Returns false when the
+// operands do not meet its alignment rules (the caller then takes the general route).
+template <int KS, bool INT4, int VEC> static void launch_shortk_one(const ShortKArgs &a, unsigned blocks, hipStream_t s)
+{
+    constexpr int NB = KS <= 4 ? 4 : 2;
+    // weights: 16-byte loads when every 16-element piece of a column is 16-byte aligned, else dwords
+    const bool b16 = !INT4 && aligned_to(a.g.B, 16) && (a.g.ldb % 16) == 0 && (a.g.K % 16) == 0;
+    if (b16) hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 16>), dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 4>), dim3(blocks), dim3(256), 0, s, a);
+}
+
+template <bool INT4, int VEC> static void launch_shortk_ks(const ShortKArgs &a, int ks, unsigned blocks, hipStream_t s)
+{
+    if (ks <= 1) launch_shortk_one<1, INT4, VEC>(a, blocks, s);
+    else if (ks <= 2) launch_shortk_one<2, INT4, VEC>(a, blocks, s);
+    else if (ks <= 4) launch_shortk_one<4, INT4, VEC>(a, blocks, s);
+    else launch_shortk_one<8, INT4, VEC>(a, blocks, s);
+}
+
+static bool shortk_eligible(const IgemmArgs &g, int b_mode, bool strided)
+{
+    if (g.K > 256 || (g.K % 8) != 0 || g.M <= 64 || g.M >= 0x7fffffe0 || b_mode == B_INT8_ROWS) return false;
+    if (std::getenv("QNN_FORCE_TILE") != nullptr || std::getenv("QNN_NO_SHORTK") != nullptr) return false;
+    const int64_t row_pitch = strided ? g.Cin : g.lda;
+    if (!aligned_to(g.A, 8) || (row_pitch % 8) != 0) return false;
+    if (!aligned_to(g.B, 4) || (g.ldb % 8) != 0) return false;
+    return true;
+}
+
+static qnn_status launch_shortk(IgemmArgs &g, int b_mode, bool strided, hipStream_t s)
+{
+    g.small_acc = 2; // K <= 256: |acc| <= 2^22
+    g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
+    const int ks = (g.K + 31) / 32;
+    const int nb = ks <= 4 ? 4 : 2;
+    ShortKArgs a = {};
+    a.g = g;
+    a.strided = strided ? 1 : 0;
+    a.col_groups = (g.N + 32 * nb - 1) / (32 * nb);
+    const int64_t row_blocks = (g.M + 31) / 32;
+    // as many waves as stay resident together (3 per SIMD for K <= 32, else 2, on 256 CUs), spread
+    // over the column groups, then trimmed so that every wave walks the same number of row blocks
+    const int64_t resident = 256 * 4 * (ks <= 1 ? 3 : 2);
+    int64_t walkers = resident / a.col_groups;
+    walkers = walkers < 1 ? 1 : (walkers > row_blocks ? row_blocks : walkers);
+    const int64_t per_walker = (row_blocks + walkers - 1) / walkers;
+    walkers = (row_blocks + per_walker - 1) / per_walker;
+    a.walkers = (int)walkers;
+    const int64_t waves = walkers * a.col_groups;
+    if (waves > 0x7fffffff) return QNN_EINVAL;
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    const int64_t row_pitch = strided ? g.Cin : g.lda;
+    const bool v16 = aligned_to(g.A, 16) && (row_pitch % 16) == 0 && (g.K % 16) == 0;
+    if (b_mode == B_INT4) {
+        if (v16) launch_shortk_ks<true, 16>(a, ks, blocks, s);
+        else launch_shortk_ks<true, 8>(a, ks, blocks, s);
+    } else {
+        if (v16) launch_shortk_ks<false, 16>(a, ks, blocks, s);
+        else launch_shortk_ks<false, 8>(a, ks, blocks, s);
+    }
+    return launch_status(hipGetLastError());
+}
+
 // Shared back end.  `vec` is the widest staging vector (in k elements) that the alignment
 // of A, B and K allows.
 static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s)
@@ -220,6 +284,7 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
     const int64_t max_tiles = 0x7ffffff;
     g.small_acc = g.K <= 8192 ? 2 : (g.K <= 16384 ? 1 : 0); // |acc| <= K * 2^14
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
+    if (a_mode == A_MATRIX && shortk_eligible(g, b_mode, false)) return launch_shortk(g, b_mode, false, s);
     // few rows: weight-streaming kernel (one workgroup per 16 output columns, K split over 8 waves)
     if (a_mode == A_MATRIX && g.M <= 64 && vec == 16 && (g.K % 64) == 0 && b_mode != B_INT8_ROWS &&
         std::getenv("QNN_FORCE_TILE") == nullptr) {
@@ -317,6 +382,8 @@ extern "C" {
 const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 0 || N <= 0 || K <= 0) return "";
+    if (M > 64 && K <= 256 && (K % 8) == 0 && std::getenv("QNN_FORCE_TILE") == nullptr && std::getenv("QNN_NO_SHORTK") == nullptr)
+        return "shortk";
     if (M <= 64 && (K % 64) == 0) return "skinny16";
     // reported for the aligned int8 case (what the benchmark shapes are)
     const Plan plan = choose_plan(M, N, K, (K % 64) == 0);
@@ -405,6 +472,8 @@ qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z
         g.lda = Cin;
         return run_igemm(g, A_MATRIX, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
     }
+    if (kh == 1 && kw == 1 && pad_h == 0 && pad_w == 0 && shortk_eligible(g, b_mode, true)) // strided 1x1: rows are pixels
+        return launch_shortk(g, b_mode, true, as_stream(stream));
     // pieces must not straddle a tap: the vector width divides Cin
     return run_igemm(g, A_CONV, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
 }

@@ -329,6 +329,87 @@ def test_qconv2d_forced_dma_tiles_match_oracle(force_tile, tile, shape):
         _run_conv(c, f"conv tile={tile} {shape} z_x={z_x}")
 
 
+# ------------------------------------------------------------ short reduction (K <= 256), weight-stationary kernel
+
+def _short_k_params(rng, N, K, bits):
+    real = 10 ** rng.uniform(-4.2, -3.2, N) / np.sqrt(K / 64.0) * (1.0 if bits == 8 else 14.0)
+    mult, shift = oracle.quantize_multipliers(real)
+    bias = rng.integers(-20000, 20000, N).astype(np.int32)
+    return bias, mult, shift
+
+
+@pytest.mark.parametrize("K", [8, 16, 24, 32, 40, 64, 96, 128, 136, 144, 192, 256])
+@pytest.mark.parametrize("M,N", [(65, 1), (100, 16), (999, 33), (300, 96), (1000, 130), (4097, 256), (200, 300)])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_qgemm_short_k_matches_oracle(M, N, K, bits):
+    assert qnn.qgemm_plan(M, N, K) == "shortk"
+    rng = np.random.default_rng(1800 + M + N + K + bits)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    if bits == 8:
+        Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+        B = Bt
+    else:
+        Bt = rng.integers(-8, 8, (N, K)).astype(np.int8)
+        B = oracle.pack_int4(Bt)
+    bias, mult, shift = _short_k_params(rng, N, K, bits)
+    for z_a in (0, 128, 255):
+        want = oracle.qgemm(A, z_a, B, mult, shift, 120, 5, 250, bias=bias, weight_bits=bits)
+        got = host(qnn.qgemm(dev(A), z_a, dev(B), dev(mult), dev(shift), 120, 5, 250, bias=dev(bias), weight_bits=bits))
+        assert_same(got, want, f"short-K qgemm {M}x{N}x{K} bits={bits} z_a={z_a}")
+
+
+@pytest.mark.parametrize("K,N", [(64, 70), (160, 40), (256, 129)])
+def test_qgemm_short_k_general_rescale_columns(K, N):
+    # columns whose multiplier / shift / bias fall outside the fast form: the whole wave takes the general path
+    M = 500
+    rng = np.random.default_rng(1900 + K + N)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    bias, mult, shift = _short_k_params(rng, N, K, 8)
+    shift[0] = 0
+    mult[1], shift[1] = 2 ** 30, -1          # multiplier 1: left shift
+    mult[2], shift[2] = 2 ** 30 + 12345, -3
+    shift[3] = 25
+    shift[N - 1] = 31
+    bias[5] = 2 ** 28
+    bias[6] = -(2 ** 28)
+    for z_a in (3, 128):
+        want = oracle.qgemm(A, z_a, Bt, mult, shift, 7, 0, 255, bias=bias)
+        got = host(qnn.qgemm(dev(A), z_a, dev(Bt), dev(mult), dev(shift), 7, 0, 255, bias=dev(bias)))
+        assert_same(got, want, f"short-K general rescale {M}x{N}x{K} z_a={z_a}")
+
+
+@pytest.mark.parametrize("K,pad_a,pad_c", [(64, 16, 16), (64, 8, 3), (96, 24, 0), (128, 0, 5), (40, 8, 1)])
+def test_qgemm_short_k_spaced_rows(K, pad_a, pad_c):
+    # A and C are column slices of wider matrices (lda > K, ldc > N); pad 8 leaves rows only 8-byte aligned
+    import torch
+    M, N = 333, 72
+    rng = np.random.default_rng(2000 + K + pad_a + pad_c)
+    wide_a = rng.integers(0, 256, (M, K + pad_a)).astype(np.uint8)
+    A = wide_a[:, :K]
+    Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    bias, mult, shift = _short_k_params(rng, N, K, 8)
+    wide_c = torch.full((M, N + pad_c), 77, dtype=torch.uint8, device="cuda")
+    want = oracle.qgemm(np.ascontiguousarray(A), 100, Bt, mult, shift, 128, 0, 255, bias=bias)
+    qnn.qgemm(dev(wide_a)[:, :K], 100, dev(Bt), dev(mult), dev(shift), 128, 0, 255, bias=dev(bias), out=wide_c[:, :N])
+    got = host(wide_c)
+    assert_same(got[:, :N], want, f"short-K spaced rows K={K}")
+    assert (got[:, N:] == 77).all(), "columns outside the output slice were written"
+
+
+@pytest.mark.parametrize("shape", [(28, 28, 64, 160, 1, 2, 0), (15, 13, 128, 96, 1, 2, 0), (9, 9, 256, 40, 1, 3, 0),
+                                   (14, 14, 96, 24, 1, 1, 0), (14, 14, 144, 32, 1, 1, 0), (7, 7, 24, 144, 1, 1, 0)],
+                         ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("bits", [8, 4])
+def test_qconv2d_pointwise_short_k_matches_oracle(shape, bits):
+    H, W, Cin, Cout, k, s, p = shape
+    layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu6", weight_bits=bits)
+    c = synth.conv_case(layer, 5, 2100 + sum(shape) + bits, oracle)
+    for z_x in (c["z_x"], 0, 255):
+        c["z_x"] = z_x
+        _run_conv(c, f"pointwise short-K conv {shape} bits={bits} z_x={z_x}")
+
+
 # ------------------------------------------------------------ split-K (few output tiles, long K)
 
 @pytest.mark.parametrize("tile", ["dma128x128", "dma64x64"])
