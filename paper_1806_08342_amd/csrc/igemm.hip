@@ -107,10 +107,12 @@ static Plan choose_plan(int64_t M, int64_t N, int64_t K, bool dma_ok)
                 const int bm = kTileM[c.t], bn = kTileN[c.t];
                 if (N < bn / 2 || M < bm / 2) continue; // mostly empty tiles
                 const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-                if (tiles < 224) continue; // would leave CUs idle: smaller tiles are better then
+                if (tiles < 160) continue; // would leave too many CUs idle: smaller tiles are better then
                 const int64_t slots = 256 * c.per_cu;
                 const int64_t waves = (tiles + slots - 1) / slots;
-                const double cost = (double)waves * c.per_cu * bm * bn / c.rate; // time of `waves` rounds
+                // time of `waves` rounds; up to 256 tiles every tile has a CU of its own and runs at
+                // the full rate of its configuration
+                const double cost = tiles <= 256 ? (double)bm * bn / c.rate : (double)waves * c.per_cu * bm * bn / c.rate;
                 if (pick == TILE_COUNT || cost < best) best = cost, pick = c.t;
             }
             if (pick != TILE_COUNT) return Plan{pick, 1};

@@ -162,15 +162,17 @@ __global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const Sh
     };
 
     // lane-invariant parts of the LDS and global addresses of the output tile
-    int st_lds[NB], st_row[NB], st_col[NB];
+    int st_lds[NB], st_row[NB];
+    bool st_col_ok[NB];
     int64_t st_off[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int idx = i * 64 + lane;
         st_row[i] = idx / (2 * NB);
-        st_col[i] = n0 + (idx % (2 * NB)) * 16;
+        const int col0 = n0 + (idx % (2 * NB)) * 16;
+        st_col_ok[i] = col0 < g.N;
         st_lds[i] = st_row[i] * PITCH + (idx % (2 * NB)) * 16;
-        st_off[i] = (int64_t)st_row[i] * g.ldc + st_col[i];
+        st_off[i] = (int64_t)st_row[i] * g.ldc + col0;
     }
     const int put_base = (4 * fhalf + (lane & 3)) * PITCH + (frow & ~3);
     // whole 16-byte chunks only, all aligned: one store per lane and chunk, no tail handling
@@ -189,10 +191,15 @@ __global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const Sh
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         uint8_t *const c_block = g.C + (int64_t)rbx * 32 * g.ldc; // wave-uniform
-        if (chunks_whole) {
+        if (chunks_whole && rbx * 32 + 32 <= M) { // the common case: only the lane-invariant column test
 #pragma unroll
             for (int i = 0; i < NB; ++i)
-                if (rbx * 32 + st_row[i] < M && st_col[i] < g.N)
+                if (st_col_ok[i])
+                    *reinterpret_cast<u32x4 *>(c_block + st_off[i]) = *reinterpret_cast<const u32x4 *>(stage + st_lds[i]);
+        } else if (chunks_whole) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                if (st_col_ok[i] && rbx * 32 + st_row[i] < M)
                     *reinterpret_cast<u32x4 *>(c_block + st_off[i]) = *reinterpret_cast<const u32x4 *>(stage + st_lds[i]);
         } else {
 #pragma nounroll
