@@ -187,9 +187,9 @@ __global__ void __launch_bounds__(kThreads) qadd_kernel(const uint8_t *__restric
     const RescaleParams po = make_rescale(g.mult_o, g.shift_o);
     const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t nthreads = (size_t)gridDim.x * blockDim.x;
-    const FusedRescale fo = make_fused(g.mult_o, g.shift_o, 0, g.z_out);
+    const FusedRescale fo = make_fused(g.mult_o, g.shift_o, 0, g.z_out, g.act_min, g.act_max);
     auto one = [&](uint32_t ca, uint32_t cb) -> uint32_t {
-        if (FUSED) return (uint32_t)med3_i32(rescale_fused(tab_a[ca] + tab_b[cb], fo), g.act_min, g.act_max);
+        if (FUSED) return (uint32_t)rescale_fused(tab_a[ca] + tab_b[cb], fo);
         int64_t u = (int64_t)tab_a[ca] + (int64_t)tab_b[cb];
         u = u > INT32_MAX ? INT32_MAX : (u < INT32_MIN ? INT32_MIN : u);
         return (uint32_t)(clamp_i32(g.act_min - g.z_out, g.act_max - g.z_out, rescale_general((int32_t)u, po)) + g.z_out);
@@ -324,7 +324,7 @@ qnn_status qnn_qadd(const uint8_t *a, int32_t z_a, int32_t mult_a, int32_t shift
     if (n == 0) return QNN_OK;
     if (!a || !b || !y) return QNN_EINVAL;
     QaddArgs g = {z_a, mult_a, shift_a, z_b, mult_b, shift_b, left_shift, mult_o, shift_o, z_out, act_min, act_max};
-    const bool fused = shift_o >= 1 && shift_o <= 21 && shift_a >= 0 && shift_b >= 0 && left_shift <= 20;
+    const bool fused = shift_o >= 1 && shift_o <= 20 && shift_a >= 0 && shift_b >= 0 && left_shift <= 20;
     const hipStream_t s = as_stream(stream);
     if (aligned(a, 16) && aligned(b, 16) && aligned(y, 16)) {
         const int grid = grid_for(n / 16 + 1, kThreads * 2);

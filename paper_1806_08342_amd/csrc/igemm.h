@@ -226,12 +226,10 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
         rp[j] = make_rescale(mu, sf);
         // |acc + corr| < 2^30 for the 64-bit fast form, < 2^29 for the fused 32-bit form
         fast_ok = fast_ok && sf >= 0 && b > -(1 << 28) && b < (1 << 28);
-        fused_ok = fused_ok && sf >= 1 && sf <= 21 && b > -(1 << 27) && b < (1 << 27);
-        fr[j] = make_fused(mu, sf, corr[j], g.z_out);
+        fused_ok = fused_ok && sf >= 1 && sf <= 20 && b > -(1 << 27) && b < (1 << 27);
+        fr[j] = make_fused(mu, sf, corr[j], g.z_out, g.lo_rel + g.z_out, g.hi_rel + g.z_out);
     }
     const bool fast = __all(fast_ok), fused = __all(fused_ok);
-    const int32_t act_lo = g.lo_rel + g.z_out, act_hi = g.hi_rel + g.z_out;
-
     // A lane holds, for one column, the rows 8q + 4*half + {0,1,2,3} (q = 0..3) of each 32x32
     // tile.  The four bytes of a row group are packed into a dword and the 4x4 byte blocks are
     // transposed across the four lanes of a quad (two DPP exchanges + byte permutes), so that
@@ -240,8 +238,7 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
     const int quad_lane = lane & 3;
     const uint32_t sel1 = (quad_lane & 1) ? 0x03070105u : 0x06020400u;
     const uint32_t sel2 = (quad_lane & 2) ? 0x03020706u : 0x05040100u;
-    auto store_group = [&](int i, int j, int q, const int32_t (&y)[4]) {
-        uint32_t x = (uint32_t)y[0] | ((uint32_t)y[1] << 8) | ((uint32_t)y[2] << 16) | ((uint32_t)y[3] << 24);
+    auto store_group = [&](int i, int j, int q, uint32_t x) { // x: the 4 bytes of rows 8q + 4*half + {0,1,2,3}
         // exchange with lane ^ 1, then with lane ^ 2 (quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E)
         uint32_t o = (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);
         x = __builtin_amdgcn_perm(o, x, sel1);
@@ -251,29 +248,46 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
         const int col = wave_n * WTN + j * 32 + (frag_row & ~3);
         *reinterpret_cast<uint32_t *>(so + row * OUT_PITCH + col) = x;
     };
-    auto run = [&](auto one) {
+    auto run = [&](auto pack4) {
 #pragma clang loop unroll(full)
         for (int i = 0; i < TM; ++i)
 #pragma clang loop unroll(full)
             for (int j = 0; j < TN; ++j)
 #pragma clang loop unroll(full)
                 for (int q = 0; q < 4; ++q) {
-                    int32_t y[4];
+                    int32_t a[4];
 #pragma clang loop unroll(full)
                     for (int e = 0; e < 4; ++e) {
-                        int32_t a = acc[i][j][4 * q + e];
-                        if (WEIGHTS_X16) a >>= 4; // weights were staged times 16; exact
-                        y[e] = one(a, j);
+                        a[e] = acc[i][j][4 * q + e];
+                        if (WEIGHTS_X16) a[e] >>= 4; // weights were staged times 16; exact
                     }
-                    store_group(i, j, q, y);
+                    store_group(i, j, q, pack4(a, j));
                 }
     };
+    auto pack_values = [&](const int32_t (&y)[4]) {
+        return (uint32_t)y[0] | ((uint32_t)y[1] << 8) | ((uint32_t)y[2] << 16) | ((uint32_t)y[3] << 24);
+    };
     if (fused) {
-        run([&](int32_t a, int j) { return med3_i32(rescale_fused(a, fr[j]), act_lo, act_hi); });
+        run([&](const int32_t (&a)[4], int j) {
+            uint32_t x = 0;
+#pragma clang loop unroll(full)
+            for (int e = 0; e < 4; ++e) x = shift_into_byte(x, rescale_fused_w(a[e], fr[j]), fr[j].n1, e);
+            return x;
+        });
     } else if (fast) {
-        run([&](int32_t a, int j) { return clamp_i32(g.lo_rel, g.hi_rel, rescale_fast(a + corr[j], rp[j])) + g.z_out; });
+        run([&](const int32_t (&a)[4], int j) {
+            int32_t y[4];
+#pragma clang loop unroll(full)
+            for (int e = 0; e < 4; ++e) y[e] = clamp_i32(g.lo_rel, g.hi_rel, rescale_fast(a[e] + corr[j], rp[j])) + g.z_out;
+            return pack_values(y);
+        });
     } else {
-        run([&](int32_t a, int j) { return clamp_i32(g.lo_rel, g.hi_rel, rescale_general(a + corr[j], rp[j])) + g.z_out; });
+        run([&](const int32_t (&a)[4], int j) {
+            int32_t y[4];
+#pragma clang loop unroll(full)
+            for (int e = 0; e < 4; ++e) y[e] = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(a[e] + corr[j], rp[j])) + g.z_out;
+            return pack_values(y);
+        });
     }
     __syncthreads();
 

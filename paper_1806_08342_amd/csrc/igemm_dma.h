@@ -69,7 +69,7 @@ template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = f
 __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs g, const int tiles_m, const int tiles_n,
                                                                 const int per_xcd, const SplitK sk)
 {
-    constexpr int NW = WM * WN, NT = NW * 64, BK = 64;
+    constexpr int NW = WM * WN, BK = 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int A_LOADS = BM / 16 / NW, B_LOADS = BN / 16 / NW; // wave-level loads per stage
@@ -363,8 +363,8 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const IgemmArgs g, c
         if (n + e >= g.N) break;
         const int32_t b = g.bias ? g.bias[n + e] : 0, mu = g.mult[n + e], sf = g.shift[n + e];
         int32_t y;
-        if (g.small_acc >= 2 && sf >= 1 && sf <= 21 && b > -(1 << 27) && b < (1 << 27)) {
-            y = med3_i32(rescale_fused(a[e], make_fused(mu, sf, b, g.z_out)), act_lo, act_hi);
+        if (g.small_acc >= 2 && sf >= 1 && sf <= 20 && b > -(1 << 27) && b < (1 << 27)) {
+            y = rescale_fused(a[e], make_fused(mu, sf, b, g.z_out, act_lo, act_hi));
         } else {
             y = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(a[e] + b, make_rescale(mu, sf))) + g.z_out;
         }

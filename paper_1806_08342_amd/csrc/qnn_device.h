@@ -68,34 +68,61 @@ __device__ __forceinline__ int32_t rescale_fast(int32_t a, const RescaleParams &
     return t >> p.rshift;
 }
 
-// Fused fast form used by the conv / GEMM epilogues, valid when 1 <= shift <= 21,
-// |acc + corr| < 2^29 and 0 <= z_out <= 255.  With a = acc + corr, n = shift:
-//   H = hi32(4a * mult)                      then  nearest(a*mult/2^31), ties up  = (H + 1) >> 1
-//   t = H + 1, s = t >> 31 (0 or -1)         and   z_out + nearest(h/2^n), ties away from zero
-//   q = (t + 2s + 2*half_z) >> (n + 1),  half_z = 2^(n-1) + (z_out << n)
-// (two nested floor divisions by powers of two collapse into one).  Only full-rate 32-bit
-// operations; the result already includes z_out and only needs the clamp.
+// Fused fast form used by the conv / GEMM epilogues, valid when 1 <= shift <= 20,
+// |acc + corr| < 2^29 and 0 <= act_min <= act_max <= 255.  With a = acc + corr, n = shift:
+//   T = hi32(4a * mult) = floor(a*mult / 2^30)     so  nearest(a*mult/2^31), ties up  = (T + 1) >> 1
+//   s = T >> 31 (0 or -1)                          and z_out + nearest(h/2^n), ties away from zero,
+//   w = T + 2s + c,  c = 2*(2^(n-1) + (z_out << n)) + 1            is  w >> (n + 1)
+// (two nested floor divisions by powers of two collapse into one; taking the sign from T
+// instead of T + 1 changes nothing, the two differ only at T = -1 where both give z_out).
+// The clamp is applied to w, against act_min << (n+1) and ((act_max + 1) << (n+1)) - 1, so
+// that the final shift can write its byte straight into a packed dword (shift_into_byte).
+// Only full-rate 32-bit operations.
 struct FusedRescale {
-    int32_t mult, corr4, c2, n1; // corr4 = 4*corr, c2 = 2*half_z, n1 = n + 1
+    int32_t mult, corr4, c, n1, lo, hi; // corr4 = 4*corr, n1 = n + 1, lo / hi = clamp bounds of w
 };
 
-__device__ __forceinline__ FusedRescale make_fused(int32_t mult, int32_t shift, int32_t corr, int32_t z_out)
+__device__ __forceinline__ FusedRescale make_fused(int32_t mult, int32_t shift, int32_t corr, int32_t z_out,
+                                                  int32_t act_min, int32_t act_max)
 {
-    const int nn = (shift >= 1 && shift <= 21) ? shift : 1; // callers check the range; keep shifts defined
+    const int nn = (shift >= 1 && shift <= 20) ? shift : 1; // callers check the range; keep shifts defined
     FusedRescale f;
     f.mult = mult;
     f.corr4 = (int32_t)((uint32_t)corr << 2);
-    f.c2 = 2 * ((1 << (nn - 1)) + (z_out << nn));
+    f.c = 2 * ((1 << (nn - 1)) + (z_out << nn)) + 1;
     f.n1 = nn + 1;
+    f.lo = act_min << (nn + 1);
+    f.hi = ((act_max + 1) << (nn + 1)) - 1;
     return f;
 }
 
-__device__ __forceinline__ int32_t rescale_fused(int32_t acc, const FusedRescale &p)
+// w of the comment above, clamped; the caller shifts it right by n1
+__device__ __forceinline__ int32_t med3_i32(int32_t v, int32_t lo, int32_t hi);
+__device__ __forceinline__ int32_t rescale_fused_w(int32_t acc, const FusedRescale &p)
 {
     const int32_t a4 = (int32_t)(((uint32_t)acc << 2) + (uint32_t)p.corr4);
-    const int32_t t = __mulhi(a4, p.mult) + 1;
-    const int32_t w = ((t >> 31) << 1) + t;
-    return (w + p.c2) >> p.n1;
+    const int32_t t = __mulhi(a4, p.mult);
+    const int32_t w = (int32_t)(((uint32_t)(t >> 31) << 1) + (uint32_t)t + (uint32_t)p.c);
+    return med3_i32(w, p.lo, p.hi);
+}
+
+// complete value (already clamped to [act_min, act_max])
+__device__ __forceinline__ int32_t rescale_fused(int32_t acc, const FusedRescale &p)
+{
+    return rescale_fused_w(acc, p) >> p.n1;
+}
+
+// arithmetic shift right whose result byte lands in byte `byte` of `packed` (sub-dword addressing)
+__device__ __forceinline__ uint32_t shift_into_byte(uint32_t packed, int32_t x, int32_t n1, int byte)
+{
+    // packed.byte[byte] = (x >> n1) & 0xff, other bytes kept (byte 0: cleared): one sub-dword-addressed shift
+    switch (byte) {
+    case 0: asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD" : "=v"(packed) : "v"(n1), "v"(x)); break; // other bytes cleared
+    case 1: asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(packed) : "v"(n1), "v"(x)); break;
+    case 2: asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(packed) : "v"(n1), "v"(x)); break;
+    default: asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(packed) : "v"(n1), "v"(x)); break;
+    }
+    return packed;
 }
 
 // median of three = clamp(lo, hi, v) for lo <= hi, one instruction

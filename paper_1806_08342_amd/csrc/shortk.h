@@ -60,18 +60,6 @@ struct ShortKColumn {
     int32_t mult, corr, c, n1, lo, hi, shift;
 };
 
-__device__ __forceinline__ uint32_t shortk_shift_into_byte(uint32_t packed, int32_t x, int32_t n1, int byte)
-{
-    // packed.byte[byte] = (x >> n1) & 0xff, other bytes kept (byte 0: cleared): one sub-dword-addressed shift
-    switch (byte) {
-    case 0: asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:DWORD" : "=v"(packed) : "v"(n1), "v"(x)); break; // other bytes cleared
-    case 1: asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(packed) : "v"(n1), "v"(x)); break;
-    case 2: asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(packed) : "v"(n1), "v"(x)); break;
-    default: asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(packed) : "v"(n1), "v"(x)); break;
-    }
-    return packed;
-}
-
 template <int NB, int KS, bool INT4, int VEC, int BVEC>
 __global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const ShortKArgs s)
 {
@@ -266,7 +254,7 @@ __global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const Sh
                         if (INT4) a >>= 4;
                         const int32_t t = __mulhi((int32_t)((uint32_t)(a + col[j].corr) << 2), col[j].mult);
                         const int32_t w = (int32_t)(((uint32_t)(t >> 31) << 1) + (uint32_t)t + (uint32_t)col[j].c);
-                        x = shortk_shift_into_byte(x, med3_i32(w, col[j].lo, col[j].hi), col[j].n1, e);
+                        x = shift_into_byte(x, med3_i32(w, col[j].lo, col[j].hi), col[j].n1, e);
                     }
                     put(j, q, x);
                 }
