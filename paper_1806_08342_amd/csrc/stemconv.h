@@ -23,7 +23,7 @@ struct StemArgs {
 };
 
 template <int KH, int TN>
-__global__ void __launch_bounds__(256) stemconv_kernel(const StemArgs s)
+__global__ void __launch_bounds__(256, 2) stemconv_kernel(const StemArgs s)
 {
     constexpr int BM = 128, BN = 32 * TN, WM = 4, WN = 1;
     constexpr int W_BYTES = BN * KH * 32;
@@ -98,8 +98,9 @@ __global__ void __launch_bounds__(256) stemconv_kernel(const StemArgs s)
         pf_lds[q] = a * X_PITCH + d * 4;
         pf_col[q] = patch_base + d * 4;
     }
-    uint32_t pre[PF];
-    auto prefetch = [&](int ho) {
+    // two register sets: the rows of the next TWO output rows are in flight while one is computed
+    uint32_t pre0[PF], pre1[PF];
+    auto prefetch = [&](int ho, uint32_t (&pre)[PF]) {
 #pragma unroll
         for (int q = 0; q < PF; ++q) {
             const int hi = ho * g.sh - g.ph + pf_a[q];
@@ -109,15 +110,16 @@ __global__ void __launch_bounds__(256) stemconv_kernel(const StemArgs s)
             pre[q] = ok ? v : fill;
         }
     };
-    prefetch(ho_begin);
+    prefetch(ho_begin, pre0);
+    if (ho_begin + 1 < ho_end) prefetch(ho_begin + 1, pre1);
 
-    for (int ho = ho_begin; ho < ho_end; ++ho) {
+    auto output_row = [&](int ho, uint32_t (&pre)[PF]) {
         __syncthreads(); // previous row: fragment reads and output copy are done
 #pragma unroll
         for (int q = 0; q < PF; ++q)
             if (pf_a[q] >= 0) *reinterpret_cast<uint32_t *>(x_lds + pf_lds[q]) = pre[q];
         __syncthreads();
-        if (ho + 1 < ho_end) prefetch(ho + 1);
+        if (ho + 2 < ho_end) prefetch(ho + 2, pre);
 
         i32x16 acc[1][TN];
 #pragma unroll
@@ -145,6 +147,10 @@ __global__ void __launch_bounds__(256) stemconv_kernel(const StemArgs s)
 #pragma unroll
         for (int j = 0; j < TN; ++j) cs[j] = colsum[j];
         igemm_epilogue<BM, BN, WM, WN, false>(gl, acc, cs, cparams, out_lds, m0, 0);
+    };
+    for (int ho = ho_begin; ho < ho_end; ho += 2) {
+        output_row(ho, pre0);
+        if (ho + 1 < ho_end) output_row(ho + 1, pre1);
     }
 }
 
