@@ -59,7 +59,9 @@ static const char *const kTileNames[TILE_COUNT] = {"64x64",     "128x128",      
 static const int kTileM[TILE_COUNT] = {64, 128, 128, 256, 256, 128, 256, 256, 64};
 static const int kTileN[TILE_COUNT] = {64, 128, 128, 256, 64, 128, 64, 128, 64};
 
-constexpr size_t kWorkspaceBytes = (size_t)64 << 20; // split-K scratch block per device
+// scratch block per device: split-K partial sums in the first half, unpacked 4-bit weights in the second
+constexpr size_t kSplitBytes = (size_t)32 << 20, kUnpackBytes = (size_t)32 << 20;
+constexpr size_t kWorkspaceBytes = kSplitBytes + kUnpackBytes;
 
 struct Plan {
     TileConfig tile;
@@ -87,7 +89,7 @@ static Plan choose_plan(int64_t M, int64_t N, int64_t K, bool dma_ok)
                 if (t == TILE_DMA_128x128 || t == TILE_DMA_64x64) splits = env_int("QNN_FORCE_SPLIT", 1);
                 const int ksteps = (int)(K / 64);
                 splits = splits < 1 ? 1 : (splits > ksteps ? ksteps : splits);
-                if ((int64_t)splits * M * N * 4 > (int64_t)kWorkspaceBytes) splits = 1;
+                if ((int64_t)splits * M * N * 4 > (int64_t)kSplitBytes) splits = 1;
                 return Plan{(TileConfig)t, splits};
             }
     }
@@ -128,14 +130,14 @@ static Plan choose_plan(int64_t M, int64_t N, int64_t K, bool dma_ok)
                 const int64_t want = (256 + tiles64 - 1) / tiles64, most = ksteps / 16;
                 plan.splits = (int)(want < most ? want : most);
             }
-            while (plan.splits > 1 && (int64_t)plan.splits * M * N * 4 > (int64_t)kWorkspaceBytes) --plan.splits;
+            while (plan.splits > 1 && (int64_t)plan.splits * M * N * 4 > (int64_t)kSplitBytes) --plan.splits;
             return plan;
         }
     }
     return Plan{(N <= 64 || M <= 64) ? TILE_64x64 : TILE_128x128, 1};
 }
 
-// Scratch memory of the split-K path: one fixed block per device, allocated at the first call
+// Scratch memory of the split-K path and of the 4-bit weight unpacking pass: one fixed block per device, allocated at the first call
 // that needs it and kept until the process ends.  Calls on different streams are ordered with
 // an event (the block is shared); while a stream is being captured into a graph no event is
 // recorded, and no block is allocated if none exists yet (the caller then runs unsplit).
@@ -279,6 +281,31 @@ static qnn_status launch_shortk(IgemmArgs &g, int b_mode, bool strided, hipStrea
     return launch_status(hipGetLastError());
 }
 
+// 4-bit weights for the pipelined kernel: one pass turns the nibble pairs of B ([N][K/2] bytes,
+// element 2j in the low nibble of byte j) into int8 [N][K] in scratch memory; the product then runs
+// on the int8 path.  Weights are small next to the activations of the layers this is used for
+// (M > 64), and the short-K and few-row kernels unpack in registers instead.
+__global__ void __launch_bounds__(256) unpack_int4_kernel(const uint8_t *__restrict__ src, int64_t ld_src_bytes, int N, int K,
+                                                         int8_t *__restrict__ dst)
+{
+    const int pieces = K / 16; // 16 elements = 8 packed bytes -> 16 bytes
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)N * pieces) return;
+    const int n = (int)(idx / pieces), p = (int)(idx - (int64_t)n * pieces);
+    const u32x2 raw = *reinterpret_cast<const u32x2 *>(src + n * ld_src_bytes + p * 8);
+    const uint32_t r2[2] = {raw.x, raw.y};
+    u32x4 out;
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {
+        uint32_t lo = r2[d] & 0x0F0F0F0Fu, hi = (r2[d] >> 4) & 0x0F0F0F0Fu; // elements 0,2,4,6 / 1,3,5,7 of this dword
+        lo |= ((lo >> 3) & 0x01010101u) * 0xF0u;                           // sign-extend each nibble to a byte
+        hi |= ((hi >> 3) & 0x01010101u) * 0xF0u;
+        out[2 * d] = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+        out[2 * d + 1] = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+    }
+    *reinterpret_cast<u32x4 *>(dst + (int64_t)n * K + p * 16) = out;
+}
+
 // Shared back end.  `vec` is the widest staging vector (in k elements) that the alignment
 // of A, B and K allows.
 static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s)
@@ -306,17 +333,43 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
         return launch_status(hipGetLastError());
     }
     const bool mat_or_conv = a_mode == A_MATRIX;
-    const bool dma_ok = b_mode == B_INT8 && vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23);
+    bool capturing = false, workspace_used = false;
+    int32_t *workspace = nullptr;
+    const bool aligned_for_dma = vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23);
+    // 4-bit weights: unpack once into scratch memory, then the int8 pipelined kernel
+    if (b_mode == B_INT4 && aligned_for_dma && (int64_t)g.N * g.K <= (int64_t)kUnpackBytes &&
+        std::getenv("QNN_FORCE_TILE") == nullptr) {
+        capturing = stream_is_capturing(s);
+        workspace = acquire_workspace(s, capturing);
+        if (workspace) {
+            int8_t *unpacked = reinterpret_cast<int8_t *>(workspace) + kSplitBytes;
+            const int64_t threads = (int64_t)g.N * (g.K / 16);
+            hipLaunchKernelGGL(unpack_int4_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, g.B, g.ldb / 2,
+                               g.N, g.K, unpacked);
+            g.B = reinterpret_cast<const uint8_t *>(unpacked), g.ldb = g.K;
+            b_mode = B_INT8;
+            workspace_used = true;
+        }
+    }
+    const bool dma_ok = b_mode == B_INT8 && aligned_for_dma;
     const Plan plan = choose_plan(g.M, g.N, g.K, dma_ok);
     const TileConfig cfg = plan.tile;
     const int64_t bm = kTileM[cfg], bn = kTileN[cfg];
+    auto finish = [&](qnn_status st) { // the scratch block is free again after what was enqueued so far
+        if (workspace_used) release_workspace(s, capturing);
+        return st;
+    };
     if (plan.splits > 1) {
-        const bool capturing = stream_is_capturing(s);
+        if (!workspace) {
+            capturing = stream_is_capturing(s);
+            workspace = acquire_workspace(s, capturing);
+        }
         SplitK sk;
         sk.ksteps = (g.K / 64 + plan.splits - 1) / plan.splits;
         sk.splits = (g.K / 64 + sk.ksteps - 1) / sk.ksteps; // no empty K range
-        sk.partial = acquire_workspace(s, capturing);
+        sk.partial = workspace;
         if (sk.partial && sk.splits > 1) {
+            workspace_used = true;
             hipError_t e;
             if (cfg == TILE_DMA_128x128)
                 e = mat_or_conv ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, true>(g, s, sk)
@@ -324,11 +377,10 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
             else
                 e = mat_or_conv ? launch_dma<64, 64, 2, 2, A_MATRIX, 4, true>(g, s, sk)
                                 : launch_dma<64, 64, 2, 2, A_CONV, 4, true>(g, s, sk);
-            release_workspace(s, capturing);
-            return launch_status(e);
+            return finish(launch_status(e));
         }
     }
-    if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return QNN_EINVAL;
+    if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return finish(QNN_EINVAL);
     const bool mat = a_mode == A_MATRIX;
     switch (cfg) {
     case TILE_64x64:
@@ -340,23 +392,23 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
         else launch_tile<128, 128, 2, 2, A_CONV>(g, b_mode, vec, s);
         break;
     case TILE_DMA_128x128:
-        return launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 4>(g, s));
+        return finish(launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 4>(g, s)));
     case TILE_DMA_128x128_S3:
-        return launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 3>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 3>(g, s));
+        return finish(launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 3>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 3>(g, s)));
     case TILE_DMA_256x256:
-        return launch_status(mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 256, 4, 2, A_CONV, 4>(g, s));
+        return finish(launch_status(mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 256, 4, 2, A_CONV, 4>(g, s)));
     case TILE_DMA_256x64:
-        return launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 4>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 4>(g, s));
+        return finish(launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 4>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 4>(g, s)));
     case TILE_DMA_64x64:
-        return launch_status(mat ? launch_dma<64, 64, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<64, 64, 2, 2, A_CONV, 4>(g, s));
+        return finish(launch_status(mat ? launch_dma<64, 64, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<64, 64, 2, 2, A_CONV, 4>(g, s)));
     case TILE_DMA_256x128:
-        return launch_status(mat ? launch_dma<256, 128, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 128, 4, 2, A_CONV, 4>(g, s));
+        return finish(launch_status(mat ? launch_dma<256, 128, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 128, 4, 2, A_CONV, 4>(g, s)));
     case TILE_DMA_256x64_S3:
-        return launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 3>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 3>(g, s));
+        return finish(launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 3>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 3>(g, s)));
     default:
-        return QNN_EINVAL;
+        return finish(QNN_EINVAL);
     }
-    return launch_status(hipGetLastError());
+    return finish(launch_status(hipGetLastError()));
 }
 
 static int pick_vec(int64_t k_like, std::initializer_list<const void *> ptrs, std::initializer_list<int64_t> pitches,

@@ -179,6 +179,36 @@ def test_qgemm_int4_matches_oracle(M, N, K):
     assert_same(got, want, f"qgemm int4 {M}x{N}x{K}")
 
 
+@pytest.mark.parametrize("M,N,K", [(128, 128, 320), (300, 200, 576), (1000, 96, 960), (65, 33, 1024), (700, 520, 2048)])
+def test_qgemm_int4_unpack_pass_then_pipelined_kernel(M, N, K):
+    # aligned 4-bit products with M > 64 and K > 256: the nibbles are unpacked to scratch memory first
+    rng = np.random.default_rng(720 + M + N + K)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    Bt = rng.integers(-8, 8, (N, K)).astype(np.int8)
+    Bt[0, :4] = (-8, 7, -1, 0)
+    Bt[N - 1, K - 2:] = (-8, -8)
+    packed = oracle.pack_int4(Bt)
+    bias = rng.integers(-20000, 20000, N).astype(np.int32)
+    mult, shift = oracle.quantize_multipliers(10 ** rng.uniform(-3.0, -2.2, N) / np.sqrt(K / 64.0))
+    for z_a in (0, 131, 255):
+        want = oracle.qgemm(A, z_a, packed, mult, shift, 128, 0, 255, bias=bias, weight_bits=4)
+        got = host(qnn.qgemm(dev(A), z_a, dev(packed), dev(mult), dev(shift), 128, 0, 255, bias=dev(bias), weight_bits=4))
+        assert_same(got, want, f"qgemm int4 (unpack pass) {M}x{N}x{K} z_a={z_a}")
+
+
+@pytest.mark.parametrize("shape", [(14, 14, 64, 96, 3, 1, 1), (7, 7, 960, 160, 1, 1, 0), (9, 9, 128, 40, 5, 2, 2), (7, 7, 576, 130, 1, 1, 0)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_qconv2d_int4_unpack_pass_matches_oracle(shape):
+    H, W, Cin, Cout, k, s, p = shape
+    layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="none", weight_bits=4)
+    c = synth.conv_case(layer, 4, 740 + sum(shape), oracle)
+    c["w"][0, 0, 0, :2] = (-8, 7)
+    c["w_packed"] = oracle.pack_int4(c["w"])
+    for z_x in (c["z_x"], 255):
+        c["z_x"] = z_x
+        _run_conv(c, f"conv int4 (unpack pass) {shape} z_x={z_x}")
+
+
 def test_qgemm_extreme_accumulators_and_left_shift():
     # all-255 activations times all-(-128)/127 weights with z_a = 0 reach the largest |acc| for this K;
     # multipliers >= 1 (negative shift) and huge biases take the general rescale path
