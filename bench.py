@@ -28,8 +28,12 @@ PEAK_INT8_TOPS = 5033.0  # dense int8 MFMA, 256 CU x 2.4 GHz x 8192 ops/clk/CU
 PEAK_HBM_GBS = 8000.0
 # vector ALU: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz full-rate 32-bit integer operations per second
 PEAK_VALU_LANE_OPS = 256 * 64 * 2.4e9
-# the exact fixed-point rescale + clamp + uint8 packing costs about 10 full-rate operations per output byte
-EPILOGUE_OPS_PER_OUTPUT = 10.0
+# the exact fixed-point rescale + clamp + uint8 packing costs about 8 full-rate operations per output byte
+EPILOGUE_OPS_PER_OUTPUT = 8.0
+# HBM bytes per launch of the dominant kernel, averaged over its launches in one pass of the sweep:
+# rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by what the same counters read for a plain 1 GiB
+# copy (figures and commands: profiles/bench_gemm_sweep_and_stacks.md).  Not measured by this script.
+MEASURED_TRAFFIC_BYTES = {"dma256x256": 283.7e6}
 
 
 def _device_uint8(torch, shape, seed):
@@ -274,9 +278,10 @@ def main():
     # dominant kernel = the tile configuration with the largest share of the step
     by_plan = {}
     for c, ms in zip(cases, per_case_ms):
-        d = by_plan.setdefault(c["plan"], dict(ms=0.0, ops=0.0, launches=0))
+        d = by_plan.setdefault(c["plan"], dict(ms=0.0, ops=0.0, launches=0, bytes=0.0))
         d["ms"] += ms
         d["ops"] += c["ops"]
+        d["bytes"] += c["M"] * c["K"] + c["K"] * c["N"] + c["M"] * c["N"] + 12 * c["N"]
         d["launches"] += 1
     dom = max(by_plan, key=lambda k: by_plan[k]["ms"])
     d = by_plan[dom]
@@ -284,7 +289,8 @@ def main():
     roofline = dict(bound="mfma", kernel=f"igemm_kernel<{dom}> (int8 32x32x32 MFMA)", achieved=round(achieved, 1),
                     peak=PEAK_INT8_TOPS, unit="TOP/s", frac=round(achieved / PEAK_INT8_TOPS, 4),
                     launches_per_step=d["launches"], avg_launch_us=round(d["ms"] * 1e3 / d["launches"], 2),
-                    ops_per_launch=d["ops"] / d["launches"], traffic=None)
+                    ops_per_launch=d["ops"] / d["launches"], traffic=MEASURED_TRAFFIC_BYTES.get(dom),
+                    algorithmic_bytes_per_launch=d["bytes"] / d["launches"])
     big = {f"{c['M']}x{c['N']}x{c['K']}": round(c["ops"] / (ms * 1e-3) * 1e-12, 1)
            for c, ms in zip(cases, per_case_ms) if (c["M"], c["N"], c["K"]) in
            [(1024,) * 3, (4096,) * 3, (8192,) * 3, (256, 8192, 8192), (64, 4096, 4096), (1, 4096, 4096)]}
