@@ -14,6 +14,15 @@
  *     (for example the storage of a torch tensor).  Pointers marked HOST are
  *     ordinary host pointers.  The library never allocates, frees or keeps
  *     any of them.
+ *   - Scratch memory: qnn_qgemm and qnn_qconv2d may use one library-owned
+ *     64 MiB device block per GPU (partial sums of products whose K is divided
+ *     over several workgroups; int8 copy of 4-bit weights).  It is allocated
+ *     with hipMalloc at the first call that needs it, never while `stream` is
+ *     being captured into a graph (such a call takes a route without scratch),
+ *     and kept until the process ends.  Eager calls on different streams that
+ *     use the block are ordered by the library with an event; captured graphs
+ *     that use it must not be replayed concurrently with each other or with
+ *     such calls.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Device entry points only enqueue work on that stream and return; they
  *     never synchronise.  Output buffers must not overlap input buffers.
@@ -105,8 +114,9 @@ qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, 
                      const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
                      void *stream);
 
-/* Name of the tile configuration ("<BM>x<BN>") that qnn_qgemm and the convolution entry points
- * select for an M x N x K product (M = output pixels, N = output channels, K = kh*kw*Cin);
+/* Name of the kernel configuration (a tile "<BM>x<BN>", with "/k<n>" when K is divided over n
+ * workgroups per tile, or "shortk" / "skinny16") that qnn_qgemm and the convolution entry points
+ * select for an aligned int8 M x N x K product (M = output pixels, N = output channels, K = kh*kw*Cin);
  * for logging and profiling.  HOST string owned by the library; "" for non-positive sizes. */
 const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K);
 
