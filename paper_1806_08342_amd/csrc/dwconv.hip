@@ -399,8 +399,16 @@ extern "C" qnn_status qnn_qdwconv2d(const uint8_t *x, int N, int H, int W, int C
         while ((1u << l) < d) ++l;
         g.shift_cgroups = l > 0 ? l - 1 : 0;
         g.magic_cgroups = d > 1 ? (uint32_t)((((uint64_t)1 << (31 + l)) + d - 1) / d) : 0u;
+        // taller patches (4 output rows per lane) reuse more of the window, but need enough lanes to
+        // give the chip something to do (tiny layers keep 2-row patches: twice the lanes)
+        static const int tall_env = std::getenv("QNN_DW_RH") ? std::atoi(std::getenv("QNN_DW_RH")) : 0;
+        const int64_t lanes_tall = lanes_x * ((g.Ho + 3) / 4) * N;
+        const bool tall = tall_env ? tall_env == 4 : lanes_tall >= 16384;
+        if (tall) g.hruns = (g.Ho + 3) / 4;
         const dim3 grid((unsigned)((lanes_x + 255) / 256), (unsigned)g.hruns, (unsigned)N);
-        if (stride_h == 1) hipLaunchKernelGGL((dwconv3x3_dot_kernel<1, RH>), grid, dim3(256), 0, s, g);
+        if (tall && stride_h == 1) hipLaunchKernelGGL((dwconv3x3_dot_kernel<1, 4>), grid, dim3(256), 0, s, g);
+        else if (tall) hipLaunchKernelGGL((dwconv3x3_dot_kernel<2, 4>), grid, dim3(256), 0, s, g);
+        else if (stride_h == 1) hipLaunchKernelGGL((dwconv3x3_dot_kernel<1, RH>), grid, dim3(256), 0, s, g);
         else hipLaunchKernelGGL((dwconv3x3_dot_kernel<2, RH>), grid, dim3(256), 0, s, g);
     } else if (c4 && stride_h == 1)
         hipLaunchKernelGGL((dwconv3x3_kernel<1, RH, RW>), dim3((unsigned)blocks), dim3(256), 0, s, g);
