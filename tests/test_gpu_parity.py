@@ -321,6 +321,25 @@ def test_qdwconv2d_matches_oracle(shape, batch):
         assert_same(got, want, f"dwconv {shape} batch {batch} z_x={z_x}")
 
 
+@pytest.mark.parametrize("variant", ["QNN_DW_RH=2", "QNN_DW_RH=4", "QNN_DW_MAD=1"])
+@pytest.mark.parametrize("shape", [(12, 12, 32, 3, 1, 1), (12, 12, 32, 3, 2, 1), (7, 7, 64, 3, 1, 1), (15, 9, 8, 3, 2, 1),
+                                   (9, 11, 4, 3, 1, 0), (30, 17, 24, 3, 1, 1), (29, 31, 96, 3, 2, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_qdwconv2d_every_3x3_variant_matches_oracle(monkeypatch, variant, shape):
+    # patch heights 2 and 4 of the dot-product kernel and the multiply-add kernel, forced by environment
+    name, value = variant.split("=")
+    monkeypatch.setenv(name, value)
+    H, W, C, k, s, p = shape
+    layer = workloads.Layer("t", "dw", H, W, C, C, k=k, stride=s, pad=p, act="relu6")
+    c = synth.conv_case(layer, 3, 1250 + sum(shape), oracle)
+    for z_x in (c["z_x"], 0, 255):
+        want = oracle.qdwconv2d(c["x"], z_x, c["w"], c["stride"], c["pad"], c["mult"], c["shift"], c["z_out"],
+                                c["act_min"], c["act_max"], bias=c["bias"])
+        got = host(qnn.qdwconv2d(dev(c["x"]), z_x, dev(c["w"]), c["stride"], c["pad"], dev(c["mult"]), dev(c["shift"]),
+                                 c["z_out"], c["act_min"], c["act_max"], bias=dev(c["bias"])))
+        assert_same(got, want, f"dwconv {variant} {shape} z_x={z_x}")
+
+
 # ------------------------------------------------ pipelined (LDS-DMA) tile configurations
 
 @pytest.fixture
