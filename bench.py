@@ -221,7 +221,7 @@ def time_streaming(torch, qnn):
 
 def cpu_baseline():
     """The oracle as it stands, on the host cores, on a bounded sample of the sweep: the
-    N = K = 4096 weight matrix times as many activation rows as take roughly 15 s of CPU work."""
+    N = K = 4096 weight matrix times as many activation rows as take roughly 20 s of CPU work."""
     import numpy as np
 
     import oracle
@@ -234,7 +234,7 @@ def cpu_baseline():
     oracle.qgemm(c["A"], c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
     dt = time.perf_counter() - t0
     rate = 256.0 * N * K / dt
-    rows = int(min(65536, max(256, (15.0 * rate / (N * K)) // 256 * 256)))
+    rows = int(min(65536, max(256, (20.0 * rate / (N * K)) // 256 * 256)))
     A = np.random.Generator(np.random.PCG64(workloads.seed_for(2, 998))).integers(0, 256, (rows, K), dtype=np.uint8)
     t0 = time.perf_counter()
     oracle.qgemm(A, c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
