@@ -224,6 +224,30 @@ def test_qgemm_extreme_accumulators_and_left_shift():
         assert_same(got, want, f"qgemm extremes z_a={z_a}")
 
 
+@pytest.mark.parametrize("M,N", [(8, 48), (40, 33), (130, 70), (300, 256)])
+@pytest.mark.parametrize("fill", ["max", "random"])
+def test_qgemm_largest_k_every_kernel_family(M, N, fill):
+    # K = 65536 is the largest reduction the int32 accumulator admits (255 * 128 * K < 2^31): few-row
+    # kernel (M <= 64), split-K tiles (few output tiles) and plain tiles; all-255 x all-(-128) is the
+    # accumulator of largest magnitude
+    K = 65536
+    rng = np.random.default_rng(2300 + M + N)
+    if fill == "max":
+        A = np.full((M, K), 255, np.uint8)
+        Bt = np.where(np.arange(N)[:, None] % 2 == 0, -128, 127).astype(np.int8) * np.ones((1, K), np.int8)
+    else:
+        A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+        Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    mult, shift = oracle.quantize_multipliers(np.full(N, 2.0 ** -23 if fill == "max" else 2.0 ** -15))
+    mult = (mult + np.arange(N)).astype(np.int32)
+    for z_a in (0, 128, 255):
+        want = oracle.qgemm(A, z_a, Bt, mult, shift, 128, 0, 255)
+        got = host(qnn.qgemm(dev(A), z_a, dev(Bt), dev(mult), dev(shift), 128, 0, 255))
+        assert_same(got, want, f"qgemm K=65536 {M}x{N} {fill} z_a={z_a}")
+    if fill == "random":
+        assert len(np.unique(want)) > 2
+
+
 def test_qgemm_config2_small_shapes():
     for i, (M, N, K) in enumerate([(256, 256, 256), (1, 512, 512), (64, 256, 1024), (256, 1024, 256)]):
         c = synth.gemm_case(M, N, K, workloads.seed_for(2, i), oracle)
