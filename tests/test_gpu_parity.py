@@ -483,6 +483,65 @@ def test_qconv2d_pointwise_short_k_matches_oracle(shape, bits):
         _run_conv(c, f"pointwise short-K conv {shape} bits={bits} z_x={z_x}")
 
 
+# ------------------------------------------------------------ medium reduction, weight-resident kernel
+
+@pytest.mark.parametrize("M,N,K", [(4096, 128, 512), (5000, 200, 320), (4100, 64, 1024), (4096, 30, 288), (6000, 256, 1152),
+                                   (4097, 97, 1280), (4500, 100, 352), (4300, 40, 736)])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_qgemm_weight_resident_matches_oracle(monkeypatch, M, N, K, bits):
+    if K <= 1024:
+        assert qnn.qgemm_plan(M, N, K) == "bres"
+    monkeypatch.setenv("QNN_BRES", "1")  # longer K: taken only on request
+    rng = np.random.default_rng(2400 + M + N + K + bits)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    if bits == 8:
+        Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+        B = Bt
+    else:
+        Bt = rng.integers(-8, 8, (N, K)).astype(np.int8)
+        B = oracle.pack_int4(Bt)
+    bias, mult, shift = _short_k_params(rng, N, K, bits)
+    for z_a in (0, 128, 255):
+        want = oracle.qgemm(A, z_a, B, mult, shift, 120, 5, 250, bias=bias, weight_bits=bits)
+        got = host(qnn.qgemm(dev(A), z_a, dev(B), dev(mult), dev(shift), 120, 5, 250, bias=dev(bias), weight_bits=bits))
+        assert_same(got, want, f"weight-resident qgemm {M}x{N}x{K} bits={bits} z_a={z_a}")
+
+
+def test_qgemm_weight_resident_general_rescale_and_many_column_groups(monkeypatch):
+    monkeypatch.setenv("QNN_BRES", "1")  # also for N > 256 (several column groups)
+    M, N, K = 4200, 600, 384
+    rng = np.random.default_rng(2500)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    bias, mult, shift = _short_k_params(rng, N, K, 8)
+    want = oracle.qgemm(A, 77, Bt, mult, shift, 128, 0, 255, bias=bias)
+    got = host(qnn.qgemm(dev(A), 77, dev(Bt), dev(mult), dev(shift), 128, 0, 255, bias=dev(bias)))
+    assert_same(got, want, "weight-resident qgemm, 5 column groups")
+    shift[0] = 0
+    mult[1], shift[1] = 2 ** 30, -1
+    shift[N - 1] = 27
+    bias[5] = 2 ** 28
+    want = oracle.qgemm(A, 3, Bt, mult, shift, 7, 0, 255, bias=bias)
+    got = host(qnn.qgemm(dev(A), 3, dev(Bt), dev(mult), dev(shift), 7, 0, 255, bias=dev(bias)))
+    assert_same(got, want, "weight-resident qgemm, general rescale")
+
+
+@pytest.mark.parametrize("shape,batch", [((40, 40, 64, 64, 3, 1, 1), 3), ((41, 37, 32, 96, 3, 2, 1), 12), ((30, 30, 32, 40, 5, 1, 2), 6),
+                                         ((64, 64, 512, 128, 1, 2, 0), 4), ((36, 36, 128, 130, 3, 1, 0), 4)],
+                         ids=lambda s: "x".join(map(str, s)) if isinstance(s, tuple) else str(s))
+@pytest.mark.parametrize("bits", [8, 4])
+def test_qconv2d_weight_resident_matches_oracle(monkeypatch, shape, batch, bits):
+    H, W, Cin, Cout, k, s, p = shape
+    layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu", weight_bits=bits)
+    if layer.K <= 1024:
+        assert qnn.qgemm_plan(batch * layer.Ho * layer.Wo, Cout, layer.K) == "bres"
+    monkeypatch.setenv("QNN_BRES", "1")
+    c = synth.conv_case(layer, batch, 2600 + sum(shape) + bits, oracle)
+    for z_x in (c["z_x"], 255):
+        c["z_x"] = z_x
+        _run_conv(c, f"weight-resident conv {shape} bits={bits} z_x={z_x}")
+
+
 # ------------------------------------------------------------ split-K (few output tiles, long K)
 
 @pytest.mark.parametrize("tile", ["dma128x128", "dma64x64"])
