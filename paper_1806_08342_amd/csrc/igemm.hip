@@ -351,7 +351,8 @@ static bool try_bres(IgemmArgs &g, int a_mode, int b_mode, hipStream_t s, qnn_st
     if (lds_for(nb) > 160 * 1024) return false;
     const int col_groups = (g.N + 32 * nb - 1) / (32 * nb);
     // worth it while the layer is far from MFMA-bound and A is not re-read by many column groups
-    if (mode != 1 && (col_groups > 2 || g.K > 1024)) return false;
+    // ... and there are enough row blocks for every wave of the chip (small layers stay with tiles)
+    if (mode != 1 && (col_groups > 2 || g.K > 1024 || g.M < 32768)) return false;
     g.small_acc = 2;
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
     BResArgs a = {};
@@ -533,7 +534,7 @@ const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K)
     if (M > 64 && K <= 256 && (K % 8) == 0 && std::getenv("QNN_FORCE_TILE") == nullptr && std::getenv("QNN_NO_SHORTK") == nullptr)
         return "shortk";
     if (M <= 64 && (K % 64) == 0) return "skinny16";
-    if (M >= 4096 && K > 256 && K <= 1024 && (K % 32) == 0 && N <= 256 && std::getenv("QNN_FORCE_TILE") == nullptr &&
+    if (M >= 32768 && K > 256 && K <= 1024 && (K % 32) == 0 && N <= 256 && std::getenv("QNN_FORCE_TILE") == nullptr &&
         (std::getenv("QNN_BRES") == nullptr || std::atoi(std::getenv("QNN_BRES")) != 0))
         return "bres";
     // reported for the aligned int8 case (what the benchmark shapes are)

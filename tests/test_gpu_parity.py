@@ -489,9 +489,7 @@ def test_qconv2d_pointwise_short_k_matches_oracle(shape, bits):
                                    (4097, 97, 1280), (4500, 100, 352), (4300, 40, 736)])
 @pytest.mark.parametrize("bits", [8, 4])
 def test_qgemm_weight_resident_matches_oracle(monkeypatch, M, N, K, bits):
-    if K <= 1024:
-        assert qnn.qgemm_plan(M, N, K) == "bres"
-    monkeypatch.setenv("QNN_BRES", "1")  # longer K: taken only on request
+    monkeypatch.setenv("QNN_BRES", "1")  # shapes this small take the kernel only on request
     rng = np.random.default_rng(2400 + M + N + K + bits)
     A = rng.integers(0, 256, (M, K)).astype(np.uint8)
     if bits == 8:
@@ -505,6 +503,15 @@ def test_qgemm_weight_resident_matches_oracle(monkeypatch, M, N, K, bits):
         want = oracle.qgemm(A, z_a, B, mult, shift, 120, 5, 250, bias=bias, weight_bits=bits)
         got = host(qnn.qgemm(dev(A), z_a, dev(B), dev(mult), dev(shift), 120, 5, 250, bias=dev(bias), weight_bits=bits))
         assert_same(got, want, f"weight-resident qgemm {M}x{N}x{K} bits={bits} z_a={z_a}")
+
+
+def test_qgemm_weight_resident_default_plan():
+    M, N, K = 40000, 128, 512
+    assert qnn.qgemm_plan(M, N, K) == "bres"
+    c = synth.gemm_case(M, N, K, workloads.seed_for(2, 90), oracle)
+    got = host(qnn.qgemm(dev(c["A"]), c["z_a"], dev(c["Bt"]), dev(c["mult"]), dev(c["shift"]), c["z_out"], 0, 255))
+    want = oracle.qgemm(c["A"], c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
+    assert_same(got, want, "weight-resident qgemm 40000x128x512, default plan")
 
 
 def test_qgemm_weight_resident_general_rescale_and_many_column_groups(monkeypatch):
@@ -533,8 +540,6 @@ def test_qgemm_weight_resident_general_rescale_and_many_column_groups(monkeypatc
 def test_qconv2d_weight_resident_matches_oracle(monkeypatch, shape, batch, bits):
     H, W, Cin, Cout, k, s, p = shape
     layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu", weight_bits=bits)
-    if layer.K <= 1024:
-        assert qnn.qgemm_plan(batch * layer.Ho * layer.Wo, Cout, layer.K) == "bres"
     monkeypatch.setenv("QNN_BRES", "1")
     c = synth.conv_case(layer, batch, 2600 + sum(shape) + bits, oracle)
     for z_x in (c["z_x"], 255):
