@@ -314,6 +314,28 @@ def test_qconv2d_matches_oracle(shape, batch):
     assert np.mean((want == c["act_min"]) | (want == c["act_max"])) < 0.75
 
 
+STEM_SHAPES = [(65, 70, 3, 64, 7, 2, 3), (50, 130, 3, 32, 3, 2, 1), (23, 301, 3, 64, 7, 2, 3), (17, 40, 3, 20, 3, 2, 1),
+               (40, 36, 4, 48, 3, 1, 1), (30, 30, 1, 40, 7, 2, 3), (31, 64, 2, 16, 7, 3, 2)]
+
+
+@pytest.mark.parametrize("kernel", ["wave", "block"])
+@pytest.mark.parametrize("shape", STEM_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_qconv2d_stem_kernels_match_oracle(monkeypatch, kernel, shape):
+    # both stem kernels (one wave per strip walking row segments: the default; one workgroup per strip: on request),
+    # images tall enough for several row segments, fused and general rescale, extreme fill codes
+    if kernel == "block":
+        monkeypatch.setenv("QNN_STEM_BLOCK", "1")
+    H, W, Cin, Cout, k, s, p = shape
+    layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu")
+    c = synth.conv_case(layer, 2, 3100 + sum(shape), oracle, in_range=(-2.0, 2.2))
+    for z_x in (c["z_x"], 0, 255):
+        c["z_x"] = z_x
+        _run_conv(c, f"stem ({kernel}) {shape} z_x={z_x}")
+    c["shift"][0] = 0  # one column off the fused path sends the whole launch down the general one
+    c["mult"][Cout - 1], c["shift"][Cout - 1] = 2 ** 30, -1
+    _run_conv(c, f"stem ({kernel}) {shape}, general rescale")
+
+
 @pytest.mark.parametrize("z_x", [0, 255])
 def test_qconv2d_padding_uses_zero_point(z_x):
     layer = workloads.Layer("t", "conv", 6, 6, 16, 16, k=3, stride=1, pad=1, act="none")
