@@ -17,7 +17,8 @@
 
 #include <type_traits>
 
-#include "igemm_dma.h" // the table of constant 16-byte chunks (padding codes)
+#include "fill_table.h"
+#include "igemm.h"
 
 namespace qnn {
 

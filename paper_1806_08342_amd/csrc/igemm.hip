@@ -1,47 +1,16 @@
-// Entry points of the dense quantized layers: qnn_qgemm and qnn_qconv2d both run the
-// implicit-GEMM MFMA kernel of igemm.h; this file validates arguments, picks the tile
-// configuration and the staging vector width, and launches.
+// Entry points of the dense quantized layers, qnn_qgemm and qnn_qconv2d: this file validates
+// arguments, picks the kernel family (launch routines in igemm_*.hip), the tile configuration and
+// the staging vector width, and launches the pipelined tile kernels of igemm_dma.h itself.
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
 
-#include "bres.h"
 #include "igemm_dma.h"
-#include "shortk.h"
-#include "skinny.h"
-#include "stemconv.h"
-#include "stemwave.h"
+#include "igemm_launch.h"
 
 namespace qnn {
 
-static uint32_t magic_for(uint32_t d) { return d <= 1 ? 0u : (uint32_t)(((1ull << 32) + d - 1) / d); }
-
-static bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
-
-template <int BM, int BN, int WM, int WN, int A_MODE, int B_MODE, int VEC>
-static void launch_one(const IgemmArgs &g, hipStream_t s)
-{
-    const int64_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-    hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, A_MODE, B_MODE, VEC>), dim3((unsigned)tiles), dim3(WM * WN * 64), 0,
-                       s, g);
-}
-
-template <int BM, int BN, int WM, int WN, int A_MODE>
-static void launch_tile(const IgemmArgs &g, int b_mode, int vec, hipStream_t s)
-{
-    if (b_mode == B_INT8) {
-        if (vec == 16) launch_one<BM, BN, WM, WN, A_MODE, B_INT8, 16>(g, s);
-        else if (vec == 8) launch_one<BM, BN, WM, WN, A_MODE, B_INT8, 8>(g, s);
-        else launch_one<BM, BN, WM, WN, A_MODE, B_INT8, 1>(g, s);
-    } else if (b_mode == B_INT4) {
-        if (vec == 16) launch_one<BM, BN, WM, WN, A_MODE, B_INT4, 16>(g, s);
-        else if (vec == 8) launch_one<BM, BN, WM, WN, A_MODE, B_INT4, 8>(g, s);
-        else launch_one<BM, BN, WM, WN, A_MODE, B_INT4, 1>(g, s);
-    } else {
-        if constexpr (A_MODE == A_MATRIX) launch_one<BM, BN, WM, WN, A_MATRIX, B_INT8_ROWS, 1>(g, s);
-    }
-}
 
 enum TileConfig {
     TILE_64x64 = 0,
@@ -237,141 +206,7 @@ static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = Spli
     return e;
 }
 
-// Short reduction (K <= 256): weight-stationary kernel of shortk.h.  Returns false when the
-// operands do not meet its alignment rules (the caller then takes the general route).
-template <int KS, bool INT4, int VEC> static void launch_shortk_one(const ShortKArgs &a, unsigned blocks, hipStream_t s)
-{
-    constexpr int NB = KS <= 4 ? 4 : 2;
-    // weights: 16-byte loads when every 16-element piece of a column is 16-byte aligned, else dwords
-    const bool b16 = !INT4 && aligned_to(a.g.B, 16) && (a.g.ldb % 16) == 0 && (a.g.K % 16) == 0;
-    if (b16) hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 16>), dim3(blocks), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 4>), dim3(blocks), dim3(256), 0, s, a);
-}
 
-template <bool INT4, int VEC> static void launch_shortk_ks(const ShortKArgs &a, int ks, unsigned blocks, hipStream_t s)
-{
-    if (ks <= 1) launch_shortk_one<1, INT4, VEC>(a, blocks, s);
-    else if (ks <= 2) launch_shortk_one<2, INT4, VEC>(a, blocks, s);
-    else if (ks <= 4) launch_shortk_one<4, INT4, VEC>(a, blocks, s);
-    else launch_shortk_one<8, INT4, VEC>(a, blocks, s);
-}
-
-static bool shortk_eligible(const IgemmArgs &g, int b_mode, bool strided)
-{
-    if (g.K > 256 || (g.K % 8) != 0 || g.M <= 64 || g.M >= 0x7fffffe0 || b_mode == B_INT8_ROWS) return false;
-    if (std::getenv("QNN_FORCE_TILE") != nullptr || std::getenv("QNN_NO_SHORTK") != nullptr) return false;
-    const int64_t row_pitch = strided ? g.Cin : g.lda;
-    if (!aligned_to(g.A, 8) || (row_pitch % 8) != 0) return false;
-    if (!aligned_to(g.B, 4) || (g.ldb % 8) != 0) return false;
-    return true;
-}
-
-static qnn_status launch_shortk(IgemmArgs &g, int b_mode, bool strided, hipStream_t s)
-{
-    g.small_acc = 2; // K <= 256: |acc| <= 2^22
-    g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
-    const int ks = (g.K + 31) / 32;
-    const int nb = ks <= 4 ? 4 : 2;
-    ShortKArgs a = {};
-    a.g = g;
-    a.strided = strided ? 1 : 0;
-    a.col_groups = (g.N + 32 * nb - 1) / (32 * nb);
-    const int64_t row_blocks = (g.M + 31) / 32;
-    // as many waves as stay resident together (3 per SIMD for K <= 32, else 2, on 256 CUs), spread
-    // over the column groups, then trimmed so that every wave walks the same number of row blocks
-    const int64_t resident = 256 * 4 * (ks <= 1 ? 3 : 2);
-    int64_t walkers = resident / a.col_groups;
-    walkers = walkers < 1 ? 1 : (walkers > row_blocks ? row_blocks : walkers);
-    const int64_t per_walker = (row_blocks + walkers - 1) / walkers;
-    walkers = (row_blocks + per_walker - 1) / per_walker;
-    a.walkers = (int)walkers;
-    const int64_t waves = walkers * a.col_groups;
-    if (waves > 0x7fffffff) return QNN_EINVAL;
-    const unsigned blocks = (unsigned)((waves + 3) / 4);
-    const int64_t row_pitch = strided ? g.Cin : g.lda;
-    const bool v16 = aligned_to(g.A, 16) && (row_pitch % 16) == 0 && (g.K % 16) == 0;
-    if (b_mode == B_INT4) {
-        if (v16) launch_shortk_ks<true, 16>(a, ks, blocks, s);
-        else launch_shortk_ks<true, 8>(a, ks, blocks, s);
-    } else {
-        if (v16) launch_shortk_ks<false, 16>(a, ks, blocks, s);
-        else launch_shortk_ks<false, 8>(a, ks, blocks, s);
-    }
-    return launch_status(hipGetLastError());
-}
-
-// Medium reduction, few output channels: weight-resident kernel of bres.h.  Returns false when the
-// shape or the alignment does not fit (the caller then takes the tiled route).
-template <int NB, int KC, bool INT4, bool CONV, bool PAD = false>
-static hipError_t launch_bres_one(const BResArgs &a, unsigned blocks, int lds, hipStream_t s)
-{
-    auto kernel = bres_kernel<NB, KC, INT4, CONV, PAD>;
-    static int configured = 0; // per instantiation: largest dynamic LDS size enabled so far
-    if (lds > configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        configured = lds;
-    }
-    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(512), lds, s, a);
-    return hipGetLastError();
-}
-
-template <int NB, bool INT4, bool CONV>
-static hipError_t launch_bres_kc(const BResArgs &a, unsigned blocks, int lds, hipStream_t s)
-{
-    // A fragments travel in chunks of KC K sub-steps; a chunk size that divides K / 32 wastes no MFMA
-    const int ks = a.g.K / 32;
-    if (ks % 8 == 0) return launch_bres_one<NB, 8, INT4, CONV>(a, blocks, lds, s);
-    if (ks % 6 == 0) return launch_bres_one<NB, 6, INT4, CONV>(a, blocks, lds, s);
-    if (ks % 4 == 0) return launch_bres_one<NB, 4, INT4, CONV>(a, blocks, lds, s);
-    return launch_bres_one<NB, 6, INT4, CONV, true>(a, blocks, lds, s); // last chunk padded with zero operands
-}
-
-template <int NB> static hipError_t launch_bres_nb(const BResArgs &a, bool i4, bool conv, unsigned blocks, int lds, hipStream_t s)
-{
-    if (conv) return i4 ? launch_bres_kc<NB, true, true>(a, blocks, lds, s) : launch_bres_kc<NB, false, true>(a, blocks, lds, s);
-    return i4 ? launch_bres_kc<NB, true, false>(a, blocks, lds, s) : launch_bres_kc<NB, false, false>(a, blocks, lds, s);
-}
-
-static bool try_bres(IgemmArgs &g, int a_mode, int b_mode, hipStream_t s, qnn_status *status)
-{
-    const char *env = std::getenv("QNN_BRES"); // tuning aid: 0 = never, 1 = whenever the shape fits
-    const int mode = env ? std::atoi(env) : -1;
-    if (mode == 0 || std::getenv("QNN_FORCE_TILE") != nullptr) return false;
-    if (b_mode == B_INT8_ROWS || (g.K % 32) != 0 || g.K <= 256 || g.M < 4096 || g.M >= 0x7fffffe0) return false;
-    const bool conv = a_mode == A_CONV;
-    if (conv) {
-        if ((g.Cin % 32) != 0 || !aligned_to(g.A, 16) || (int64_t)g.H * g.W * g.Cin >= (1ll << 31)) return false;
-    } else if (!aligned_to(g.A, 16) || (g.lda % 16) != 0) {
-        return false;
-    }
-    if (b_mode == B_INT4 ? (!aligned_to(g.B, 8) || (g.ldb % 16) != 0) : (!aligned_to(g.B, 16) || (g.ldb % 16) != 0)) return false;
-    int nb = g.N <= 32 ? 1 : (g.N <= 64 ? 2 : 4);
-    auto lds_for = [&](int n) { return (g.K / 32) * n * 1024 + 8 * 32 * (32 * n + 32); };
-    while (nb > 1 && lds_for(nb) > 160 * 1024) nb /= 2;
-    if (lds_for(nb) > 160 * 1024) return false;
-    const int col_groups = (g.N + 32 * nb - 1) / (32 * nb);
-    // worth it while the layer is far from MFMA-bound and A is not re-read by many column groups
-    // ... and there are enough row blocks for every wave of the chip (small layers stay with tiles)
-    if (mode != 1 && (col_groups > 2 || g.K > 1024 || g.M < 32768)) return false;
-    g.small_acc = 2;
-    g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
-    BResArgs a = {};
-    a.g = g, a.col_groups = col_groups;
-    const int64_t row_blocks = (g.M + 31) / 32;
-    int64_t walkers = 256 / col_groups < 1 ? 1 : 256 / col_groups; // one workgroup (8 waves) per CU
-    if (walkers * 8 > row_blocks) walkers = (row_blocks + 7) / 8;
-    a.groups_walkers = (int)walkers;
-    const unsigned blocks = (unsigned)(walkers * col_groups);
-    const int lds = lds_for(nb);
-    const bool i4 = b_mode == B_INT4;
-    hipError_t e;
-    if (nb == 4) e = launch_bres_nb<4>(a, i4, conv, blocks, lds, s);
-    else if (nb == 2) e = launch_bres_nb<2>(a, i4, conv, blocks, lds, s);
-    else e = launch_bres_nb<1>(a, i4, conv, blocks, lds, s);
-    *status = launch_status(e);
-    return true;
-}
 
 // 4-bit weights for the pipelined kernel: one pass turns the nibble pairs of B ([N][K/2] bytes,
 // element 2j in the low nibble of byte j) into int8 [N][K] in scratch memory; the product then runs
@@ -406,24 +241,11 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
     g.small_acc = g.K <= 8192 ? 2 : (g.K <= 16384 ? 1 : 0); // |acc| <= K * 2^14
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
     if (a_mode == A_MATRIX && shortk_eligible(g, b_mode, false)) return launch_shortk(g, b_mode, false, s);
-    // few rows: weight-streaming kernel (one workgroup per 16 output columns, K split over 8 waves)
-    if (a_mode == A_MATRIX && g.M <= 64 && vec == 16 && (g.K % 64) == 0 && b_mode != B_INT8_ROWS &&
-        std::getenv("QNN_FORCE_TILE") == nullptr) {
-        const unsigned blocks = (unsigned)((g.N + 15) / 16);
-        const int mt = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : 4);
-        const bool i4 = b_mode == B_INT4;
-        if (mt == 1) {
-            if (i4) hipLaunchKernelGGL((skinny_gemm_kernel<1, true>), dim3(blocks), dim3(512), 0, s, g);
-            else hipLaunchKernelGGL((skinny_gemm_kernel<1, false>), dim3(blocks), dim3(512), 0, s, g);
-        } else if (mt == 2) {
-            if (i4) hipLaunchKernelGGL((skinny_gemm_kernel<2, true>), dim3(blocks), dim3(512), 0, s, g);
-            else hipLaunchKernelGGL((skinny_gemm_kernel<2, false>), dim3(blocks), dim3(512), 0, s, g);
-        } else {
-            if (i4) hipLaunchKernelGGL((skinny_gemm_kernel<4, true>), dim3(blocks), dim3(512), 0, s, g);
-            else hipLaunchKernelGGL((skinny_gemm_kernel<4, false>), dim3(blocks), dim3(512), 0, s, g);
-        }
-        return launch_status(hipGetLastError());
+    {
+        qnn_status st;
+        if (try_skinny(g, a_mode, b_mode, vec, s, &st)) return st;
     }
+
     {
         qnn_status st;
         if (try_bres(g, a_mode, b_mode, s, &st)) return st;
@@ -480,12 +302,10 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
     const bool mat = a_mode == A_MATRIX;
     switch (cfg) {
     case TILE_64x64:
-        if (mat) launch_tile<64, 64, 2, 2, A_MATRIX>(g, b_mode, vec, s);
-        else launch_tile<64, 64, 2, 2, A_CONV>(g, b_mode, vec, s);
+        launch_plain_tile(false, g, a_mode, b_mode, vec, s);
         break;
     case TILE_128x128:
-        if (mat) launch_tile<128, 128, 2, 2, A_MATRIX>(g, b_mode, vec, s);
-        else launch_tile<128, 128, 2, 2, A_CONV>(g, b_mode, vec, s);
+        launch_plain_tile(true, g, a_mode, b_mode, vec, s);
         break;
     case TILE_DMA_128x128:
         return finish(launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 4>(g, s)));
@@ -598,55 +418,11 @@ qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z
     g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
     g.C = y, g.ldc = Cout;
     const int b_mode = weight_bits == 4 ? B_INT4 : B_INT8;
-    // network stems: a handful of input channels, one kernel row = one short contiguous byte run
-    if (weight_bits == 8 && Cin < 16 && kw * Cin <= 32 && stride_w * Cin <= 7 && (kh == 3 || kh == 7) && Cout <= 64 &&
-        ((int64_t)W * Cin) % 4 == 0 && aligned_to(x, 4)) {
-        g.small_acc = 2;
-        g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
-        // default: the barrier-free kernel (one wave per 32-pixel strip), built for row strides 1 and 2
-        if (std::getenv("QNN_STEM_BLOCK") == nullptr && (stride_h == 1 || stride_h == 2)) {
-            StemWaveArgs sw = {};
-            sw.g = g, sw.kh = kh, sw.run = kw * Cin;
-            sw.strips = (Wo + 31) / 32;
-            // enough waves for the chip (about 8 per SIMD), but at least 4 output rows per segment:
-            // the first row of a segment fetches all kh image rows, the others only stride_h
-            const int64_t columns = (int64_t)N * sw.strips;
-            int64_t segments = (8192 + columns - 1) / columns;
-            const int64_t most = (Ho + 3) / 4;
-            segments = segments < 1 ? 1 : (segments > most ? most : segments);
-            sw.rows_per_seg = (int)((Ho + segments - 1) / segments);
-            sw.segments = (Ho + sw.rows_per_seg - 1) / sw.rows_per_seg;
-            sw.waves = columns * sw.segments;
-            const int64_t wblocks = (sw.waves + 3) / 4;
-            if (wblocks <= 0x7fffffff) {
-                const hipStream_t s = as_stream(stream);
-                const dim3 grid((unsigned)wblocks);
-                const int nb = Cout <= 32 ? 1 : 2;
-#define QNN_STEMWAVE(KH_, NB_, SH_) \
-    if (kh == KH_ && nb == NB_ && stride_h == SH_) hipLaunchKernelGGL((stemwave_kernel<KH_, NB_, SH_>), grid, dim3(256), 0, s, sw)
-                QNN_STEMWAVE(3, 1, 1); QNN_STEMWAVE(3, 1, 2); QNN_STEMWAVE(3, 2, 1); QNN_STEMWAVE(3, 2, 2);
-                QNN_STEMWAVE(7, 1, 1); QNN_STEMWAVE(7, 1, 2); QNN_STEMWAVE(7, 2, 1); QNN_STEMWAVE(7, 2, 2);
-#undef QNN_STEMWAVE
-                return launch_status(hipGetLastError());
-            }
-        }
-        StemArgs st = {};
-        st.g = g, st.kh = kh, st.run = kw * Cin;
-        st.strips = (Wo + 127) / 128;
-        // a workgroup walks up to 8 output rows (weights are staged once per workgroup), fewer
-        // when that would leave the chip with too few workgroups
-        const int64_t row_strips = (int64_t)N * Ho * st.strips;
-        st.rows_per_wg = (int)(row_strips / 2048 < 1 ? 1 : (row_strips / 2048 > 8 ? 8 : row_strips / 2048));
-        const int64_t blocks = (int64_t)N * ((Ho + st.rows_per_wg - 1) / st.rows_per_wg) * st.strips;
-        if (blocks <= 0x7fffffff) {
-            const hipStream_t s = as_stream(stream);
-            if (kh == 3 && Cout <= 32) hipLaunchKernelGGL((stemconv_kernel<3, 1>), dim3((unsigned)blocks), dim3(256), 0, s, st);
-            else if (kh == 3) hipLaunchKernelGGL((stemconv_kernel<3, 2>), dim3((unsigned)blocks), dim3(256), 0, s, st);
-            else if (Cout <= 32) hipLaunchKernelGGL((stemconv_kernel<7, 1>), dim3((unsigned)blocks), dim3(256), 0, s, st);
-            else hipLaunchKernelGGL((stemconv_kernel<7, 2>), dim3((unsigned)blocks), dim3(256), 0, s, st);
-            return launch_status(hipGetLastError());
-        }
+    {
+        qnn_status st;
+        if (try_stem(g, N, kh, stride_h, stride_w, weight_bits, as_stream(stream), &st)) return st;
     }
+
     const bool pointwise = kh == 1 && kw == 1 && stride_h == 1 && stride_w == 1 && pad_h == 0 && pad_w == 0;
     if (pointwise) { // a 1x1 convolution over NHWC is a plain matrix product
         g.lda = Cin;

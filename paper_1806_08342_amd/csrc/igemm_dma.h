@@ -18,20 +18,10 @@
 // read a constant chunk holding the code z_x.
 #pragma once
 
+#include "fill_table.h"
 #include "igemm.h"
 
 namespace qnn {
-
-// 256 constant 16-byte chunks: entry v is the byte v repeated (fill codes for padding taps)
-struct FillTable {
-    uint8_t v[256][16];
-    constexpr FillTable() : v{}
-    {
-        for (int i = 0; i < 256; ++i)
-            for (int j = 0; j < 16; ++j) v[i][j] = (uint8_t)i;
-    }
-};
-__device__ const FillTable g_fill_table{};
 
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {

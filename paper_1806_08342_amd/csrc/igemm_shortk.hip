@@ -1,0 +1,95 @@
+// Launch routines of the weight-stationary short-K kernel and of the few-row kernel.
+#include "igemm_launch.h"
+#include "shortk.h"
+#include "skinny.h"
+
+namespace qnn {
+
+// Short reduction (K <= 256): weight-stationary kernel of shortk.h.  Returns false when the
+// operands do not meet its alignment rules (the caller then takes the general route).
+template <int KS, bool INT4, int VEC> static void launch_shortk_one(const ShortKArgs &a, unsigned blocks, hipStream_t s)
+{
+    constexpr int NB = KS <= 4 ? 4 : 2;
+    // weights: 16-byte loads when every 16-element piece of a column is 16-byte aligned, else dwords
+    const bool b16 = !INT4 && aligned_to(a.g.B, 16) && (a.g.ldb % 16) == 0 && (a.g.K % 16) == 0;
+    if (b16) hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 16>), dim3(blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 4>), dim3(blocks), dim3(256), 0, s, a);
+}
+
+template <bool INT4, int VEC> static void launch_shortk_ks(const ShortKArgs &a, int ks, unsigned blocks, hipStream_t s)
+{
+    if (ks <= 1) launch_shortk_one<1, INT4, VEC>(a, blocks, s);
+    else if (ks <= 2) launch_shortk_one<2, INT4, VEC>(a, blocks, s);
+    else if (ks <= 4) launch_shortk_one<4, INT4, VEC>(a, blocks, s);
+    else launch_shortk_one<8, INT4, VEC>(a, blocks, s);
+}
+
+bool shortk_eligible(const IgemmArgs &g, int b_mode, bool strided)
+{
+    if (g.K > 256 || (g.K % 8) != 0 || g.M <= 64 || g.M >= 0x7fffffe0 || b_mode == B_INT8_ROWS) return false;
+    if (std::getenv("QNN_FORCE_TILE") != nullptr || std::getenv("QNN_NO_SHORTK") != nullptr) return false;
+    const int64_t row_pitch = strided ? g.Cin : g.lda;
+    if (!aligned_to(g.A, 8) || (row_pitch % 8) != 0) return false;
+    if (!aligned_to(g.B, 4) || (g.ldb % 8) != 0) return false;
+    return true;
+}
+
+qnn_status launch_shortk(IgemmArgs &g, int b_mode, bool strided, hipStream_t s)
+{
+    g.small_acc = 2; // K <= 256: |acc| <= 2^22
+    g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
+    const int ks = (g.K + 31) / 32;
+    const int nb = ks <= 4 ? 4 : 2;
+    ShortKArgs a = {};
+    a.g = g;
+    a.strided = strided ? 1 : 0;
+    a.col_groups = (g.N + 32 * nb - 1) / (32 * nb);
+    const int64_t row_blocks = (g.M + 31) / 32;
+    // as many waves as stay resident together (3 per SIMD for K <= 32, else 2, on 256 CUs), spread
+    // over the column groups, then trimmed so that every wave walks the same number of row blocks
+    const int64_t resident = 256 * 4 * (ks <= 1 ? 3 : 2);
+    int64_t walkers = resident / a.col_groups;
+    walkers = walkers < 1 ? 1 : (walkers > row_blocks ? row_blocks : walkers);
+    const int64_t per_walker = (row_blocks + walkers - 1) / walkers;
+    walkers = (row_blocks + per_walker - 1) / per_walker;
+    a.walkers = (int)walkers;
+    const int64_t waves = walkers * a.col_groups;
+    if (waves > 0x7fffffff) return QNN_EINVAL;
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    const int64_t row_pitch = strided ? g.Cin : g.lda;
+    const bool v16 = aligned_to(g.A, 16) && (row_pitch % 16) == 0 && (g.K % 16) == 0;
+    if (b_mode == B_INT4) {
+        if (v16) launch_shortk_ks<true, 16>(a, ks, blocks, s);
+        else launch_shortk_ks<true, 8>(a, ks, blocks, s);
+    } else {
+        if (v16) launch_shortk_ks<false, 16>(a, ks, blocks, s);
+        else launch_shortk_ks<false, 8>(a, ks, blocks, s);
+    }
+    return launch_status(hipGetLastError());
+}
+
+bool try_skinny(const IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s, qnn_status *status)
+{
+    // few rows: weight-streaming kernel (one workgroup per 16 output columns, K split over 8 waves)
+    if (a_mode == A_MATRIX && g.M <= 64 && vec == 16 && (g.K % 64) == 0 && b_mode != B_INT8_ROWS &&
+        std::getenv("QNN_FORCE_TILE") == nullptr) {
+        const unsigned blocks = (unsigned)((g.N + 15) / 16);
+        const int mt = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : 4);
+        const bool i4 = b_mode == B_INT4;
+        if (mt == 1) {
+            if (i4) hipLaunchKernelGGL((skinny_gemm_kernel<1, true>), dim3(blocks), dim3(512), 0, s, g);
+            else hipLaunchKernelGGL((skinny_gemm_kernel<1, false>), dim3(blocks), dim3(512), 0, s, g);
+        } else if (mt == 2) {
+            if (i4) hipLaunchKernelGGL((skinny_gemm_kernel<2, true>), dim3(blocks), dim3(512), 0, s, g);
+            else hipLaunchKernelGGL((skinny_gemm_kernel<2, false>), dim3(blocks), dim3(512), 0, s, g);
+        } else {
+            if (i4) hipLaunchKernelGGL((skinny_gemm_kernel<4, true>), dim3(blocks), dim3(512), 0, s, g);
+            else hipLaunchKernelGGL((skinny_gemm_kernel<4, false>), dim3(blocks), dim3(512), 0, s, g);
+        }
+        *status = launch_status(hipGetLastError());
+        return true;
+    }
+    return false;
+}
+
+} // namespace qnn

@@ -9,14 +9,15 @@
 // image rows are fetched (aligned dword loads, out-of-image dwords replaced by the code z_x; the
 // loads for the next output row are in flight while the current one is computed; the row stride
 // is a template parameter so that these fetches are straight-line code).  Each lane
-// cuts its 32-byte window out of the ring with dword reads + v_alignbyte.  Nothing in the
+// cuts its 32-byte window out of the ring with dword reads + v_alignbyte (the codes are stored
+// in the ring already offset to signed bytes).  Nothing in the
 // kernel synchronises waves with each other.  Epilogue as in shortk.h.
 #pragma once
 
 #include <type_traits>
 
+#include "fill_table.h"
 #include "igemm.h"
-#include "igemm_dma.h" // g_fill_table
 
 namespace qnn {
 
@@ -175,7 +176,7 @@ __global__ void __launch_bounds__(256) stemwave_kernel(const StemWaveArgs s)
             for (int a = 0; a < KH; ++a) first[a] = fetch_row(hi0 + a);
 #pragma unroll
             for (int a = 0; a < KH - NEW; ++a)
-                *reinterpret_cast<uint32_t *>(ring_slot(hi0 + a) + lane * 4) = col_inside ? first[a] : fill;
+                *reinterpret_cast<uint32_t *>(ring_slot(hi0 + a) + lane * 4) = (col_inside ? first[a] : fill) ^ 0x80808080u;
 #pragma unroll
             for (int a = 0; a < NEW; ++a) fresh[a] = first[KH - NEW + a];
         }
@@ -186,7 +187,7 @@ __global__ void __launch_bounds__(256) stemwave_kernel(const StemWaveArgs s)
             const int fresh_first = ho * SH - g.ph + KH - NEW;
 #pragma unroll
             for (int a = 0; a < NEW; ++a)
-                *reinterpret_cast<uint32_t *>(ring_slot(fresh_first + a) + lane * 4) = col_inside ? fresh[a] : fill;
+                *reinterpret_cast<uint32_t *>(ring_slot(fresh_first + a) + lane * 4) = (col_inside ? fresh[a] : fill) ^ 0x80808080u;
             wave_sync();
             // ---- previous output row's stores, then the loads for the next output row (see shortk.h);
             // behind the last row of the segment the loads repeat a row already seen (in bounds, unused)
@@ -212,7 +213,7 @@ __global__ void __launch_bounds__(256) stemwave_kernel(const StemWaveArgs s)
                 i32x4 fa;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    fa[e] = (int32_t)(__builtin_amdgcn_alignbyte(d[e + 1], d[e], (uint32_t)win_shift) ^ 0x80808080u);
+                    fa[e] = (int32_t)__builtin_amdgcn_alignbyte(d[e + 1], d[e], (uint32_t)win_shift);
 #pragma unroll
                 for (int j = 0; j < NB; ++j) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb[a][j], acc[j], 0, 0, 0);
             }
