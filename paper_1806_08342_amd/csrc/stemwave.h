@@ -10,8 +10,8 @@
 // loads for the next output row are in flight while the current one is computed; the row stride
 // is a template parameter so that these fetches are straight-line code).  Each lane
 // cuts its 32-byte window out of the ring with dword reads + v_alignbyte (the codes are stored
-// in the ring already offset to signed bytes).  Nothing in the
-// kernel synchronises waves with each other.  Epilogue as in shortk.h.
+// in the ring already offset to signed bytes).  After the weights are staged (once per
+// workgroup, two barriers) nothing in the kernel synchronises waves with each other.  Epilogue as in shortk.h.
 #pragma once
 
 #include <type_traits>
@@ -37,17 +37,55 @@ __global__ void __launch_bounds__(256) stemwave_kernel(const StemWaveArgs s)
     constexpr int PITCH = 32 * NB + 32; // staged output row (see shortk.h)
     constexpr int RING = 8, ROW_BYTES = 256 + 32; // ring rows; a little slack behind a row for the window reads
     static_assert(KH <= RING, "the rows of one output row must fit the ring");
-    __shared__ __attribute__((aligned(16))) uint8_t ring_all[4][RING * ROW_BYTES];
-    __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][32 * PITCH];
+    // one LDS block: the raw filter bank while the fragments are built, then the waves' rings and output tiles
+    constexpr int RING_ALL = 4 * RING * ROW_BYTES, WORK = RING_ALL + 4 * 32 * PITCH;
+    static_assert(NB * 32 * KH * 32 + 32 <= WORK, "the raw weights must fit the block they borrow");
+    __shared__ __attribute__((aligned(16))) uint8_t work[WORK];
+    __shared__ __attribute__((aligned(16))) uint8_t wfrag[KH * NB * 1024]; // B fragments: (kernel row, column block) x lane x 16
     const IgemmArgs &g = s.g;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint8_t *const ring = ring_all[wave], *const stage = stage_all[wave];
+    uint8_t *const ring = work + wave * (RING * ROW_BYTES), *const stage = work + RING_ALL + wave * (32 * PITCH);
     const int frow = lane & 31, fhalf = lane >> 5;
+
+    // ---- weights, once per workgroup: [Cout][kh][run] bytes -> LDS with coalesced loads, then each
+    // wave cuts a share of the MFMA B fragments (kernel row, column block; rows zero padded to 32)
+    // out of it and leaves them in LDS for all four waves
+    {
+        const int total = g.N * KH * s.run;
+        if ((reinterpret_cast<uintptr_t>(g.B) & 3) == 0) {
+            for (int i = threadIdx.x; i * 4 + 4 <= total; i += 256)
+                reinterpret_cast<uint32_t *>(work)[i] = reinterpret_cast<const uint32_t *>(g.B)[i];
+            if ((int)threadIdx.x < (total & 3)) work[(total & ~3) + threadIdx.x] = g.B[(total & ~3) + threadIdx.x];
+        } else {
+            for (int i = threadIdx.x; i < total; i += 256) work[i] = g.B[i];
+        }
+        __syncthreads();
+        for (int p = wave; p < KH * NB; p += 4) { // p = a * NB + j, wave-uniform
+            const int a = p / NB, j = p % NB;
+            int co = j * 32 + frow;
+            co = co < g.N ? co : g.N - 1;
+            const int addr = (co * KH + a) * s.run + fhalf * 16;
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(work + (addr & ~3));
+            uint32_t d[5];
+#pragma unroll
+            for (int e = 0; e < 5; ++e) d[e] = src[e];
+            u32x4 f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                int valid = s.run - fhalf * 16 - e * 4; // bytes of this dword that belong to the kernel row
+                valid = valid < 0 ? 0 : (valid > 4 ? 4 : valid);
+                const uint32_t mask = valid >= 4 ? 0xffffffffu : ((1u << (8 * valid)) - 1u);
+                f[e] = __builtin_amdgcn_alignbyte(d[e + 1], d[e], (uint32_t)(addr & 3)) & mask;
+            }
+            *reinterpret_cast<u32x4 *>(wfrag + p * 1024 + lane * 16) = f;
+        }
+        __syncthreads(); // the only workgroup barriers: from here on the waves run independently
+    }
 
     // ---- wave -> (image, strip of 32 output columns, segment of output rows); all wave-uniform
     int64_t w = (int64_t)blockIdx.x * 4 + wave;
-    if (w >= s.waves) return; // no workgroup barriers anywhere: a wave may leave alone
+    if (w >= s.waves) return;
     const int strip = (int)(w % s.strips);
     w /= s.strips;
     const int seg = (int)(w % s.segments);
@@ -57,7 +95,6 @@ __global__ void __launch_bounds__(256) stemwave_kernel(const StemWaveArgs s)
     const int ho_end = ho_begin + s.rows_per_seg < g.Ho ? ho_begin + s.rows_per_seg : g.Ho;
     if (ho_begin >= ho_end) return;
 
-    // ---- weights: [Cout][kh][run] in memory -> B fragments [kernel row][column block], zero padded to 32
     i32x4 fb[KH][NB];
     int32_t c_mult[NB], c_corr[NB], c_c[NB], c_n1[NB], c_lo[NB], c_hi[NB], c_shift[NB];
     bool fused_ok = true;
@@ -68,18 +105,9 @@ __global__ void __launch_bounds__(256) stemwave_kernel(const StemWaveArgs s)
         int32_t colsum = 0;
 #pragma unroll
         for (int a = 0; a < KH; ++a) {
-            const uint8_t *wrow = g.B + ((int64_t)co * KH + a) * s.run;
+            fb[a][j] = *reinterpret_cast<const i32x4 *>(wfrag + (a * NB + j) * 1024 + lane * 16);
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                uint32_t v = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int c = fhalf * 16 + d * 4 + e;
-                    if (c < s.run) v |= (uint32_t)wrow[c] << (8 * e);
-                }
-                fb[a][j][d] = (int32_t)v;
-                colsum = __builtin_amdgcn_sdot4((int32_t)v, 0x01010101, colsum, false);
-            }
+            for (int d = 0; d < 4; ++d) colsum = __builtin_amdgcn_sdot4(fb[a][j][d], 0x01010101, colsum, false);
         }
         colsum += __shfl_xor(colsum, 32);
         const int32_t b = g.bias ? g.bias[co] : 0, mu = g.mult[co], sf = g.shift[co];
