@@ -33,7 +33,7 @@ EPILOGUE_OPS_PER_OUTPUT = 8.0
 # HBM bytes per launch of the dominant kernel, averaged over its launches in one pass of the sweep:
 # rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by what the same counters read for a plain 1 GiB
 # copy (figures and commands: profiles/bench_gemm_sweep_and_stacks.md).  Not measured by this script.
-MEASURED_TRAFFIC_BYTES = {"dma256x256": 283.7e6}
+MEASURED_TRAFFIC_BYTES = {"dma256x256": 283.8e6}
 
 
 def _device_uint8(torch, shape, seed):
