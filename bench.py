@@ -30,6 +30,7 @@ PEAK_HBM_GBS = 8000.0
 PEAK_VALU_LANE_OPS = 256 * 64 * 2.4e9
 # the exact fixed-point rescale + clamp + uint8 packing costs about 8 full-rate operations per output byte
 EPILOGUE_OPS_PER_OUTPUT = 8.0
+ADD_OPS_PER_OUTPUT = 10.0  # fused residual add: two table addresses, add, 7-operation rescale into a byte
 # HBM bytes per launch of the dominant kernel, averaged over its launches in one pass of the sweep:
 # rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by what the same counters read for a plain 1 GiB
 # copy (figures and commands: profiles/bench_gemm_sweep_and_stacks.md).  Not measured by this script.
@@ -164,7 +165,13 @@ def time_stack(torch, qnn, workloads, synth, layers, batch, config_id, reps):
             w = _dev(torch, c.get("w_packed", c["w"]))
             mult, shift, bias = _dev(torch, c["mult"]), _dev(torch, c["shift"]), _dev(torch, c["bias"])
             y = torch.empty((batch, l.Ho, l.Wo, l.Cout), dtype=torch.uint8, device="cuda:0")
-            if l.kind == "dw":
+            if l.kind == "conv_add":  # the residual add of the block, fused behind its last 1x1
+                ad = synth.qadd_case((1,), seed + 7, qnn, act=l.act)
+                res = _device_uint8(torch, (batch, l.Ho, l.Wo, l.Cout), seed + 1)
+                fn = lambda: qnn.qconv2d_add(x, c["z_x"], w, c["stride"], c["pad"], mult, shift, c["z_out"], 0, 255, res,
+                                             ad["z_b"], ad["params"], ad["z_out"], ad["act_min"], ad["act_max"], bias=bias,
+                                             weight_bits=l.weight_bits, out=y)
+            elif l.kind == "dw":
                 fn = lambda: qnn.qdwconv2d(x, c["z_x"], w, c["stride"], c["pad"], mult, shift, c["z_out"],
                                            c["act_min"], c["act_max"], bias=bias, out=y)
             else:
@@ -175,6 +182,8 @@ def time_stack(torch, qnn, workloads, synth, layers, batch, config_id, reps):
         t_mfma, t_hbm = 2.0 * macs / (PEAK_INT8_TOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)
         outputs = batch * l.Ho * l.Wo * l.Cout if l.kind != "qadd" else batch * l.H * l.W * l.Cout
         alu_ops = EPILOGUE_OPS_PER_OUTPUT + (18.0 if l.kind == "dw" else 0.0)  # depthwise: + 9 MACs as unpack + mad
+        if l.kind == "conv_add":
+            alu_ops += ADD_OPS_PER_OUTPUT
         t_alu = outputs * alu_ops / PEAK_VALU_LANE_OPS
         bound = max(t_mfma, t_hbm)
         rows.append(dict(layer=l.name, kind=l.kind, count=l.count, us=round(t * 1e6, 2), tops=round(2e-12 * macs / t, 2),
@@ -325,8 +334,16 @@ def main():
         sec["streaming"] = time_streaming(torch, qnn)
         sec["mobilenet_v1_b64"] = time_stack(torch, qnn, workloads, synth, workloads.mobilenet_v1(), 64, 3, 5)
         sec["mobilenet_v1_b1"] = time_stack(torch, qnn, workloads, synth, workloads.mobilenet_v1(), 1, 3, 5)
-        sec["resnet50_b256"] = time_stack(torch, qnn, workloads, synth, workloads.resnet50(), 256, 4, 3)
-        sec["mobilenet_v2_int4_b32"] = time_stack(torch, qnn, workloads, synth, workloads.mobilenet_v2(4), 32, 5, 5)
+        # residual adds fused behind the last 1x1 of their block (qnn_qconv2d_add); the figure with
+        # separate qnn_qadd launches is kept beside it
+        fused = workloads.fuse_adds
+        sec["resnet50_b256"] = time_stack(torch, qnn, workloads, synth, fused(workloads.resnet50()), 256, 4, 3)
+        sec["mobilenet_v2_int4_b32"] = time_stack(torch, qnn, workloads, synth, fused(workloads.mobilenet_v2(4)), 32, 5, 5)
+        for name, layers_, batch_, cfg_ in (("resnet50_b256", workloads.resnet50(), 256, 4),
+                                            ("mobilenet_v2_int4_b32", workloads.mobilenet_v2(4), 32, 5)):
+            plain = time_stack(torch, qnn, workloads, synth, layers_, batch_, cfg_, 3)
+            sec[name]["separate_adds"] = dict(images_per_s=plain["images_per_s"], ms=plain["ms"],
+                                              frac_of_sum_of_bounds=plain["frac_of_sum_of_bounds"])
         layer_dump = {}
         for k, v in sec.items():
             if isinstance(v, dict) and "layers" in v:

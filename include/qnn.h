@@ -163,6 +163,36 @@ qnn_status qnn_qadd(const uint8_t *a, int32_t z_a, int32_t mult_a, int32_t shift
                     int32_t mult_b, int32_t shift_b, int32_t left_shift, int32_t mult_o, int32_t shift_o,
                     int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *y, size_t n, void *stream);
 
+/* The add of Sec. 3.2.1 fused behind the layer that produces one of its operands (the last 1x1
+ * convolution of a residual block; fusing operators is what Sec. 3.2 and the recommendations of
+ * Sec. 5 advise): the layer's uint8 result never goes to memory.  Bit for bit the same as
+ *   qnn_qgemm / qnn_qconv2d (with z_out = z_mid, act_min = mid_min, act_max = mid_max) into a
+ *   temporary t, followed by
+ *   qnn_qadd(t, z_mid, mult_m, shift_m, residual, z_r, mult_r, shift_r, left_shift, mult_o, shift_o,
+ *            z_out, act_min, act_max).
+ * (z_mid, mid_min, mid_max): the quantizer and clamp of the layer's own uint8 result (the first
+ * operand of the add).  add: HOST pointer, read during the call.
+ * residual: DEVICE uint8, same shape as the output ([M][N] with row pitch ldr >= N for qgemm, dense
+ * NHWC [N][Ho][Wo][Cout] for qconv2d), must not overlap the output.  Layers whose kernel cannot apply
+ * the add in its epilogue run it as a second pass over the output; the result is the same. */
+typedef struct qnn_add_params {
+    int32_t mult_m, shift_m;        /* the layer's result enters the add with these */
+    int32_t z_r, mult_r, shift_r;   /* the residual operand */
+    int32_t left_shift, mult_o, shift_o;
+    int32_t z_out, act_min, act_max; /* quantizer / fused activation of the sum */
+} qnn_add_params;
+
+qnn_status qnn_qgemm_add(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
+                         int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
+                         const int32_t *shift, int32_t z_mid, int32_t mid_min, int32_t mid_max, const uint8_t *residual,
+                         int64_t ldr, const qnn_add_params *add, uint8_t *C, int64_t ldc, void *stream);
+
+qnn_status qnn_qconv2d_add(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
+                           int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w,
+                           const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_mid,
+                           int32_t mid_min, int32_t mid_max, const uint8_t *residual, const qnn_add_params *add,
+                           uint8_t *y, void *stream);
+
 /* ------------------------------------------------------------------ host-only helpers */
 
 /* Quantizer parameters from a real range, Sec. 2.1: the range is first widened to contain 0,

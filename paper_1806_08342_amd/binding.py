@@ -20,7 +20,7 @@ B_COLUMNS_CONTIGUOUS, B_ROWS_CONTIGUOUS = 0, 1
 
 EXPORTS = [
     "qnn_last_error", "qnn_version", "qnn_qgemm_plan", "qnn_quantize", "qnn_dequantize", "qnn_requantize", "qnn_qgemm", "qnn_pack_b",
-    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
+    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
     "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4",
 ]
 
@@ -58,6 +58,9 @@ def load_library():
         "qnn_qgemm": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
         "qnn_pack_b": [vp, i64, i64, i64, vp, i64, vp],
         "qnn_qconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
+        "qnn_qgemm_add": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, vp, i64, vp],
+        "qnn_qconv2d_add": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp,
+                            vp, vp],
         "qnn_qdwconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
         "qnn_qadd": [vp, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp],
         "qnn_choose_qparams": [f64, f64, ci, C.POINTER(f32), C.POINTER(i32)],
@@ -277,6 +280,60 @@ def qconv2d(x, z_x, w, stride, pad, mult, shift, z_out, act_min, act_max, bias=N
         _dev(x, torch.uint8, "x"), N, H, W, Cin, z_x, wp, Cout, kh, kw, weight_bits, stride[0], stride[1], pad[0],
         pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"),
         z_out, act_min, act_max, _dev(y, torch.uint8, "y"), _stream()))
+    return y
+
+
+class _AddParams(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("mult_m", "shift_m", "z_r", "mult_r", "shift_r", "left_shift", "mult_o",
+                                         "shift_o", "z_out", "act_min", "act_max")]
+
+
+def _add_struct(z_r, params, z_out, act_min, act_max):
+    """`params` is what qadd_params(s_mid, s_residual, s_out) returns (operand a = the layer's own result)."""
+    p = params
+    return _AddParams(p["mult_a"], p["shift_a"], z_r, p["mult_b"], p["shift_b"], p["left_shift"], p["mult_o"],
+                      p["shift_o"], z_out, act_min, act_max)
+
+
+def qgemm_add(A, z_a, B, mult, shift, z_mid, mid_min, mid_max, residual, z_r, params, z_out, act_min, act_max,
+              bias=None, weight_bits=8, out=None):
+    """qgemm (columns-contiguous B) whose uint8 result, quantized with (z_mid, mid_min, mid_max), is added to
+    `residual` (uint8 [M,N], rows may be spaced apart) with the rescaling add of `params`; returns uint8 [M,N]."""
+    torch = _torch()
+    M, K = A.shape
+    if weight_bits == 4:
+        N, ldb, bp = B.shape[0], B.shape[1] * 2, _dev(B, torch.uint8, "B")
+    else:
+        (N, ldb), bp = B.shape, _dev(B, torch.int8, "B")
+    Cm = torch.empty((M, N), dtype=torch.uint8, device=A.device) if out is None else out
+    ap, lda = _dev_rows(A, torch.uint8, "A")
+    cp, ldc = _dev_rows(Cm, torch.uint8, "C")
+    rp, ldr = _dev_rows(residual, torch.uint8, "residual")
+    add = _add_struct(z_r, params, z_out, act_min, act_max)
+    _check("qnn_qgemm_add", load_library().qnn_qgemm_add(
+        ap, lda, z_a, bp, ldb, B_COLUMNS_CONTIGUOUS, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
+        _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_mid, mid_min, mid_max, rp, ldr,
+        C.addressof(add), cp, ldc, _stream()))
+    return Cm
+
+
+def qconv2d_add(x, z_x, w, stride, pad, mult, shift, z_mid, mid_min, mid_max, residual, z_r, params, z_out, act_min,
+                act_max, bias=None, weight_bits=8, out=None):
+    """qconv2d followed by the rescaling add with `residual` (uint8 NHWC, the shape of the output), fused."""
+    torch = _torch()
+    N, H, W, Cin = x.shape
+    Cout, kh, kw = w.shape[:3]
+    wp = _dev(w, torch.uint8 if weight_bits == 4 else torch.int8, "w")
+    Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
+    y = torch.empty((N, Ho, Wo, Cout), dtype=torch.uint8, device=x.device) if out is None else out
+    if tuple(residual.shape) != (N, Ho, Wo, Cout):
+        raise ValueError(f"residual has shape {tuple(residual.shape)}, the output {(N, Ho, Wo, Cout)}")
+    add = _add_struct(z_r, params, z_out, act_min, act_max)
+    _check("qnn_qconv2d_add", load_library().qnn_qconv2d_add(
+        _dev(x, torch.uint8, "x"), N, H, W, Cin, z_x, wp, Cout, kh, kw, weight_bits, stride[0], stride[1], pad[0],
+        pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"),
+        z_mid, mid_min, mid_max, _dev(residual, torch.uint8, "residual"), C.addressof(add),
+        _dev(y, torch.uint8, "y"), _stream()))
     return y
 
 

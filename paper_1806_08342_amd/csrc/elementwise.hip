@@ -221,6 +221,36 @@ __global__ void __launch_bounds__(kThreads) qadd_kernel(const uint8_t *__restric
     }
 }
 
+
+// ------------------------------------------------ add behind a product, second-pass form
+
+// y = ADD(y, r) row by row, in place (each 16-byte chunk is read, combined and written by one lane)
+template <bool FUSED>
+__global__ void __launch_bounds__(kThreads) add_inplace_kernel(uint8_t *y, int64_t ldy, const uint8_t *r, int64_t ldr,
+                                                               int64_t M, int64_t N, AddParams p, int vec16)
+{
+    __shared__ int32_t tab[512];
+    add_fill_tables(tab, p, threadIdx.x, kThreads);
+    __syncthreads();
+    const AddOut ao = make_add_out(p);
+    const int64_t chunks_per_row = (N + 15) / 16, total = M * chunks_per_row;
+    for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < total; q += (int64_t)gridDim.x * kThreads) {
+        const int64_t m = q / chunks_per_row;
+        const int64_t n = (q - m * chunks_per_row) * 16;
+        uint8_t *yp = y + m * ldy + n;
+        const uint8_t *rp = r + m * ldr + n;
+        if (vec16 && n + 16 <= N) {
+            const u32x4 a = *reinterpret_cast<const u32x4 *>(yp), b = *reinterpret_cast<const u32x4 *>(rp);
+            u32x4 o;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) o[d] = add_codes4<FUSED>(a[d], b[d], tab, ao);
+            *reinterpret_cast<u32x4 *>(yp) = o;
+        } else {
+            for (int e = 0; e < 16 && n + e < N; ++e) yp[e] = (uint8_t)add_code1<FUSED>(yp[e], rp[e], tab, ao);
+        }
+    }
+}
+
 // ------------------------------------------------------------------- pack_b
 
 // dst[n][k] = src[k][n], 64x64 byte tiles through LDS so both sides are coalesced
@@ -242,6 +272,20 @@ __global__ void __launch_bounds__(kThreads) pack_b_kernel(const int8_t *__restri
 }
 
 static bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+qnn_status launch_add_inplace(uint8_t *y, int64_t ldy, const uint8_t *r, int64_t ldr, int64_t M, int32_t N,
+                              const AddParams &p, hipStream_t s)
+{
+    int64_t rows = M, cols = N;
+    if (ldy == N && ldr == N) rows = 1, cols = M * (int64_t)N, ldy = ldr = cols; // dense: one long row, whole chunks throughout
+    const int vec16 = aligned(y, 16) && aligned(r, 16) && (rows == 1 || ((ldy % 16) == 0 && (ldr % 16) == 0));
+    const size_t chunks = (size_t)rows * (size_t)((cols + 15) / 16);
+    const int grid = grid_for(chunks, kThreads * 2);
+    const bool fused = p.shift_o >= 1 && p.shift_o <= 20 && p.shift_m >= 0 && p.shift_r >= 0 && p.left_shift <= 20;
+    if (fused) hipLaunchKernelGGL((add_inplace_kernel<true>), dim3(grid), dim3(kThreads), 0, s, y, ldy, r, ldr, rows, cols, p, vec16);
+    else hipLaunchKernelGGL((add_inplace_kernel<false>), dim3(grid), dim3(kThreads), 0, s, y, ldy, r, ldr, rows, cols, p, vec16);
+    return launch_status(hipGetLastError());
+}
 
 } // namespace qnn
 

@@ -18,6 +18,8 @@
 // bank-conflict free.
 #pragma once
 
+#include <type_traits>
+
 #include "qnn_device.h"
 
 namespace qnn {
@@ -47,6 +49,11 @@ struct IgemmArgs {
     int64_t ldc;
     int32_t c_vec16;  // C and ldc are 16-byte aligned
     int32_t small_acc; // 2: |acc| and the zero-point correction are each below 2^27; 1: below 2^28; 0: unknown
+    // optional rescaling add behind the product: C = ADD(code of the product, R); R == nullptr: none
+    const uint8_t *R;
+    int64_t ldr;
+    int32_t r_vec16; // R and ldr are 16-byte aligned
+    AddParams add;
 };
 
 __device__ __forceinline__ uint32_t fast_div(uint32_t k, uint32_t d, uint32_t magic)
@@ -209,6 +216,7 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
     constexpr int NT = WM * WN * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int OUT_PITCH = BN + 16;
+    constexpr int ADD_TABLE_OFFSET = BM * OUT_PITCH + 4 * WM * WN * TN * 64; // behind the tile and the column-sum partials
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / WN, wave_n = wave % WN;
@@ -289,22 +297,55 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
             return pack_values(y);
         });
     }
+    // optional rescaling add: tables of the 2 x 256 rescaled codes behind the output tile and the
+    // column-sum partials (the operand ring is free by now)
+    const bool add = g.R != nullptr; // uniform
+    int32_t *const add_tab = reinterpret_cast<int32_t *>(so + ADD_TABLE_OFFSET);
+    if (add) add_fill_tables(add_tab, g.add, tid, NT);
     __syncthreads();
 
     constexpr int ROW_CHUNKS = BN / 16;
-    for (int q = tid; q < BM * ROW_CHUNKS; q += NT) {
-        const int row = q / ROW_CHUNKS, cc = q % ROW_CHUNKS;
-        const int64_t m = m0 + row;
-        const int n = n0 + cc * 16;
-        if (m >= g.M || n >= g.N) continue;
-        uint8_t *dst = g.C + m * g.ldc + n;
-        const uint8_t *src = so + row * OUT_PITCH + cc * 16;
-        if (g.c_vec16 && n + 16 <= g.N) {
-            *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
-        } else {
-            for (int e = 0; e < 16 && n + e < g.N; ++e) dst[e] = src[e];
+    if (!add) {
+        for (int q = tid; q < BM * ROW_CHUNKS; q += NT) {
+            const int row = q / ROW_CHUNKS, cc = q % ROW_CHUNKS;
+            const int64_t m = m0 + row;
+            const int n = n0 + cc * 16;
+            if (m >= g.M || n >= g.N) continue;
+            uint8_t *dst = g.C + m * g.ldc + n;
+            const uint8_t *src = so + row * OUT_PITCH + cc * 16;
+            if (g.c_vec16 && n + 16 <= g.N) {
+                *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(src);
+            } else {
+                for (int e = 0; e < 16 && n + e < g.N; ++e) dst[e] = src[e];
+            }
         }
+        return;
     }
+    const AddOut ao = make_add_out(g.add);
+    auto add_tile = [&](auto fused_tag) {
+        constexpr bool FUSED = decltype(fused_tag)::value;
+        for (int q = tid; q < BM * ROW_CHUNKS; q += NT) {
+            const int row = q / ROW_CHUNKS, cc = q % ROW_CHUNKS;
+            const int64_t m = m0 + row;
+            const int n = n0 + cc * 16;
+            if (m >= g.M || n >= g.N) continue;
+            uint8_t *dst = g.C + m * g.ldc + n;
+            const uint8_t *res = g.R + m * g.ldr + n;
+            const uint8_t *src = so + row * OUT_PITCH + cc * 16;
+            if (g.c_vec16 && g.r_vec16 && n + 16 <= g.N) {
+                const u32x4 r = *reinterpret_cast<const u32x4 *>(res);
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(src);
+                u32x4 y;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) y[d] = add_codes4<FUSED>(v[d], r[d], add_tab, ao);
+                *reinterpret_cast<u32x4 *>(dst) = y;
+            } else {
+                for (int e = 0; e < 16 && n + e < g.N; ++e) dst[e] = (uint8_t)add_code1<FUSED>(src[e], res[e], add_tab, ao);
+            }
+        }
+    };
+    if (ao.fused) add_tile(std::true_type{});
+    else add_tile(std::false_type{});
 }
 
 template <int BM, int BN, int WM, int WN, bool WEIGHTS_X16, int TM, int TN>
@@ -326,7 +367,8 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_kernel(const IgemmArgs g)
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 MFMA tiles");
     constexpr int OUT_PITCH = BN + 16;
     constexpr int STAGE_BYTES = (BM + BN) * BK;
-    constexpr int SMEM_BYTES = (2 * STAGE_BYTES > BM * OUT_PITCH) ? 2 * STAGE_BYTES : BM * OUT_PITCH;
+    constexpr int OUT_BYTES = BM * OUT_PITCH + 4 * WM * WN * TN * 64 + 2048; // tile, column-sum partials, add tables
+    constexpr int SMEM_BYTES = (2 * STAGE_BYTES > OUT_BYTES) ? 2 * STAGE_BYTES : OUT_BYTES;
     __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM_BYTES];
 
     const int tid = threadIdx.x;

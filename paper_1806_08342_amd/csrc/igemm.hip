@@ -166,8 +166,8 @@ static void release_workspace(hipStream_t s, bool capturing)
 template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false>
 static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = SplitK{1, 0, nullptr})
 {
-    constexpr int kStages = NSTAGE * (BM + BN) * 64, kOut = BM * (BN + 16) + 4 * WM * WN * (BN / WN / 32) * 64;
-    constexpr int kLds = kStages > kOut ? kStages : kOut; // operand ring, reused for the output tile + column sums
+    constexpr int kStages = NSTAGE * (BM + BN) * 64, kOut = BM * (BN + 16) + 4 * WM * WN * (BN / WN / 32) * 64 + 2048;
+    constexpr int kLds = kStages > kOut ? kStages : kOut; // operand ring, reused for the output tile + column sums + add tables
     auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE, SPLIT>;
     static bool configured = false; // per instantiation
     if (!configured) {
@@ -240,15 +240,19 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
     const int64_t max_tiles = 0x7ffffff;
     g.small_acc = g.K <= 8192 ? 2 : (g.K <= 16384 ? 1 : 0); // |acc| <= K * 2^14
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
+    g.r_vec16 = g.R != nullptr && aligned_to(g.R, 16) && (g.ldr % 16 == 0);
     if (a_mode == A_MATRIX && shortk_eligible(g, b_mode, false)) return launch_shortk(g, b_mode, false, s);
+    // kernels that do not apply a residual add themselves run without it; the add follows as a second pass
+    auto add_pass = [&](qnn_status st) {
+        if (st != QNN_OK || !g.R) return st;
+        return launch_add_inplace(g.C, g.ldc, g.R, g.ldr, g.M, g.N, g.add, s);
+    };
     {
         qnn_status st;
-        if (try_skinny(g, a_mode, b_mode, vec, s, &st)) return st;
-    }
-
-    {
-        qnn_status st;
-        if (try_bres(g, a_mode, b_mode, s, &st)) return st;
+        IgemmArgs plain = g;
+        plain.R = nullptr;
+        if (try_skinny(plain, a_mode, b_mode, vec, s, &st)) return add_pass(st);
+        if (try_bres(plain, a_mode, b_mode, s, &st)) return add_pass(st);
     }
     const bool mat_or_conv = a_mode == A_MATRIX;
     bool capturing = false, workspace_used = false;
@@ -289,13 +293,15 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
         if (sk.partial && sk.splits > 1) {
             workspace_used = true;
             hipError_t e;
+            IgemmArgs plain = g; // the reduction kernel writes the product's code; the add follows
+            plain.R = nullptr;
             if (cfg == TILE_DMA_128x128)
-                e = mat_or_conv ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, true>(g, s, sk)
-                                : launch_dma<128, 128, 2, 2, A_CONV, 4, true>(g, s, sk);
+                e = mat_or_conv ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, true>(plain, s, sk)
+                                : launch_dma<128, 128, 2, 2, A_CONV, 4, true>(plain, s, sk);
             else
-                e = mat_or_conv ? launch_dma<64, 64, 2, 2, A_MATRIX, 4, true>(g, s, sk)
-                                : launch_dma<64, 64, 2, 2, A_CONV, 4, true>(g, s, sk);
-            return finish(launch_status(e));
+                e = mat_or_conv ? launch_dma<64, 64, 2, 2, A_MATRIX, 4, true>(plain, s, sk)
+                                : launch_dma<64, 64, 2, 2, A_CONV, 4, true>(plain, s, sk);
+            return finish(add_pass(launch_status(e)));
         }
     }
     if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return finish(QNN_EINVAL);
@@ -347,6 +353,101 @@ static int pick_vec(int64_t k_like, std::initializer_list<const void *> ptrs, st
 
 using namespace qnn;
 
+// residual == nullptr: the plain layer; else the add of `add` is applied behind it
+static qnn_status fill_add(IgemmArgs &g, const uint8_t *residual, int64_t ldr, const qnn_add_params *add, int32_t z_mid)
+{
+    if (!residual) return QNN_OK;
+    if (!add || ldr < g.N) return QNN_EINVAL;
+    auto bad_shift = [](int32_t v) { return v < -31 || v > 31; };
+    if (add->left_shift < 0 || add->left_shift > 22 || add->z_r < 0 || add->z_r > 255) return QNN_EINVAL;
+    if (bad_shift(add->shift_m) || bad_shift(add->shift_r) || bad_shift(add->shift_o)) return QNN_EINVAL;
+    if (bad_out_range(add->z_out, add->act_min, add->act_max)) return QNN_EINVAL;
+    g.R = residual, g.ldr = ldr;
+    g.add = AddParams{z_mid,          add->mult_m,  add->shift_m, add->z_r,   add->mult_r,  add->shift_r,
+                      add->left_shift, add->mult_o, add->shift_o, add->z_out, add->act_min, add->act_max};
+    return QNN_OK;
+}
+
+static qnn_status qgemm_impl(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
+                             int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
+                             const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C,
+                             int64_t ldc, void *stream, const uint8_t *residual, int64_t ldr, const qnn_add_params *add)
+{
+    if (!A || !B || !mult || !shift || !C) return QNN_EINVAL;
+    if (M <= 0 || N <= 0 || K <= 0 || K > 65536 || N > 0x7fffffff || lda < K || ldc < N) return QNN_EINVAL;
+    if (z_a < 0 || z_a > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
+    if (weight_bits != 8 && weight_bits != 4) return QNN_EINVAL;
+    if (b_layout != QNN_B_COLUMNS_CONTIGUOUS && b_layout != QNN_B_ROWS_CONTIGUOUS) return QNN_EINVAL;
+    if (b_layout == QNN_B_COLUMNS_CONTIGUOUS ? ldb < K : ldb < N) return QNN_EINVAL;
+    if (weight_bits == 4 && (b_layout != QNN_B_COLUMNS_CONTIGUOUS || (K % 2) || (ldb % 2))) return QNN_EINVAL;
+
+    IgemmArgs g = {};
+    g.A = A, g.lda = lda;
+    g.B = static_cast<const uint8_t *>(B), g.ldb = ldb;
+    g.M = M, g.N = (int32_t)N, g.K = (int32_t)K, g.z_a = z_a;
+    g.bias = bias, g.mult = mult, g.shift = shift;
+    g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
+    g.C = C, g.ldc = ldc;
+    if (qnn_status st = fill_add(g, residual, ldr, add, z_out); st != QNN_OK) return st;
+    int b_mode = weight_bits == 4 ? B_INT4 : (b_layout == QNN_B_ROWS_CONTIGUOUS ? B_INT8_ROWS : B_INT8);
+    int vec = 1;
+    if (b_mode != B_INT8_ROWS) vec = pick_vec(K, {A, B}, {lda, ldb}, weight_bits);
+    return run_igemm(g, A_MATRIX, b_mode, vec, as_stream(stream));
+}
+
+
+static qnn_status qconv2d_impl(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
+                               int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w,
+                               const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_out,
+                               int32_t act_min, int32_t act_max, uint8_t *y, void *stream, const uint8_t *residual,
+                               const qnn_add_params *add)
+{
+    if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
+    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0) return QNN_EINVAL;
+    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return QNN_EINVAL;
+    if (H + 2 * (int64_t)pad_h < kh || W + 2 * (int64_t)pad_w < kw) return QNN_EINVAL;
+    const int64_t K = (int64_t)kh * kw * Cin;
+    if (K > 65536 || z_x < 0 || z_x > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
+    if (weight_bits != 8 && weight_bits != 4) return QNN_EINVAL;
+    if (weight_bits == 4 && (Cin % 2)) return QNN_EINVAL;
+    const int Ho = (H + 2 * pad_h - kh) / stride_h + 1, Wo = (W + 2 * pad_w - kw) / stride_w + 1;
+
+    IgemmArgs g = {};
+    g.A = x;
+    g.H = H, g.W = W, g.Cin = Cin, g.Ho = Ho, g.Wo = Wo, g.kw = kw;
+    g.sh = stride_h, g.sw = stride_w, g.ph = pad_h, g.pw = pad_w;
+    g.magic_cin = magic_for((uint32_t)Cin), g.magic_kw = magic_for((uint32_t)kw);
+    g.B = static_cast<const uint8_t *>(w), g.ldb = K;
+    g.M = (int64_t)N * Ho * Wo, g.N = Cout, g.K = (int32_t)K, g.z_a = z_x;
+    g.bias = bias, g.mult = mult, g.shift = shift;
+    g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
+    g.C = y, g.ldc = Cout;
+    if (qnn_status st = fill_add(g, residual, Cout, add, z_out); st != QNN_OK) return st;
+    g.r_vec16 = g.R != nullptr && aligned_to(g.R, 16) && (g.ldr % 16 == 0);
+    const int b_mode = weight_bits == 4 ? B_INT4 : B_INT8;
+    {
+        qnn_status st;
+        IgemmArgs plain = g; // the stem kernels do not apply a residual add
+        plain.R = nullptr;
+        if (try_stem(plain, N, kh, stride_h, stride_w, weight_bits, as_stream(stream), &st)) {
+            if (st != QNN_OK || !g.R) return st;
+            return launch_add_inplace(g.C, g.ldc, g.R, g.ldr, g.M, g.N, g.add, as_stream(stream));
+        }
+    }
+
+    const bool pointwise = kh == 1 && kw == 1 && stride_h == 1 && stride_w == 1 && pad_h == 0 && pad_w == 0;
+    if (pointwise) { // a 1x1 convolution over NHWC is a plain matrix product
+        g.lda = Cin;
+        return run_igemm(g, A_MATRIX, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
+    }
+    if (kh == 1 && kw == 1 && pad_h == 0 && pad_w == 0 && shortk_eligible(g, b_mode, true)) // strided 1x1: rows are pixels
+        return launch_shortk(g, b_mode, true, as_stream(stream));
+    // pieces must not straddle a tap: the vector width divides Cin
+    return run_igemm(g, A_CONV, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
+}
+
+
+
 extern "C" {
 
 const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K)
@@ -371,25 +472,18 @@ qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, 
                      const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
                      void *stream)
 {
-    if (!A || !B || !mult || !shift || !C) return QNN_EINVAL;
-    if (M <= 0 || N <= 0 || K <= 0 || K > 65536 || N > 0x7fffffff || lda < K || ldc < N) return QNN_EINVAL;
-    if (z_a < 0 || z_a > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
-    if (weight_bits != 8 && weight_bits != 4) return QNN_EINVAL;
-    if (b_layout != QNN_B_COLUMNS_CONTIGUOUS && b_layout != QNN_B_ROWS_CONTIGUOUS) return QNN_EINVAL;
-    if (b_layout == QNN_B_COLUMNS_CONTIGUOUS ? ldb < K : ldb < N) return QNN_EINVAL;
-    if (weight_bits == 4 && (b_layout != QNN_B_COLUMNS_CONTIGUOUS || (K % 2) || (ldb % 2))) return QNN_EINVAL;
+    return qgemm_impl(A, lda, z_a, B, ldb, b_layout, weight_bits, M, N, K, bias, mult, shift, z_out, act_min, act_max, C,
+                      ldc, stream, nullptr, 0, nullptr);
+}
 
-    IgemmArgs g = {};
-    g.A = A, g.lda = lda;
-    g.B = static_cast<const uint8_t *>(B), g.ldb = ldb;
-    g.M = M, g.N = (int32_t)N, g.K = (int32_t)K, g.z_a = z_a;
-    g.bias = bias, g.mult = mult, g.shift = shift;
-    g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
-    g.C = C, g.ldc = ldc;
-    int b_mode = weight_bits == 4 ? B_INT4 : (b_layout == QNN_B_ROWS_CONTIGUOUS ? B_INT8_ROWS : B_INT8);
-    int vec = 1;
-    if (b_mode != B_INT8_ROWS) vec = pick_vec(K, {A, B}, {lda, ldb}, weight_bits);
-    return run_igemm(g, A_MATRIX, b_mode, vec, as_stream(stream));
+qnn_status qnn_qgemm_add(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
+                         int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
+                         const int32_t *shift, int32_t z_mid, int32_t mid_min, int32_t mid_max, const uint8_t *residual,
+                         int64_t ldr, const qnn_add_params *add, uint8_t *C, int64_t ldc, void *stream)
+{
+    if (!residual || !add) return QNN_EINVAL;
+    return qgemm_impl(A, lda, z_a, B, ldb, b_layout, weight_bits, M, N, K, bias, mult, shift, z_mid, mid_min, mid_max, C,
+                      ldc, stream, residual, ldr, add);
 }
 
 qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
@@ -397,41 +491,19 @@ qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z
                        const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
                        uint8_t *y, void *stream)
 {
-    if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
-    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0) return QNN_EINVAL;
-    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return QNN_EINVAL;
-    if (H + 2 * (int64_t)pad_h < kh || W + 2 * (int64_t)pad_w < kw) return QNN_EINVAL;
-    const int64_t K = (int64_t)kh * kw * Cin;
-    if (K > 65536 || z_x < 0 || z_x > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
-    if (weight_bits != 8 && weight_bits != 4) return QNN_EINVAL;
-    if (weight_bits == 4 && (Cin % 2)) return QNN_EINVAL;
-    const int Ho = (H + 2 * pad_h - kh) / stride_h + 1, Wo = (W + 2 * pad_w - kw) / stride_w + 1;
+    return qconv2d_impl(x, N, H, W, Cin, z_x, w, Cout, kh, kw, weight_bits, stride_h, stride_w, pad_h, pad_w, bias, mult,
+                        shift, z_out, act_min, act_max, y, stream, nullptr, nullptr);
+}
 
-    IgemmArgs g = {};
-    g.A = x;
-    g.H = H, g.W = W, g.Cin = Cin, g.Ho = Ho, g.Wo = Wo, g.kw = kw;
-    g.sh = stride_h, g.sw = stride_w, g.ph = pad_h, g.pw = pad_w;
-    g.magic_cin = magic_for((uint32_t)Cin), g.magic_kw = magic_for((uint32_t)kw);
-    g.B = static_cast<const uint8_t *>(w), g.ldb = K;
-    g.M = (int64_t)N * Ho * Wo, g.N = Cout, g.K = (int32_t)K, g.z_a = z_x;
-    g.bias = bias, g.mult = mult, g.shift = shift;
-    g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
-    g.C = y, g.ldc = Cout;
-    const int b_mode = weight_bits == 4 ? B_INT4 : B_INT8;
-    {
-        qnn_status st;
-        if (try_stem(g, N, kh, stride_h, stride_w, weight_bits, as_stream(stream), &st)) return st;
-    }
-
-    const bool pointwise = kh == 1 && kw == 1 && stride_h == 1 && stride_w == 1 && pad_h == 0 && pad_w == 0;
-    if (pointwise) { // a 1x1 convolution over NHWC is a plain matrix product
-        g.lda = Cin;
-        return run_igemm(g, A_MATRIX, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
-    }
-    if (kh == 1 && kw == 1 && pad_h == 0 && pad_w == 0 && shortk_eligible(g, b_mode, true)) // strided 1x1: rows are pixels
-        return launch_shortk(g, b_mode, true, as_stream(stream));
-    // pieces must not straddle a tap: the vector width divides Cin
-    return run_igemm(g, A_CONV, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
+qnn_status qnn_qconv2d_add(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
+                           int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w,
+                           const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_mid,
+                           int32_t mid_min, int32_t mid_max, const uint8_t *residual, const qnn_add_params *add,
+                           uint8_t *y, void *stream)
+{
+    if (!residual || !add) return QNN_EINVAL;
+    return qconv2d_impl(x, N, H, W, Cin, z_x, w, Cout, kh, kw, weight_bits, stride_h, stride_w, pad_h, pad_w, bias, mult,
+                        shift, z_mid, mid_min, mid_max, y, stream, residual, add);
 }
 
 } // extern "C"

@@ -12,6 +12,13 @@ template <int KS, bool INT4, int VEC> static void launch_shortk_one(const ShortK
     constexpr int NB = KS <= 4 ? 4 : 2;
     // weights: 16-byte loads when every 16-element piece of a column is 16-byte aligned, else dwords
     const bool b16 = !INT4 && aligned_to(a.g.B, 16) && (a.g.ldb % 16) == 0 && (a.g.K % 16) == 0;
+    if constexpr (VEC == 16) {
+        if (a.g.R) { // residual add in the store phase (the launcher only leaves R set for VEC == 16)
+            if (b16) hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 16, true>), dim3(blocks), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 4, true>), dim3(blocks), dim3(256), 0, s, a);
+            return;
+        }
+    }
     if (b16) hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 16>), dim3(blocks), dim3(256), 0, s, a);
     else hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 4>), dim3(blocks), dim3(256), 0, s, a);
 }
@@ -58,6 +65,9 @@ qnn_status launch_shortk(IgemmArgs &g, int b_mode, bool strided, hipStream_t s)
     const unsigned blocks = (unsigned)((waves + 3) / 4);
     const int64_t row_pitch = strided ? g.Cin : g.lda;
     const bool v16 = aligned_to(g.A, 16) && (row_pitch % 16) == 0 && (g.K % 16) == 0;
+    // the add is built into the 16-byte variants only, for outputs and residuals made of whole aligned chunks
+    const bool add_pass = g.R != nullptr && !(v16 && g.c_vec16 && g.r_vec16 && (g.N % 16) == 0);
+    if (add_pass) a.g.R = nullptr;
     if (b_mode == B_INT4) {
         if (v16) launch_shortk_ks<true, 16>(a, ks, blocks, s);
         else launch_shortk_ks<true, 8>(a, ks, blocks, s);
@@ -65,7 +75,9 @@ qnn_status launch_shortk(IgemmArgs &g, int b_mode, bool strided, hipStream_t s)
         if (v16) launch_shortk_ks<false, 16>(a, ks, blocks, s);
         else launch_shortk_ks<false, 8>(a, ks, blocks, s);
     }
-    return launch_status(hipGetLastError());
+    const qnn_status st = launch_status(hipGetLastError());
+    if (st != QNN_OK || !add_pass) return st;
+    return launch_add_inplace(g.C, g.ldc, g.R, g.ldr, g.M, g.N, g.add, s);
 }
 
 bool try_skinny(const IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s, qnn_status *status)

@@ -138,4 +138,78 @@ __device__ __forceinline__ int32_t clamp_i32(int32_t lo, int32_t hi, int32_t v)
     return v < lo ? lo : (v > hi ? hi : v);
 }
 
+// ---- rescaling add behind a product (the residual connection of Sec. 3.2.1 fused into the
+// producing layer, as the operator-fusion advice of Sec. 3.2 / 5 recommends).  The product's uint8
+// code m (its own scale and zero-point) and the residual's code r are brought to a common scale
+// and summed: RESCALE_o(RESCALE_m((m - z_m) << L) + RESCALE_r((r - z_r) << L)) + z_out, clamped.
+// The two inner values depend only on an 8-bit code: 2 x 256 entries, tabulated once per workgroup.
+struct AddParams {
+    int32_t z_m, mult_m, shift_m; // the product's code enters the add with these
+    int32_t z_r, mult_r, shift_r; // the residual operand
+    int32_t left_shift, mult_o, shift_o, z_out, act_min, act_max;
+};
+
+// tab[0..255]: codes of the product, tab[256..511]: codes of the residual (LDS, 2 KB)
+__device__ __forceinline__ void add_fill_tables(int32_t *tab, const AddParams &p, int tid, int nthreads)
+{
+    for (int v = tid; v < 512; v += nthreads) {
+        const bool res = v >= 256;
+        const int32_t d = (v & 255) - (res ? p.z_r : p.z_m);
+        tab[v] = rescale_general(d * (1 << p.left_shift), make_rescale(res ? p.mult_r : p.mult_m, res ? p.shift_r : p.shift_m));
+    }
+}
+
+struct AddOut {
+    FusedRescale fo;
+    RescaleParams po;
+    int32_t z_out, lo_rel, hi_rel;
+    bool fused; // both table ranges below 2^28 and 1 <= shift_o <= 20: the 32-bit form is exact
+};
+
+__device__ __forceinline__ AddOut make_add_out(const AddParams &p)
+{
+    AddOut o;
+    o.fo = make_fused(p.mult_o, p.shift_o, 0, p.z_out, p.act_min, p.act_max);
+    o.po = make_rescale(p.mult_o, p.shift_o);
+    o.z_out = p.z_out, o.lo_rel = p.act_min - p.z_out, o.hi_rel = p.act_max - p.z_out;
+    o.fused = p.shift_o >= 1 && p.shift_o <= 20 && p.shift_m >= 0 && p.shift_r >= 0 && p.left_shift <= 20;
+    return o;
+}
+
+// one code of the product + one of the residual -> one output code
+template <bool FUSED> __device__ __forceinline__ uint32_t add_code1(uint32_t m, uint32_t r, const int32_t *tab, const AddOut &o)
+{
+    const int32_t tm = tab[m], tr = tab[256 + r];
+    if constexpr (FUSED) {
+        return (uint32_t)rescale_fused(tm + tr, o.fo);
+    } else {
+        int64_t u = (int64_t)tm + (int64_t)tr;
+        u = u > INT32_MAX ? INT32_MAX : (u < INT32_MIN ? INT32_MIN : u);
+        return (uint32_t)(clamp_i32(o.lo_rel, o.hi_rel, rescale_general((int32_t)u, o.po)) + o.z_out);
+    }
+}
+
+// four codes of the product (bytes of m) + four of the residual (bytes of r) -> four output codes
+template <bool FUSED> __device__ __forceinline__ uint32_t add_codes4(uint32_t m, uint32_t r, const int32_t *tab, const AddOut &o)
+{
+    uint32_t x = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int32_t tm = tab[(m >> (8 * e)) & 0xffu], tr = tab[256 + ((r >> (8 * e)) & 0xffu)];
+        if constexpr (FUSED) {
+            x = shift_into_byte(x, rescale_fused_w(tm + tr, o.fo), o.fo.n1, e);
+        } else {
+            int64_t u = (int64_t)tm + (int64_t)tr;
+            u = u > INT32_MAX ? INT32_MAX : (u < INT32_MIN ? INT32_MIN : u);
+            x |= (uint32_t)(clamp_i32(o.lo_rel, o.hi_rel, rescale_general((int32_t)u, o.po)) + o.z_out) << (8 * e);
+        }
+    }
+    return x;
+}
+
+// y[m][n] = ADD(y[m][n], r[m][n]) in place (elementwise.hip): the second pass of the kernels that
+// do not apply the add themselves
+qnn_status launch_add_inplace(uint8_t *y, int64_t ldy, const uint8_t *r, int64_t ldr, int64_t M, int32_t N,
+                              const AddParams &p, hipStream_t s);
+
 } // namespace qnn

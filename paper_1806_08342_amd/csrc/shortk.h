@@ -60,12 +60,19 @@ struct ShortKColumn {
     int32_t mult, corr, c, n1, lo, hi, shift;
 };
 
-template <int NB, int KS, bool INT4, int VEC, int BVEC>
+// ADD: the rescaling add with a residual tensor (g.R) is applied to the output tile on its way
+// from LDS to global memory; the residual chunks of a row block are requested one round ahead.
+template <int NB, int KS, bool INT4, int VEC, int BVEC, bool ADD = false>
 __global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const ShortKArgs s)
 {
     constexpr int PITCH = 32 * NB + 32; // bytes per staged output row: the 8 rows a store instruction touches fall in distinct banks
     __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][32 * PITCH];
+    __shared__ int32_t add_tab[ADD ? 512 : 1];
     const IgemmArgs &g = s.g;
+    if constexpr (ADD) { // the only workgroup barrier, before any wave may leave
+        add_fill_tables(add_tab, g.add, threadIdx.x, 256);
+        __syncthreads();
+    }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform: row-block arithmetic stays scalar
     uint8_t *stage = stage_all[wave];
@@ -171,15 +178,53 @@ __global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const Sh
     const uint32_t sel2 = (quad_lane & 2) ? 0x03020706u : 0x05040100u;
     const int32_t lo_rel = g.lo_rel, hi_rel = g.hi_rel, z_out = g.z_out;
 
+    // residual chunks of a row block (ADD): same lanes and addresses as the stores of that block
+    const AddOut ao = make_add_out(g.add);
+    int64_t st_roff[NB];
+    u32x4 rres[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        st_roff[i] = (int64_t)st_row[i] * g.ldr + (n0 + (i * 64 + lane) % (2 * NB) * 16);
+        rres[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+    auto load_res = [&](int rbx) __attribute__((always_inline)) {
+        const uint8_t *const r_block = g.R + (int64_t)rbx * 32 * g.ldr; // wave-uniform
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+            if (st_col_ok[i] && rbx * 32 + st_row[i] < M) rres[i] = *reinterpret_cast<const u32x4 *>(r_block + st_roff[i]);
+    };
+    auto add16 = [&](u32x4 v, u32x4 r) __attribute__((always_inline)) {
+        u32x4 y;
+        if (ao.fused) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                y[d] = add_codes4<true>(v[d], r[d], add_tab, ao);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma nounroll
+            for (int d = 0; d < 4; ++d) y[d] = add_codes4<false>(v[d], r[d], add_tab, ao);
+        }
+        return y;
+    };
+
     // the output tile of row block rbx, from the wave's LDS area to global memory.  Called one
     // round late, right after the next block's MFMAs are issued and before the loads of the block
     // after it: the stores then never sit between a load and the wait for that load.
-    auto store_block = [&](int rbx) {
+    auto store_block = [&](int rbx) __attribute__((always_inline)) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         uint8_t *const c_block = g.C + (int64_t)rbx * 32 * g.ldc; // wave-uniform
-        if (chunks_whole && rbx * 32 + 32 <= M) { // the common case: only the lane-invariant column test
+        if constexpr (ADD) { // the launcher uses ADD only when every output chunk is a whole, aligned 16-byte chunk
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                if (st_col_ok[i] && rbx * 32 + st_row[i] < M)
+                    *reinterpret_cast<u32x4 *>(c_block + st_off[i]) =
+                        add16(*reinterpret_cast<const u32x4 *>(stage + st_lds[i]), rres[i]);
+                __builtin_amdgcn_sched_barrier(0); // one chunk at a time: the table reads of all chunks at once would spill
+            }
+        } else if (chunks_whole && rbx * 32 + 32 <= M) { // the common case: only the lane-invariant column test
 #pragma unroll
             for (int i = 0; i < NB; ++i)
                 if (st_col_ok[i])
@@ -228,6 +273,7 @@ __global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const Sh
                 acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xs, fb[ks][j], acc[j], 0, 0, 0); // columns past N: clamped loads, never stored
         }
         if (rb_stored >= 0) store_block(rb_stored);
+        if constexpr (ADD) load_res(rb); // used one round from now, when this block is stored
         // the fragments are consumed: fetch the next block's into the same registers now, so that
         // the loads are in flight during the epilogue
         if (rb + s.walkers < row_blocks) load_rows(rb + s.walkers, fa);

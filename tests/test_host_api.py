@@ -124,6 +124,23 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     assert lib.qnn_qadd(p, 0, 1, 40, p, 0, 1, 0, 20, 1, 0, 0, 0, 255, p, 16, None) == EINVAL  # shift out of range
     assert lib.qnn_qadd(null, 0, 1, 0, null, 0, 1, 0, 20, 1, 0, 0, 0, 255, null, 0, None) == 0
     assert lib.qnn_pack_b(p, 4, 8, 8, p, 8, None) == EINVAL  # ld_src < N
+    # the fused add: every field is checked on the host before anything is launched
+    fields = dict(mult_m=1 << 30, shift_m=1, z_r=0, mult_r=1 << 30, shift_r=1, left_shift=20, mult_o=1 << 30, shift_o=10,
+                  z_out=0, act_min=0, act_max=255)
+    def gemm_add(residual=p, ldr=64, **kw):
+        add = binding._AddParams(**{**fields, **kw})
+        return lib.qnn_qgemm_add(p, 64, 0, p, 64, 0, 8, 64, 64, 64, null, p, p, 0, 0, 255, residual, ldr, C.addressof(add),
+                                 p, 64, None)
+    assert gemm_add(residual=null) == EINVAL
+    assert gemm_add(ldr=8) == EINVAL
+    assert gemm_add(left_shift=23) == EINVAL
+    assert gemm_add(shift_o=32) == EINVAL
+    assert gemm_add(z_r=256) == EINVAL
+    assert gemm_add(act_min=9, act_max=3) == EINVAL
+    assert lib.qnn_qgemm_add(p, 64, 0, p, 64, 0, 8, 64, 64, 64, null, p, p, 0, 0, 255, p, 64, null, p, 64, None) == EINVAL
+    add = binding._AddParams(**fields)
+    assert lib.qnn_qconv2d_add(p, 1, 8, 8, 16, 0, p, 8, 3, 3, 8, 1, 1, 1, 1, null, p, p, 0, 0, 255, null, C.addressof(add),
+                               p, None) == EINVAL
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

@@ -6,5 +6,5 @@ quantizer-parameter helpers it needs (choose_qparams, quantize_multipliers, act_
 pack_int4, quantize_weights) are passed in by the caller -- the oracle's in the tests, the
 library's own host helpers in the benchmark.
 """
-from .shapes import Layer, gemm_sweep, mobilenet_v1, mobilenet_v2, resnet50, single_conv  # noqa: F401
+from .shapes import Layer, fuse_adds, gemm_sweep, mobilenet_v1, mobilenet_v2, resnet50, single_conv  # noqa: F401
 from .synth import SEED_BASE, conv_case, gemm_case, qadd_case, quantize_case, seed_for  # noqa: F401

@@ -14,7 +14,7 @@ from typing import List, Tuple
 @dataclass(frozen=True)
 class Layer:
     name: str
-    kind: str  # "conv", "dw", "qadd"
+    kind: str  # "conv", "dw", "qadd", "conv_add" (a convolution with the residual add fused behind it)
     H: int
     W: int
     Cin: int
@@ -49,7 +49,8 @@ class Layer:
         if self.kind == "qadd":
             return 3 * batch * self.H * self.W * self.Cout
         w_bytes = self.K * self.Cout * self.weight_bits // 8
-        return batch * (self.H * self.W * self.Cin + self.Ho * self.Wo * self.Cout) + w_bytes + 12 * self.Cout
+        residual = batch * self.Ho * self.Wo * self.Cout if self.kind == "conv_add" else 0
+        return batch * (self.H * self.W * self.Cin + self.Ho * self.Wo * self.Cout) + residual + w_bytes + 12 * self.Cout
 
 
 def single_conv() -> List[Layer]:
@@ -124,6 +125,28 @@ def mobilenet_v2(weight_bits: int = 4) -> List[Layer]:
             idx += 1
     layers.append(Layer("head", "conv", h, h, 320, 1280, k=1, weight_bits=wb))
     return layers
+
+
+def fuse_adds(layers: List[Layer]) -> List[Layer]:
+    """The same network with every residual add folded into the convolution that produces its
+    first operand (the last 1x1 of the block): that layer becomes a "conv_add" carrying the
+    add's activation, and the separate "qadd" entry disappears."""
+    out: List[Layer] = []
+    for l in layers:
+        if l.kind == "qadd":
+            for back in (1, 2):  # the producing 1x1 is the previous layer, or the one before a projection shortcut
+                if back > len(out):
+                    continue  # not enough layers before the add to look this far back
+                p = out[-back]
+                if p.kind == "conv" and p.act == "none" and (p.Ho, p.Wo, p.Cout) == (l.H, l.W, l.Cout) and \
+                        not p.name.endswith("_proj"):
+                    out[-back] = replace(p, kind="conv_add", act=l.act, name=p.name + "+add")
+                    break
+            else:
+                out.append(l)
+            continue
+        out.append(l)
+    return out
 
 
 def unique_shapes(layers: List[Layer]) -> List[Layer]:
