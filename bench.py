@@ -198,6 +198,23 @@ def time_stack(torch, qnn, workloads, synth, layers, batch, config_id, reps):
                 layers=rows)
 
 
+def time_asym(torch, qnn):
+    """asymmetric per-channel weights (a zero-point per column) against the symmetric product, two shapes"""
+    out = {}
+    for (M, N, K) in [(4096, 4096, 4096), (50176, 256, 1024)]:
+        A = _device_uint8(torch, (M, K), 11)
+        Bt = _device_uint8(torch, (N, K), 12).view(torch.int8)
+        z_w = (torch.arange(N, dtype=torch.int32, device="cuda:0") % 41) - 20
+        mult = torch.full((N,), 1 << 30, dtype=torch.int32, device="cuda:0")
+        shift = torch.full((N,), 16, dtype=torch.int32, device="cuda:0")
+        Cm = torch.empty((M, N), dtype=torch.uint8, device="cuda:0")
+        t_sym = time_kernel(torch, lambda: qnn.qgemm(A, 128, Bt, mult, shift, 128, 0, 255, out=Cm), reps=5)
+        t_asym = time_kernel(torch, lambda: qnn.qgemm_asym(A, 128, Bt, z_w, mult, shift, 128, 0, 255, out=Cm), reps=5)
+        out[f"{M}x{N}x{K}"] = dict(us=round(t_asym * 1e6, 1), tops=round(2e-12 * M * N * K / t_asym, 1),
+                                  symmetric_us=round(t_sym * 1e6, 1))
+    return out
+
+
 def time_streaming(torch, qnn):
     """quantize / dequantize / requantize / qadd on configuration 5's 256x224x224x3 tensor size"""
     n = 256 * 224 * 224 * 3
@@ -332,6 +349,7 @@ def main():
     if not args.no_secondary:
         sec = {}
         sec["streaming"] = time_streaming(torch, qnn)
+        sec["asymmetric_weights"] = time_asym(torch, qnn)
         sec["mobilenet_v1_b64"] = time_stack(torch, qnn, workloads, synth, workloads.mobilenet_v1(), 64, 3, 5)
         sec["mobilenet_v1_b1"] = time_stack(torch, qnn, workloads, synth, workloads.mobilenet_v1(), 1, 3, 5)
         # residual adds fused behind the last 1x1 of their block (qnn_qconv2d_add); the figure with

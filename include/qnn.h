@@ -193,6 +193,28 @@ qnn_status qnn_qconv2d_add(const uint8_t *x, int N, int H, int W, int Cin, int32
                            int32_t mid_min, int32_t mid_max, const uint8_t *residual, const qnn_add_params *add,
                            uint8_t *y, void *stream);
 
+/* The same layers with asymmetric per-channel weights: column / output channel n carries its own
+ * zero-point z_w[n] (Sec. 2.1 affine quantizer applied per channel, Sec. 2.2; the scheme the
+ * post-training experiments of Sec. 3.1 find most accurate).  The sum becomes
+ *   sum_k (A[m][k] - z_a) * (B[k][n] - z_w[n])
+ * = sum_k A*B - z_a * sum_k B[k][n] - z_w[n] * sum_k A[m][k] + K * z_a * z_w[n]        (eq. 5-6)
+ * The activation sums of the third term are shared by all channels: one extra pass over A forms
+ * them per output row (for a convolution: over the taps inside the image; padding holds the code
+ * z_x and adds nothing), into the library's scratch block (see above; QNN_EUNSUPPORTED if the block
+ * cannot be had, e.g. first use during stream capture, or M > 8 Mi rows).
+ * z_w: DEVICE int32[N] (resp. [Cout]), each in [-128, 127] for 8-bit and [-8, 7] for 4-bit weights.
+ * K (resp. kh*kw*Cin) <= 32768, which keeps |sum| below 2^31.  Everything else as in qnn_qgemm /
+ * qnn_qconv2d. */
+qnn_status qnn_qgemm_asym(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
+                          int weight_bits, const int32_t *z_w, int64_t M, int64_t N, int64_t K, const int32_t *bias,
+                          const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
+                          uint8_t *C, int64_t ldc, void *stream);
+
+qnn_status qnn_qconv2d_asym(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
+                            int kw, int weight_bits, const int32_t *z_w, int stride_h, int stride_w, int pad_h, int pad_w,
+                            const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_out,
+                            int32_t act_min, int32_t act_max, uint8_t *y, void *stream);
+
 /* ------------------------------------------------------------------ host-only helpers */
 
 /* Quantizer parameters from a real range, Sec. 2.1: the range is first widened to contain 0,

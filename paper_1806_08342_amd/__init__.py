@@ -19,9 +19,11 @@ from .binding import (  # noqa: F401
     qadd_params,
     qconv2d,
     qconv2d_add,
+    qconv2d_asym,
     qdwconv2d,
     qgemm,
     qgemm_add,
+    qgemm_asym,
     qgemm_plan,
     quantize,
     quantize_multiplier,
@@ -32,6 +34,6 @@ from .binding import (  # noqa: F401
 
 __all__ = [
     "QnnError", "act_range", "choose_qparams", "dequantize", "library_path", "load_library", "pack_b", "pack_int4", "prepare_qgemm",
-    "qadd", "qadd_params", "qconv2d", "qconv2d_add", "qdwconv2d", "qgemm", "qgemm_add", "qgemm_plan", "quantize", "quantize_multiplier",
+    "qadd", "qadd_params", "qconv2d", "qconv2d_add", "qconv2d_asym", "qdwconv2d", "qgemm", "qgemm_add", "qgemm_asym", "qgemm_plan", "quantize", "quantize_multiplier",
     "quantize_multipliers", "quantize_weights", "requantize",
 ]

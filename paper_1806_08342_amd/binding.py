@@ -20,7 +20,7 @@ B_COLUMNS_CONTIGUOUS, B_ROWS_CONTIGUOUS = 0, 1
 
 EXPORTS = [
     "qnn_last_error", "qnn_version", "qnn_qgemm_plan", "qnn_quantize", "qnn_dequantize", "qnn_requantize", "qnn_qgemm", "qnn_pack_b",
-    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
+    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
     "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4",
 ]
 
@@ -58,6 +58,8 @@ def load_library():
         "qnn_qgemm": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
         "qnn_pack_b": [vp, i64, i64, i64, vp, i64, vp],
         "qnn_qconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
+        "qnn_qgemm_asym": [vp, i64, i32, vp, i64, ci, ci, vp, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
+        "qnn_qconv2d_asym": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
         "qnn_qgemm_add": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, vp, i64, vp],
         "qnn_qconv2d_add": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp,
                             vp, vp],
@@ -334,6 +336,40 @@ def qconv2d_add(x, z_x, w, stride, pad, mult, shift, z_mid, mid_min, mid_max, re
         pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"),
         z_mid, mid_min, mid_max, _dev(residual, torch.uint8, "residual"), C.addressof(add),
         _dev(y, torch.uint8, "y"), _stream()))
+    return y
+
+
+def qgemm_asym(A, z_a, B, z_w, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8, out=None):
+    """qgemm with a zero-point per weight column: z_w int32 [N] on the device.  B: int8 [N,K] (columns
+    contiguous) or uint8 [N,K/2] nibble-packed."""
+    torch = _torch()
+    M, K = A.shape
+    if weight_bits == 4:
+        N, ldb, bp = B.shape[0], B.shape[1] * 2, _dev(B, torch.uint8, "B")
+    else:
+        (N, ldb), bp = B.shape, _dev(B, torch.int8, "B")
+    Cm = torch.empty((M, N), dtype=torch.uint8, device=A.device) if out is None else out
+    ap, lda = _dev_rows(A, torch.uint8, "A")
+    cp, ldc = _dev_rows(Cm, torch.uint8, "C")
+    _check("qnn_qgemm_asym", load_library().qnn_qgemm_asym(
+        ap, lda, z_a, bp, ldb, B_COLUMNS_CONTIGUOUS, weight_bits, _dev(z_w, torch.int32, "z_w"), M, N, K,
+        _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out,
+        act_min, act_max, cp, ldc, _stream()))
+    return Cm
+
+
+def qconv2d_asym(x, z_x, w, z_w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8, out=None):
+    """qconv2d with a zero-point per output channel: z_w int32 [Cout] on the device."""
+    torch = _torch()
+    N, H, W, Cin = x.shape
+    Cout, kh, kw = w.shape[:3]
+    wp = _dev(w, torch.uint8 if weight_bits == 4 else torch.int8, "w")
+    Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
+    y = torch.empty((N, Ho, Wo, Cout), dtype=torch.uint8, device=x.device) if out is None else out
+    _check("qnn_qconv2d_asym", load_library().qnn_qconv2d_asym(
+        _dev(x, torch.uint8, "x"), N, H, W, Cin, z_x, wp, Cout, kh, kw, weight_bits, _dev(z_w, torch.int32, "z_w"),
+        stride[0], stride[1], pad[0], pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"),
+        _dev(shift, torch.int32, "shift"), z_out, act_min, act_max, _dev(y, torch.uint8, "y"), _stream()))
     return y
 
 

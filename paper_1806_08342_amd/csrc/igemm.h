@@ -49,6 +49,9 @@ struct IgemmArgs {
     int64_t ldc;
     int32_t c_vec16;  // C and ldc are 16-byte aligned
     int32_t small_acc; // 2: |acc| and the zero-point correction are each below 2^27; 1: below 2^28; 0: unknown
+    // optional per-column weight zero-points (eq. 5-6 with z_w != 0): zw[n] and the row sums
+    // rowsum[m] = sum_k (A[m][k] - z_a) over the taps inside the image (both int32, device); nullptr: z_w = 0
+    const int32_t *zw, *rowsum;
     // optional rescaling add behind the product: C = ADD(code of the product, R); R == nullptr: none
     const uint8_t *R;
     int64_t ldr;
@@ -187,7 +190,7 @@ __device__ __forceinline__ void load_b_chunk(const IgemmArgs &g, int n, int kc, 
 // Per-channel epilogue parameters of the TN column tiles a lane owns; fetched at kernel start
 // so that their global-memory latency is hidden behind the main loop.
 template <int TN> struct ChannelParams {
-    int32_t bias[TN], mult[TN], shift[TN];
+    int32_t bias[TN], mult[TN], shift[TN], zw[TN];
 };
 
 template <int BN, int WN, int TN>
@@ -199,9 +202,10 @@ __device__ __forceinline__ ChannelParams<TN> load_channel_params(const IgemmArgs
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int n = n0 + wave_n * WTN + j * 32 + (lane & 31);
-        p.bias[j] = 0, p.mult[j] = 0, p.shift[j] = 1;
+        p.bias[j] = 0, p.mult[j] = 0, p.shift[j] = 1, p.zw[j] = 0;
         if (n < g.N) {
             p.bias[j] = g.bias ? g.bias[n] : 0;
+            p.zw[j] = g.zw ? g.zw[n] : 0;
             p.mult[j] = g.mult[n];
             p.shift[j] = g.shift[n];
         }
@@ -209,7 +213,9 @@ __device__ __forceinline__ ChannelParams<TN> load_channel_params(const IgemmArgs
     return p;
 }
 
-template <int BM, int BN, int WM, int WN, bool WEIGHTS_X16, int TM, int TN>
+// ZW: per-column weight zero-points; the term - z_w[n] * rowsum[m] joins every accumulator (the
+// tile's row sums are staged in LDS behind the add tables)
+template <int BM, int BN, int WM, int WN, bool WEIGHTS_X16, bool ZW, int TM, int TN>
 __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (&acc)[TM][TN], int32_t (&colsum)[TN],
                                                     const ChannelParams<TN> &cp, uint8_t *so, int64_t m0, int n0)
 {
@@ -217,11 +223,13 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int OUT_PITCH = BN + 16;
     constexpr int ADD_TABLE_OFFSET = BM * OUT_PITCH + 4 * WM * WN * TN * 64; // behind the tile and the column-sum partials
+    constexpr int ROWSUM_OFFSET = ADD_TABLE_OFFSET + 2048;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / WN, wave_n = wave % WN;
     const int frag_row = lane & 31, frag_half = lane >> 5;
-    bool fast_ok = g.small_acc >= 1, fused_ok = g.small_acc >= 2;
+    // with weight zero-points |z_w * rowsum| <= 2^15 * K joins the sum: the 32-bit forms stay exact for K <= 2048
+    bool fast_ok = g.small_acc >= 1 && (!ZW || g.K <= 4096), fused_ok = g.small_acc >= 2 && (!ZW || g.K <= 2048);
     int32_t corr[TN];
     RescaleParams rp[TN];
     FusedRescale fr[TN];
@@ -256,6 +264,11 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
         const int col = wave_n * WTN + j * 32 + (frag_row & ~3);
         *reinterpret_cast<uint32_t *>(so + row * OUT_PITCH + col) = x;
     };
+    int32_t *const rs_lds = reinterpret_cast<int32_t *>(so + ROWSUM_OFFSET);
+    if constexpr (ZW) { // the caller has synchronised: the operand ring is free
+        for (int r = tid; r < BM; r += NT) rs_lds[r] = m0 + r < g.M ? g.rowsum[m0 + r] : 0;
+        __syncthreads();
+    }
     auto run = [&](auto pack4) {
 #pragma clang loop unroll(full)
         for (int i = 0; i < TM; ++i)
@@ -264,10 +277,14 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
 #pragma clang loop unroll(full)
                 for (int q = 0; q < 4; ++q) {
                     int32_t a[4];
+                    i32x4 rs4 = {0, 0, 0, 0};
+                    if constexpr (ZW) // rows 8q + 4*half + {0,1,2,3} of this 32-row tile
+                        rs4 = *reinterpret_cast<const i32x4 *>(rs_lds + wave_m * WTM + i * 32 + 8 * q + 4 * frag_half);
 #pragma clang loop unroll(full)
                     for (int e = 0; e < 4; ++e) {
                         a[e] = acc[i][j][4 * q + e];
                         if (WEIGHTS_X16) a[e] >>= 4; // weights were staged times 16; exact
+                        if constexpr (ZW) a[e] = (int32_t)((uint32_t)a[e] - (uint32_t)cp.zw[j] * (uint32_t)rs4[e]); // wraps like the sum it is part of
                     }
                     store_group(i, j, q, pack4(a, j));
                 }
@@ -348,14 +365,14 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
     else add_tile(std::false_type{});
 }
 
-template <int BM, int BN, int WM, int WN, bool WEIGHTS_X16, int TM, int TN>
+template <int BM, int BN, int WM, int WN, bool WEIGHTS_X16, bool ZW = false, int TM, int TN>
 __device__ __forceinline__ void igemm_epilogue(const IgemmArgs &g, i32x16 (&acc)[TM][TN], int32_t (&colsum)[TN],
                                                const ChannelParams<TN> &cp, uint8_t *so, int64_t m0, int n0)
 {
-    igemm_epilogue_impl<BM, BN, WM, WN, WEIGHTS_X16, TM, TN>(g, acc, colsum, cp, so, m0, n0);
+    igemm_epilogue_impl<BM, BN, WM, WN, WEIGHTS_X16, ZW, TM, TN>(g, acc, colsum, cp, so, m0, n0);
 }
 
-template <int BM, int BN, int WM, int WN, int A_MODE, int B_MODE, int VEC>
+template <int BM, int BN, int WM, int WN, int A_MODE, int B_MODE, int VEC, bool ZW = false>
 __global__ void __launch_bounds__(WM *WN * 64) igemm_kernel(const IgemmArgs g)
 {
     constexpr int NT = WM * WN * 64;
@@ -367,7 +384,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_kernel(const IgemmArgs g)
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 MFMA tiles");
     constexpr int OUT_PITCH = BN + 16;
     constexpr int STAGE_BYTES = (BM + BN) * BK;
-    constexpr int OUT_BYTES = BM * OUT_PITCH + 4 * WM * WN * TN * 64 + 2048; // tile, column-sum partials, add tables
+    constexpr int OUT_BYTES = BM * OUT_PITCH + 4 * WM * WN * TN * 64 + 2048 + 4 * BM; // tile, column-sum partials, add tables, row sums
     constexpr int SMEM_BYTES = (2 * STAGE_BYTES > OUT_BYTES) ? 2 * STAGE_BYTES : OUT_BYTES;
     __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM_BYTES];
 
@@ -475,7 +492,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_kernel(const IgemmArgs g)
     }
 
     // the last __syncthreads above guarantees nobody still reads the operand tiles
-    igemm_epilogue<BM, BN, WM, WN, B_MODE == B_INT4>(g, acc, colsum, cparams, smem, m0, n0);
+    igemm_epilogue<BM, BN, WM, WN, B_MODE == B_INT4, ZW>(g, acc, colsum, cparams, smem, m0, n0);
 }
 
 } // namespace qnn

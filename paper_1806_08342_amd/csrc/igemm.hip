@@ -163,12 +163,13 @@ static void release_workspace(hipStream_t s, bool capturing)
     if (hipEventRecord(w.done, s) == hipSuccess) w.used = true, w.last = s;
 }
 
-template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false>
+template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false, bool ZW = false>
 static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = SplitK{1, 0, nullptr})
 {
-    constexpr int kStages = NSTAGE * (BM + BN) * 64, kOut = BM * (BN + 16) + 4 * WM * WN * (BN / WN / 32) * 64 + 2048;
+    constexpr int kStages = NSTAGE * (BM + BN) * 64;
+    constexpr int kOut = BM * (BN + 16) + 4 * WM * WN * (BN / WN / 32) * 64 + 2048 + 4 * BM; // + add tables + row sums
     constexpr int kLds = kStages > kOut ? kStages : kOut; // operand ring, reused for the output tile + column sums + add tables
-    auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE, SPLIT>;
+    auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE, SPLIT, ZW>;
     static bool configured = false; // per instantiation
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -233,14 +234,50 @@ __global__ void __launch_bounds__(256) unpack_int4_kernel(const uint8_t *__restr
     *reinterpret_cast<u32x4 *>(dst + (int64_t)n * K + p * 16) = out;
 }
 
+// Per-column weight zero-points (eq. 5-6 with z_w != 0): the activation row sums go to the scratch
+// block first (one pass over A), then one tile configuration whose epilogue subtracts
+// z_w[n] * rowsum[m]: the pipelined 128x128 tile when the operands are aligned, else the staged
+// 64x64 tile.  No split-K (the scratch block holds the row sums).
+static qnn_status run_igemm_zw(IgemmArgs &g, int a_mode, int b_mode, int vec, int kh, hipStream_t s)
+{
+    if (g.M * 4 > (int64_t)kSplitBytes) return QNN_EUNSUPPORTED;
+    const bool capturing = stream_is_capturing(s);
+    int32_t *workspace = acquire_workspace(s, capturing);
+    if (!workspace) return QNN_EUNSUPPORTED; // no scratch block yet and none may be allocated during capture
+    auto finish = [&](qnn_status st) {
+        release_workspace(s, capturing);
+        return st;
+    };
+    if (qnn_status st = launch_rowsum(g, a_mode, kh, workspace, s); st != QNN_OK) return finish(st);
+    g.rowsum = workspace;
+    const bool aligned_for_dma = vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23);
+    if (b_mode == B_INT4 && aligned_for_dma && (int64_t)g.N * g.K <= (int64_t)kUnpackBytes) {
+        int8_t *unpacked = reinterpret_cast<int8_t *>(workspace) + kSplitBytes;
+        const int64_t threads = (int64_t)g.N * (g.K / 16);
+        hipLaunchKernelGGL(unpack_int4_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, g.B, g.ldb / 2, g.N,
+                           g.K, unpacked);
+        g.B = reinterpret_cast<const uint8_t *>(unpacked), g.ldb = g.K;
+        b_mode = B_INT8;
+    }
+    if (b_mode == B_INT8 && aligned_for_dma && ((g.M + 127) / 128) * ((g.N + 127) / 128) <= 0x7ffffff) {
+        const hipError_t e = a_mode == A_MATRIX ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, false, true>(g, s)
+                                                : launch_dma<128, 128, 2, 2, A_CONV, 4, false, true>(g, s);
+        return finish(launch_status(e));
+    }
+    if (((g.M + 63) / 64) * ((g.N + 63) / 64) > 0x7ffffff) return finish(QNN_EINVAL);
+    launch_plain_tile_zw(g, a_mode, b_mode, vec, s);
+    return finish(launch_status(hipGetLastError()));
+}
+
 // Shared back end.  `vec` is the widest staging vector (in k elements) that the alignment
 // of A, B and K allows.
-static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s)
+static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s, int kh = 1)
 {
     const int64_t max_tiles = 0x7ffffff;
     g.small_acc = g.K <= 8192 ? 2 : (g.K <= 16384 ? 1 : 0); // |acc| <= K * 2^14
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
     g.r_vec16 = g.R != nullptr && aligned_to(g.R, 16) && (g.ldr % 16 == 0);
+    if (g.zw) return run_igemm_zw(g, a_mode, b_mode, vec, kh, s);
     if (a_mode == A_MATRIX && shortk_eligible(g, b_mode, false)) return launch_shortk(g, b_mode, false, s);
     // kernels that do not apply a residual add themselves run without it; the add follows as a second pass
     auto add_pass = [&](qnn_status st) {
@@ -371,7 +408,8 @@ static qnn_status fill_add(IgemmArgs &g, const uint8_t *residual, int64_t ldr, c
 static qnn_status qgemm_impl(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
                              int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
                              const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C,
-                             int64_t ldc, void *stream, const uint8_t *residual, int64_t ldr, const qnn_add_params *add)
+                             int64_t ldc, void *stream, const uint8_t *residual, int64_t ldr, const qnn_add_params *add,
+                             const int32_t *z_w = nullptr)
 {
     if (!A || !B || !mult || !shift || !C) return QNN_EINVAL;
     if (M <= 0 || N <= 0 || K <= 0 || K > 65536 || N > 0x7fffffff || lda < K || ldc < N) return QNN_EINVAL;
@@ -389,6 +427,8 @@ static qnn_status qgemm_impl(const uint8_t *A, int64_t lda, int32_t z_a, const v
     g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
     g.C = C, g.ldc = ldc;
     if (qnn_status st = fill_add(g, residual, ldr, add, z_out); st != QNN_OK) return st;
+    g.zw = z_w;
+    if (z_w && K > 32768) return QNN_EINVAL; // |sum| < 2^31 needs K * 255 * 255 < 2^31 once z_w != 0
     int b_mode = weight_bits == 4 ? B_INT4 : (b_layout == QNN_B_ROWS_CONTIGUOUS ? B_INT8_ROWS : B_INT8);
     int vec = 1;
     if (b_mode != B_INT8_ROWS) vec = pick_vec(K, {A, B}, {lda, ldb}, weight_bits);
@@ -400,7 +440,7 @@ static qnn_status qconv2d_impl(const uint8_t *x, int N, int H, int W, int Cin, i
                                int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w,
                                const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_out,
                                int32_t act_min, int32_t act_max, uint8_t *y, void *stream, const uint8_t *residual,
-                               const qnn_add_params *add)
+                               const qnn_add_params *add, const int32_t *z_w = nullptr)
 {
     if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
     if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0) return QNN_EINVAL;
@@ -424,8 +464,10 @@ static qnn_status qconv2d_impl(const uint8_t *x, int N, int H, int W, int Cin, i
     g.C = y, g.ldc = Cout;
     if (qnn_status st = fill_add(g, residual, Cout, add, z_out); st != QNN_OK) return st;
     g.r_vec16 = g.R != nullptr && aligned_to(g.R, 16) && (g.ldr % 16 == 0);
+    g.zw = z_w;
+    if (z_w && K > 32768) return QNN_EINVAL;
     const int b_mode = weight_bits == 4 ? B_INT4 : B_INT8;
-    {
+    if (!z_w) {
         qnn_status st;
         IgemmArgs plain = g; // the stem kernels do not apply a residual add
         plain.R = nullptr;
@@ -440,10 +482,10 @@ static qnn_status qconv2d_impl(const uint8_t *x, int N, int H, int W, int Cin, i
         g.lda = Cin;
         return run_igemm(g, A_MATRIX, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
     }
-    if (kh == 1 && kw == 1 && pad_h == 0 && pad_w == 0 && shortk_eligible(g, b_mode, true)) // strided 1x1: rows are pixels
+    if (!z_w && kh == 1 && kw == 1 && pad_h == 0 && pad_w == 0 && shortk_eligible(g, b_mode, true)) // strided 1x1: rows are pixels
         return launch_shortk(g, b_mode, true, as_stream(stream));
     // pieces must not straddle a tap: the vector width divides Cin
-    return run_igemm(g, A_CONV, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
+    return run_igemm(g, A_CONV, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream), kh);
 }
 
 
@@ -484,6 +526,26 @@ qnn_status qnn_qgemm_add(const uint8_t *A, int64_t lda, int32_t z_a, const void 
     if (!residual || !add) return QNN_EINVAL;
     return qgemm_impl(A, lda, z_a, B, ldb, b_layout, weight_bits, M, N, K, bias, mult, shift, z_mid, mid_min, mid_max, C,
                       ldc, stream, residual, ldr, add);
+}
+
+qnn_status qnn_qgemm_asym(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
+                          int weight_bits, const int32_t *z_w, int64_t M, int64_t N, int64_t K, const int32_t *bias,
+                          const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
+                          uint8_t *C, int64_t ldc, void *stream)
+{
+    if (!z_w) return QNN_EINVAL;
+    return qgemm_impl(A, lda, z_a, B, ldb, b_layout, weight_bits, M, N, K, bias, mult, shift, z_out, act_min, act_max, C,
+                      ldc, stream, nullptr, 0, nullptr, z_w);
+}
+
+qnn_status qnn_qconv2d_asym(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
+                            int kw, int weight_bits, const int32_t *z_w, int stride_h, int stride_w, int pad_h, int pad_w,
+                            const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_out,
+                            int32_t act_min, int32_t act_max, uint8_t *y, void *stream)
+{
+    if (!z_w) return QNN_EINVAL;
+    return qconv2d_impl(x, N, H, W, Cin, z_x, w, Cout, kh, kw, weight_bits, stride_h, stride_w, pad_h, pad_w, bias, mult,
+                        shift, z_out, act_min, act_max, y, stream, nullptr, nullptr, z_w);
 }
 
 qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,

@@ -55,7 +55,7 @@ struct SplitK {
     int32_t *partial; // device memory, splits * M * N int32
 };
 
-template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false>
+template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false, bool ZW = false>
 __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs g, const int tiles_m, const int tiles_n,
                                                                 const int per_xcd, const int xcd_rows, const SplitK sk)
 {
@@ -341,7 +341,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
                 }
         }
     } else {
-        igemm_epilogue<BM, BN, WM, WN, false>(g, acc, colsum, cparams, smem, m0, n0);
+        igemm_epilogue<BM, BN, WM, WN, false, ZW>(g, acc, colsum, cparams, smem, m0, n0);
     }
 }
 

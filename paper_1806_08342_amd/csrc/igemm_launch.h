@@ -30,7 +30,12 @@ bool try_bres(IgemmArgs &g, int a_mode, int b_mode, hipStream_t s, qnn_status *s
 // convolution geometry; returns false if the layer is not a stem these kernels cover.
 bool try_stem(IgemmArgs &g, int batch, int kh, int stride_h, int stride_w, int weight_bits, hipStream_t s, qnn_status *status);
 
+// Row sums of the activations for per-channel weight zero-points: out[m], M int32 (igemm_rowsum.hip)
+qnn_status launch_rowsum(const IgemmArgs &g, int a_mode, int kh, int32_t *out, hipStream_t s);
+
 // Register-staged tiles of igemm.h (any alignment, any weight layout): 64x64 or 128x128.
 void launch_plain_tile(bool big, const IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s);
+// the 64x64 tile with per-column weight zero-points (g.zw, g.rowsum set)
+void launch_plain_tile_zw(const IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s);
 
 } // namespace qnn

@@ -1,0 +1,106 @@
+"""GPU parity of the layers with asymmetric per-channel weights (a zero-point per output channel;
+qnn_qgemm_asym / qnn_qconv2d_asym) against the oracle, which evaluates the defining sum
+sum_k (x - z_x)(w - z_w) directly (Sec. 2.3 eq. 4); the GPU evaluates the four-term expansion of
+eq. 5-6 with the activation sums formed in a pass of their own."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1806_08342_amd as qnn
+import workloads
+from workloads import synth
+
+from gpu_util import assert_same, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(rng, M, N, K, bits):
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    lim = 8 if bits == 4 else 128
+    Bt = rng.integers(-lim, lim, (N, K)).astype(np.int8)
+    z_w = rng.integers(-lim, lim, N).astype(np.int32)
+    z_w[0], z_w[N - 1] = -lim, lim - 1  # the extremes of the code range
+    if N > 2:
+        z_w[1] = 0
+    # away from z_a = 128 and z_w = 0 the sum has a mean term that grows with K (not sqrt(K)): up to
+    # K * 255 * (lim + |z_w|); the multipliers bring that to about +-100 output codes
+    real = rng.uniform(60.0, 140.0, N) / (K * 255.0 * (lim + np.abs(z_w)))
+    mult, shift = oracle.quantize_multipliers(real)
+    bias = rng.integers(-20000, 20000, N).astype(np.int32)
+    return A, Bt, z_w, bias, mult, shift
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (5, 7, 3), (64, 64, 64), (100, 70, 200), (129, 257, 65), (300, 40, 1024),
+                                   (513, 129, 4096), (1000, 256, 128), (33, 500, 72), (4096, 96, 576), (256, 256, 8192)])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_qgemm_asym_matches_oracle(M, N, K, bits):
+    if bits == 4 and K % 2:
+        pytest.skip("nibble pairs need an even K")
+    rng = np.random.default_rng(5000 + M + N + K + bits)
+    A, Bt, z_w, bias, mult, shift = _case(rng, M, N, K, bits)
+    Bo = oracle.pack_int4(Bt) if bits == 4 else Bt
+    for z_a in (0, 131, 255):
+        want = oracle.qgemm(A, z_a, Bo, mult, shift, 120, 0, 255, bias=bias, weight_bits=bits, z_w=z_w)
+        got = host(qnn.qgemm_asym(dev(A), z_a, dev(Bo), dev(z_w), dev(mult), dev(shift), 120, 0, 255, bias=dev(bias),
+                                  weight_bits=bits))
+        assert_same(got, want, f"qgemm_asym {M}x{N}x{K} bits={bits} z_a={z_a}")
+    if M * N >= 4096:
+        assert np.mean((want == 0) | (want == 255)) < 0.7 and len(np.unique(want)) > 16, "parity would be vacuous"
+    # z_w = 0 must reproduce the symmetric entry point
+    zero = np.zeros(N, np.int32)
+    sym = host(qnn.qgemm(dev(A), 77, dev(Bo), dev(mult), dev(shift), 120, 0, 255, bias=dev(bias), weight_bits=bits))
+    same = host(qnn.qgemm_asym(dev(A), 77, dev(Bo), dev(zero), dev(mult), dev(shift), 120, 0, 255, bias=dev(bias),
+                               weight_bits=bits))
+    assert_same(same, sym, "z_w = 0")
+
+
+def test_qgemm_asym_extreme_operands_and_general_rescale():
+    # all-255 activations against all-(-128) weights with z_w = 127 at the largest admissible K:
+    # the true sum K * 255 * (-255) is close to -2^31 and every partial term wraps on the way
+    M, N, K = 70, 66, 32768
+    A = np.full((M, K), 255, np.uint8)
+    Bt = np.full((N, K), -128, np.int8)
+    z_w = np.full(N, 127, np.int32)
+    mult, shift = oracle.quantize_multipliers(np.full(N, 1.0 / (K * 255.0 * 255.0 / 100.0)))
+    shift[3] = 0
+    mult[5], shift[5] = 2 ** 30, -1
+    want = oracle.qgemm(A, 0, Bt, mult, shift, 200, 0, 255, z_w=z_w)
+    got = host(qnn.qgemm_asym(dev(A), 0, dev(Bt), dev(z_w), dev(mult), dev(shift), 200, 0, 255))
+    assert_same(got, want, "qgemm_asym extreme operands")
+    rng = np.random.default_rng(5100)
+    A, Bt, z_w, bias, mult, shift = _case(rng, 300, 140, 2048, 8)
+    shift[0] = 0
+    mult[1], shift[1] = 2 ** 30, -1
+    shift[139] = 27
+    want = oracle.qgemm(A, 9, Bt, mult, shift, 7, 0, 255, bias=bias, z_w=z_w)
+    got = host(qnn.qgemm_asym(dev(A), 9, dev(Bt), dev(z_w), dev(mult), dev(shift), 7, 0, 255, bias=dev(bias)))
+    assert_same(got, want, "qgemm_asym general rescale")
+
+
+CONV_SHAPES = [
+    # H, W, Cin, Cout, k, stride, pad, bits
+    (9, 7, 16, 8, 3, 1, 1, 8), (12, 12, 3, 32, 3, 2, 1, 8), (20, 20, 3, 64, 7, 2, 3, 8), (14, 14, 64, 96, 1, 2, 0, 8),
+    (14, 14, 32, 64, 1, 1, 0, 8), (8, 8, 20, 30, 3, 1, 1, 8), (14, 14, 64, 64, 3, 1, 1, 8), (11, 13, 48, 72, 5, 2, 2, 8),
+    (28, 28, 128, 130, 3, 2, 1, 8), (14, 14, 32, 192, 1, 1, 0, 4), (9, 9, 64, 24, 3, 2, 1, 4),
+]
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("batch", [1, 3])
+def test_qconv2d_asym_matches_oracle(shape, batch):
+    H, W, Cin, Cout, k, s, p, bits = shape
+    layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu", weight_bits=bits)
+    c = synth.conv_case(layer, batch, 5200 + sum(shape) + batch, oracle)
+    rng = np.random.default_rng(5300 + sum(shape))
+    lim = 8 if bits == 4 else 128
+    z_w = rng.integers(-lim, lim, Cout).astype(np.int32)
+    z_w[0] = -lim
+    w_o = c.get("w_packed", c["w"])
+    for z_x in (c["z_x"], 0, 255):  # padding must count as the code z_x in the window sums as well
+        want = oracle.qconv2d(c["x"], z_x, w_o, c["stride"], c["pad"], c["mult"], c["shift"], c["z_out"], c["act_min"],
+                              c["act_max"], bias=c["bias"], weight_bits=bits, z_w=z_w)
+        got = host(qnn.qconv2d_asym(dev(c["x"]), z_x, dev(w_o), dev(z_w), c["stride"], c["pad"], dev(c["mult"]),
+                                    dev(c["shift"]), c["z_out"], c["act_min"], c["act_max"], bias=dev(c["bias"]),
+                                    weight_bits=bits))
+        assert_same(got, want, f"qconv2d_asym {shape} batch {batch} z_x={z_x}")

@@ -124,6 +124,12 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     assert lib.qnn_qadd(p, 0, 1, 40, p, 0, 1, 0, 20, 1, 0, 0, 0, 255, p, 16, None) == EINVAL  # shift out of range
     assert lib.qnn_qadd(null, 0, 1, 0, null, 0, 1, 0, 20, 1, 0, 0, 0, 255, null, 0, None) == 0
     assert lib.qnn_pack_b(p, 4, 8, 8, p, 8, None) == EINVAL  # ld_src < N
+    # asymmetric weights: the zero-point array is required, and K is limited to 32768
+    asym = lambda z_w=p, K=64: lib.qnn_qgemm_asym(p, K, 0, p, K, 0, 8, z_w, 64, 64, K, null, p, p, 0, 0, 255, p, 64, None)
+    assert asym(z_w=null) == EINVAL
+    assert asym(K=32768 + 64) == EINVAL
+    assert lib.qnn_qconv2d_asym(p, 1, 8, 8, 16, 0, p, 8, 3, 3, 8, null, 1, 1, 1, 1, null, p, p, 0, 0, 255, p, None) == EINVAL
+    assert lib.qnn_qconv2d_asym(p, 1, 64, 64, 4096, 0, p, 8, 3, 3, 8, p, 1, 1, 1, 1, null, p, p, 0, 0, 255, p, None) == EINVAL
     # the fused add: every field is checked on the host before anything is launched
     fields = dict(mult_m=1 << 30, shift_m=1, z_r=0, mult_r=1 << 30, shift_r=1, left_shift=20, mult_o=1 << 30, shift_o=10,
                   z_out=0, act_min=0, act_max=255)
