@@ -240,6 +240,9 @@ def time_streaming(torch, qnn):
     p = qnn.qadd_params(0.02, 0.031, 0.04)
     t = time_kernel(torch, lambda: qnn.qadd(q, 120, b, 131, p, 0, 0, 255, out=y.view(-1)), reps=10)
     out["qadd"] = dict(us=round(t * 1e6, 1), gbs=round(3.0 * n / t * 1e-9, 1), frac=round(3.0 * n / t / 8e12, 3))
+    st = qnn.new_range_state()
+    t = time_kernel(torch, lambda: qnn.quantize_dynamic(x, st, out=q), reps=10)  # range pass (4 B) + quantize pass (5 B)
+    out["quantize_dynamic"] = dict(us=round(t * 1e6, 1), gbs=round(9.0 * n / t * 1e-9, 1), frac=round(9.0 * n / t / 8e12, 3))
     return out
 
 

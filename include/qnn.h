@@ -215,6 +215,43 @@ qnn_status qnn_qconv2d_asym(const uint8_t *x, int N, int H, int W, int Cin, int3
                             const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_out,
                             int32_t act_min, int32_t act_max, uint8_t *y, void *stream);
 
+/* Quantizer parameters from the data, on the device (Sec. 2.5: activation ranges are the minimum and
+ * maximum of the tensor, or their moving average across batches; Sec. 2.1 turns a range into scale
+ * and zero-point).  No value travels to the host.
+ * state: DEVICE, 24 bytes, owned by the caller; xmin / xmax persist between calls (the moving
+ *        average), key_min / key_max are work space of the reduction.
+ * qnn_minmax: batch range over the FINITE elements of x (NaN and +-inf are skipped; no finite element:
+ *   range [0, 0]); momentum == 0: state range = batch range; 0 < momentum < 1:
+ *   state.x = momentum * state.x + (1 - momentum) * batch (products and sum each rounded once in
+ *   binary64, result rounded to binary32; the caller initialises xmin / xmax before the first such call);
+ *   then (scale, zero_point) = qnn_choose_qparams(xmin, xmax, bits), evaluated on the device.
+ * qnn_quantize_with: qnn_quantize with scale / zero_point read from state, codes 0..255.
+ * qnn_quantize_dynamic: qnn_minmax(momentum 0, 8 bits) followed by qnn_quantize_with.
+ * x: DEVICE fp32[n] (read); q: DEVICE uint8[n] (written).  n == 0 is allowed. */
+typedef struct qnn_dyn_qparams {
+    float scale;
+    int32_t zero_point;
+    float xmin, xmax;
+    uint32_t key_min, key_max;
+} qnn_dyn_qparams;
+
+qnn_status qnn_minmax(const float *x, size_t n, float momentum, int bits, qnn_dyn_qparams *state, void *stream);
+qnn_status qnn_quantize_with(const float *x, uint8_t *q, size_t n, const qnn_dyn_qparams *state, void *stream);
+qnn_status qnn_quantize_dynamic(const float *x, uint8_t *q, size_t n, qnn_dyn_qparams *state, void *stream);
+
+/* Simulated quantization for quantization-aware training (Sec. 2.4).
+ * Forward (eq. 12-13): y[i] = dequantize(quantize(x[i])) with the given quantizer and code range
+ *   [qmin, qmax] within 0..255 (e.g. 0..15 for 4-bit activations); same arithmetic as qnn_quantize /
+ *   qnn_dequantize, so y is bit-identical to calling the two.
+ * Backward (straight-through estimator, eq. 14-15): grad_x[i] = grad_y[i] if x_min <= x[i] <= x_max, else
+ *   0, with x_min = (qmin - zero_point) * scale and x_max = (qmax - zero_point) * scale in binary32
+ *   (NaN inputs get no gradient).
+ * x, grad_y: DEVICE fp32[n] (read); y, grad_x: DEVICE fp32[n] (written). */
+qnn_status qnn_simquant(const float *x, float *y, size_t n, float scale, int32_t zero_point, int32_t qmin, int32_t qmax,
+                        void *stream);
+qnn_status qnn_simquant_backward(const float *x, const float *grad_y, float *grad_x, size_t n, float scale,
+                                 int32_t zero_point, int32_t qmin, int32_t qmax, void *stream);
+
 /* ------------------------------------------------------------------ host-only helpers */
 
 /* Quantizer parameters from a real range, Sec. 2.1: the range is first widened to contain 0,

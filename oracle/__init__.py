@@ -282,3 +282,47 @@ def qadd(a, z_a, b, z_b, params, z_out, act_min, act_max):
                              p["mult_b"], p["shift_b"], p["left_shift"], p["mult_o"], p["shift_o"], int(z_out),
                              int(act_min), int(act_max), _p(y, np.uint8), C.c_size_t(a.size)))
     return y
+
+
+# ------------------------------------------------ ranges from the data, simulated quantization
+# Plain definitions written out with numpy and the pinned functions above (no new C code).
+
+def finite_range(x):
+    """(min, max) over the finite elements of x as binary32 (Sec. 2.5: the range of an activation tensor
+    is its minimum and maximum); (0, 0) when there is none."""
+    x = np.asarray(x, dtype=np.float32).reshape(-1)
+    x = x[np.isfinite(x)]
+    if x.size == 0:
+        return np.float32(0.0), np.float32(0.0)
+    return np.float32(x.min()), np.float32(x.max())
+
+
+def moving_average(old, new, momentum):
+    """momentum * old + (1 - momentum) * new (Sec. 2.5: moving average of the range across batches):
+    the two products and the sum each rounded once in binary64, the result rounded to binary32."""
+    m = np.float64(np.float32(momentum))
+    return np.float32(m * np.float64(np.float32(old)) + (np.float64(1.0) - m) * np.float64(np.float32(new)))
+
+
+def dynamic_qparams(x, bits=8, state=None, momentum=0.0):
+    """(scale, zero_point, xmin, xmax) of the quantizer of x's own range, or of the moving average that
+    starts from state = (xmin, xmax)."""
+    lo, hi = finite_range(x)
+    if momentum != 0.0:
+        lo, hi = moving_average(state[0], lo, momentum), moving_average(state[1], hi, momentum)
+    s, z = choose_qparams(float(lo), float(hi), bits)
+    return s, z, lo, hi
+
+
+def simquant(x, scale, zero_point, qmin=0, qmax=255):
+    """Sec. 2.4 eq. 12-13: a quantizer followed by a de-quantizer."""
+    return dequantize(quantize(x, scale, zero_point, qmin, qmax), scale, zero_point)
+
+
+def simquant_backward(x, grad_y, scale, zero_point, qmin=0, qmax=255):
+    """Sec. 2.4 eq. 14-15 (straight-through estimator): the gradient passes where x lies inside the
+    representable range [x_min, x_max] = de-quantized extreme codes, and is zero elsewhere."""
+    x = np.asarray(x, dtype=np.float32)
+    ends = dequantize(np.array([qmin, qmax], dtype=np.uint8), scale, zero_point)
+    inside = (x >= ends[0]) & (x <= ends[1])
+    return np.where(inside, np.asarray(grad_y, dtype=np.float32), np.float32(0.0)).astype(np.float32)

@@ -20,7 +20,8 @@ B_COLUMNS_CONTIGUOUS, B_ROWS_CONTIGUOUS = 0, 1
 
 EXPORTS = [
     "qnn_last_error", "qnn_version", "qnn_qgemm_plan", "qnn_quantize", "qnn_dequantize", "qnn_requantize", "qnn_qgemm", "qnn_pack_b",
-    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
+    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_minmax", "qnn_quantize_with",
+    "qnn_quantize_dynamic", "qnn_simquant", "qnn_simquant_backward", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
     "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4",
 ]
 
@@ -58,6 +59,11 @@ def load_library():
         "qnn_qgemm": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
         "qnn_pack_b": [vp, i64, i64, i64, vp, i64, vp],
         "qnn_qconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
+        "qnn_minmax": [vp, sz, f32, ci, vp, vp],
+        "qnn_quantize_with": [vp, vp, sz, vp, vp],
+        "qnn_quantize_dynamic": [vp, vp, sz, vp, vp],
+        "qnn_simquant": [vp, vp, sz, f32, i32, i32, i32, vp],
+        "qnn_simquant_backward": [vp, vp, vp, sz, f32, i32, i32, i32, vp],
         "qnn_qgemm_asym": [vp, i64, i32, vp, i64, ci, ci, vp, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
         "qnn_qconv2d_asym": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
         "qnn_qgemm_add": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, vp, i64, vp],
@@ -371,6 +377,63 @@ def qconv2d_asym(x, z_x, w, z_w, stride, pad, mult, shift, z_out, act_min, act_m
         stride[0], stride[1], pad[0], pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"),
         _dev(shift, torch.int32, "shift"), z_out, act_min, act_max, _dev(y, torch.uint8, "y"), _stream()))
     return y
+
+
+def new_range_state(xmin=0.0, xmax=0.0):
+    """Device-resident quantizer state (qnn_dyn_qparams: scale, zero_point, xmin, xmax, 2 work words) as
+    an int32 tensor of 6 elements; `read_range_state` decodes it."""
+    torch = _torch()
+    host = np.zeros(6, dtype=np.int32)
+    host[2:4] = np.array([xmin, xmax], dtype=np.float32).view(np.int32)
+    return torch.from_numpy(host).to("cuda:0")
+
+
+def read_range_state(state):
+    h = state.cpu().numpy()
+    f = h.view(np.float32)
+    return dict(scale=float(f[0]), zero_point=int(h[1]), xmin=float(f[2]), xmax=float(f[3]))
+
+
+def minmax(x, state, momentum=0.0, bits=8):
+    """Range of the finite elements of x (or its moving average) and the quantizer parameters, into `state`."""
+    torch = _torch()
+    _check("qnn_minmax", load_library().qnn_minmax(_dev(x, torch.float32, "x"), x.numel(), float(momentum), int(bits),
+                                                   _dev(state, torch.int32, "state"), _stream()))
+    return state
+
+
+def quantize_with(x, state, out=None):
+    torch = _torch()
+    q = torch.empty(x.shape, dtype=torch.uint8, device=x.device) if out is None else out
+    _check("qnn_quantize_with", load_library().qnn_quantize_with(_dev(x, torch.float32, "x"), _dev(q, torch.uint8, "q"),
+                                                                 x.numel(), _dev(state, torch.int32, "state"), _stream()))
+    return q
+
+
+def quantize_dynamic(x, state, out=None):
+    """uint8 codes of x with the quantizer of its own range; the parameters are left in `state`."""
+    torch = _torch()
+    q = torch.empty(x.shape, dtype=torch.uint8, device=x.device) if out is None else out
+    _check("qnn_quantize_dynamic", load_library().qnn_quantize_dynamic(
+        _dev(x, torch.float32, "x"), _dev(q, torch.uint8, "q"), x.numel(), _dev(state, torch.int32, "state"), _stream()))
+    return q
+
+
+def simquant(x, scale, zero_point, qmin=0, qmax=255, out=None):
+    torch = _torch()
+    y = torch.empty(x.shape, dtype=torch.float32, device=x.device) if out is None else out
+    _check("qnn_simquant", load_library().qnn_simquant(_dev(x, torch.float32, "x"), _dev(y, torch.float32, "y"), x.numel(),
+                                                       float(scale), int(zero_point), int(qmin), int(qmax), _stream()))
+    return y
+
+
+def simquant_backward(x, grad_y, scale, zero_point, qmin=0, qmax=255, out=None):
+    torch = _torch()
+    gx = torch.empty(x.shape, dtype=torch.float32, device=x.device) if out is None else out
+    _check("qnn_simquant_backward", load_library().qnn_simquant_backward(
+        _dev(x, torch.float32, "x"), _dev(grad_y, torch.float32, "grad_y"), _dev(gx, torch.float32, "grad_x"), x.numel(),
+        float(scale), int(zero_point), int(qmin), int(qmax), _stream()))
+    return gx
 
 
 def qdwconv2d(x, z_x, w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, out=None):

@@ -69,6 +69,164 @@ __global__ void __launch_bounds__(kThreads) quantize_kernel(const float *__restr
     }
 }
 
+// ------------------------------------------- ranges on the device, dynamic quantization
+
+// Sec. 2.5: activation ranges come from the minimum and maximum of the tensor (their moving average
+// across batches during training); Sec. 2.1 turns a range into (scale, zero_point).  Everything stays on
+// the device: a reduction with one atomic pair per workgroup on order-preserving integer keys, a
+// one-lane kernel that updates the range and derives the parameters in double precision exactly as
+// qnn_choose_qparams does on the host, and a quantize kernel that reads them from memory.
+__device__ __forceinline__ uint32_t float_key(float v) // monotonic: a < b  <=>  key(a) < key(b)
+{
+    const uint32_t b = __float_as_uint(v);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__device__ __forceinline__ float key_float(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+__global__ void minmax_init_kernel(qnn_dyn_qparams *st)
+{
+    st->key_min = 0xffffffffu;
+    st->key_max = 0u;
+}
+
+__global__ void __launch_bounds__(kThreads) minmax_kernel(const float *__restrict__ x, size_t n, qnn_dyn_qparams *st)
+{
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    float lo = INFINITY, hi = -INFINITY; // values that are not finite take no part in the range
+    auto take = [&](float v) {
+        if (__builtin_isfinite(v)) lo = fminf(lo, v), hi = fmaxf(hi, v);
+    };
+    if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+        const size_t nvec = n / 4;
+        const f32x4 *xv = reinterpret_cast<const f32x4 *>(x);
+        size_t v = tid;
+        for (; v + 3 * nthreads < nvec; v += 4 * nthreads) { // four independent 16-byte loads in flight per lane
+            f32x4 a[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) a[u] = xv[v + u * nthreads]; // plain loads: the quantize pass reads x again
+#pragma unroll
+            for (int u = 0; u < 4; ++u) take(a[u].x), take(a[u].y), take(a[u].z), take(a[u].w);
+        }
+        for (; v < nvec; v += nthreads) {
+            const f32x4 a = xv[v];
+            take(a.x), take(a.y), take(a.z), take(a.w);
+        }
+        for (size_t i = nvec * 4 + tid; i < n; i += nthreads) take(x[i]);
+    } else {
+        for (size_t i = tid; i < n; i += nthreads) take(x[i]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off));
+        hi = fmaxf(hi, __shfl_xor(hi, off));
+    }
+    __shared__ float s_lo[kThreads / 64], s_hi[kThreads / 64];
+    if ((threadIdx.x & 63) == 0) s_lo[threadIdx.x >> 6] = lo, s_hi[threadIdx.x >> 6] = hi;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / 64; ++w) lo = fminf(lo, s_lo[w]), hi = fmaxf(hi, s_hi[w]);
+        if (lo <= hi) { // at least one finite value in this block
+            // atomics on one address serialise across the chip: skip them when the value seen so far is
+            // already as good (a stale read only costs an atomic that changes nothing)
+            const uint32_t klo = float_key(lo), khi = float_key(hi);
+            if (klo < __hip_atomic_load(&st->key_min, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMin(&st->key_min, klo);
+            if (khi > __hip_atomic_load(&st->key_max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(&st->key_max, khi);
+        }
+    }
+}
+
+__device__ __forceinline__ double nearest_away_dev(double v) { return v < 0.0 ? -floor(-v + 0.5) : floor(v + 0.5); }
+
+// range update (momentum 0: the batch range; else moving average) and quantizer parameters
+__global__ void range_finalize_kernel(qnn_dyn_qparams *st, float momentum, int bits)
+{
+    float bmin = 0.0f, bmax = 0.0f;
+    if (st->key_min <= st->key_max) bmin = key_float(st->key_min), bmax = key_float(st->key_max);
+    if (momentum != 0.0f) { // m * old + (1 - m) * batch, each operation rounded once in double, then to binary32
+        const double m = (double)momentum, om = __dsub_rn(1.0, m);
+        bmin = (float)__dadd_rn(__dmul_rn(m, (double)st->xmin), __dmul_rn(om, (double)bmin));
+        bmax = (float)__dadd_rn(__dmul_rn(m, (double)st->xmax), __dmul_rn(om, (double)bmax));
+    }
+    st->xmin = bmin, st->xmax = bmax;
+    const double lo = fmin((double)bmin, 0.0), hi = fmax((double)bmax, 0.0);
+    const double steps = (double)((1 << bits) - 1);
+    if (hi - lo == 0.0) {
+        st->scale = 1.0f, st->zero_point = 0;
+        return;
+    }
+    const float sc = (float)__ddiv_rn(__dsub_rn(hi, lo), steps);
+    double z = nearest_away_dev(__ddiv_rn(-lo, (double)sc));
+    z = fmin(fmax(z, 0.0), steps);
+    st->scale = sc, st->zero_point = (int32_t)z;
+}
+
+// quantize with parameters that live in device memory (8-bit codes)
+__global__ void __launch_bounds__(kThreads) quantize_with_kernel(const float *__restrict__ x, uint8_t *__restrict__ q, size_t n,
+                                                                 const qnn_dyn_qparams *__restrict__ st)
+{
+    const float scale = st->scale;
+    const int32_t z = st->zero_point;
+    const float lo = (float)(0 - z), hi = (float)(255 - z);
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    if (((reinterpret_cast<uintptr_t>(x) & 15) | (reinterpret_cast<uintptr_t>(q) & 3)) == 0) {
+        const size_t nvec = n / 4;
+        const f32x4 *xv = reinterpret_cast<const f32x4 *>(x);
+        uint32_t *qv = reinterpret_cast<uint32_t *>(q);
+        size_t v = tid;
+        for (; v + 3 * nthreads < nvec; v += 4 * nthreads) {
+            f32x4 a[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) a[u] = __builtin_nontemporal_load(&xv[v + u * nthreads]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t p = quantize_one(a[u].x, scale, lo, hi, z) | (quantize_one(a[u].y, scale, lo, hi, z) << 8) |
+                                   (quantize_one(a[u].z, scale, lo, hi, z) << 16) |
+                                   (quantize_one(a[u].w, scale, lo, hi, z) << 24);
+                __builtin_nontemporal_store(p, &qv[v + u * nthreads]);
+            }
+        }
+        for (; v < nvec; v += nthreads) {
+            const f32x4 a = xv[v];
+            qv[v] = quantize_one(a.x, scale, lo, hi, z) | (quantize_one(a.y, scale, lo, hi, z) << 8) |
+                    (quantize_one(a.z, scale, lo, hi, z) << 16) | (quantize_one(a.w, scale, lo, hi, z) << 24);
+        }
+        for (size_t i = nvec * 4 + tid; i < n; i += nthreads) q[i] = (uint8_t)quantize_one(x[i], scale, lo, hi, z);
+    } else {
+        for (size_t i = tid; i < n; i += nthreads) q[i] = (uint8_t)quantize_one(x[i], scale, lo, hi, z);
+    }
+}
+
+// ------------------------------------------------- simulated quantization (training side)
+
+// Sec. 2.4: SimQuant = quantizer followed by de-quantizer (eq. 12-13); in the backward pass the
+// quantizer is replaced by a clamp to the representable range, i.e. the incoming gradient passes
+// where x_min <= x <= x_max and is zero elsewhere (straight-through estimator, eq. 14-15).
+__global__ void __launch_bounds__(kThreads) simquant_kernel(const float *__restrict__ x, float *__restrict__ y, size_t n,
+                                                            float scale, int32_t z, float lo, float hi)
+{
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += nthreads) {
+        const int32_t code = (int32_t)quantize_one(x[i], scale, lo, hi, z);
+        y[i] = __fmul_rn((float)(code - z), scale);
+    }
+}
+
+__global__ void __launch_bounds__(kThreads) simquant_backward_kernel(const float *__restrict__ x, const float *__restrict__ gy,
+                                                                     float *__restrict__ gx, size_t n, float xmin, float xmax)
+{
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += nthreads) {
+        const float v = x[i];
+        gx[i] = (v >= xmin && v <= xmax) ? gy[i] : 0.0f; // NaN fails both comparisons: no gradient
+    }
+}
+
 // ---------------------------------------------------------------- dequantize
 
 template <int VEC>
@@ -354,6 +512,59 @@ qnn_status qnn_requantize(const int32_t *acc, uint8_t *y, size_t rows, size_t ch
             hipLaunchKernelGGL((requantize_kernel<1, false>), dim3(grid), dim3(kThreads), 0, s, acc, y, total, ch,
                                mult, shift, z_out, act_min, act_max);
     }
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_minmax(const float *x, size_t n, float momentum, int bits, qnn_dyn_qparams *state, void *stream)
+{
+    if (!state || (n && !x) || bits < 2 || bits > 16 || !(momentum >= 0.0f) || !(momentum < 1.0f)) return QNN_EINVAL;
+    const hipStream_t s = as_stream(stream);
+    hipLaunchKernelGGL(minmax_init_kernel, dim3(1), dim3(1), 0, s, state);
+    if (n) hipLaunchKernelGGL(minmax_kernel, dim3(grid_for(n / 4 + 1, kThreads * 4, 256 * 8)), dim3(kThreads), 0, s, x, n, state);
+    hipLaunchKernelGGL(range_finalize_kernel, dim3(1), dim3(1), 0, s, state, momentum, bits);
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_quantize_with(const float *x, uint8_t *q, size_t n, const qnn_dyn_qparams *state, void *stream)
+{
+    if (!state) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (!x || !q) return QNN_EINVAL;
+    hipLaunchKernelGGL(quantize_with_kernel, dim3(grid_for(n / 4 + 1, kThreads * 4)), dim3(kThreads), 0, as_stream(stream), x, q,
+                       n, state);
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_quantize_dynamic(const float *x, uint8_t *q, size_t n, qnn_dyn_qparams *state, void *stream)
+{
+    if (n && (!x || !q)) return QNN_EINVAL;
+    const qnn_status st = qnn_minmax(x, n, 0.0f, 8, state, stream);
+    return st != QNN_OK ? st : qnn_quantize_with(x, q, n, state, stream);
+}
+
+qnn_status qnn_simquant(const float *x, float *y, size_t n, float scale, int32_t zero_point, int32_t qmin, int32_t qmax,
+                        void *stream)
+{
+    if (!(scale > 0.0f) || __builtin_isinf(scale) || qmin < 0 || qmax > 255 || qmin > qmax) return QNN_EINVAL;
+    if (zero_point < qmin || zero_point > qmax) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (!x || !y) return QNN_EINVAL;
+    hipLaunchKernelGGL(simquant_kernel, dim3(grid_for(n, kThreads * 4)), dim3(kThreads), 0, as_stream(stream), x, y, n, scale,
+                       zero_point, (float)(qmin - zero_point), (float)(qmax - zero_point));
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_simquant_backward(const float *x, const float *grad_y, float *grad_x, size_t n, float scale,
+                                 int32_t zero_point, int32_t qmin, int32_t qmax, void *stream)
+{
+    if (!(scale > 0.0f) || __builtin_isinf(scale) || qmin < 0 || qmax > 255 || qmin > qmax) return QNN_EINVAL;
+    if (zero_point < qmin || zero_point > qmax) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (!x || !grad_y || !grad_x) return QNN_EINVAL;
+    // the ends of the representable range are the de-quantized extreme codes (one binary32 product each)
+    const float xmin = (float)(qmin - zero_point) * scale, xmax = (float)(qmax - zero_point) * scale;
+    hipLaunchKernelGGL(simquant_backward_kernel, dim3(grid_for(n, kThreads * 4)), dim3(kThreads), 0, as_stream(stream), x, grad_y,
+                       grad_x, n, xmin, xmax);
     return launch_status(hipGetLastError());
 }
 

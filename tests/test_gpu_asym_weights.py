@@ -1,6 +1,6 @@
 """GPU parity of the layers with asymmetric per-channel weights (a zero-point per output channel;
 qnn_qgemm_asym / qnn_qconv2d_asym) against the oracle, which evaluates the defining sum
-sum_k (x - z_x)(w - z_w) directly (Sec. 2.3 eq. 4); the GPU evaluates the four-term expansion of
+sum_k (x - z_x)(w - z_w) directly (Sec. 2.1 eq. 4); the GPU evaluates the four-term expansion of
 eq. 5-6 with the activation sums formed in a pass of their own."""
 import numpy as np
 import pytest

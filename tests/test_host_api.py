@@ -124,6 +124,18 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     assert lib.qnn_qadd(p, 0, 1, 40, p, 0, 1, 0, 20, 1, 0, 0, 0, 255, p, 16, None) == EINVAL  # shift out of range
     assert lib.qnn_qadd(null, 0, 1, 0, null, 0, 1, 0, 20, 1, 0, 0, 0, 255, null, 0, None) == 0
     assert lib.qnn_pack_b(p, 4, 8, 8, p, 8, None) == EINVAL  # ld_src < N
+    # ranges on the device and simulated quantization
+    assert lib.qnn_minmax(p, 16, C.c_float(0.0), 8, null, None) == EINVAL
+    assert lib.qnn_minmax(p, 16, C.c_float(1.0), 8, p, None) == EINVAL      # momentum must stay below 1
+    assert lib.qnn_minmax(p, 16, C.c_float(0.0), 1, p, None) == EINVAL      # 2..16 bits
+    assert lib.qnn_quantize_with(p, p, 16, null, None) == EINVAL
+    assert lib.qnn_quantize_dynamic(null, p, 16, p, None) == EINVAL
+    assert lib.qnn_simquant(p, p, 16, C.c_float(0.0), 0, 0, 255, None) == EINVAL
+    assert lib.qnn_simquant(p, p, 16, C.c_float(0.1), 300, 0, 255, None) == EINVAL
+    assert lib.qnn_simquant(p, null, 16, C.c_float(0.1), 0, 0, 255, None) == EINVAL
+    assert lib.qnn_simquant_backward(p, p, p, 16, C.c_float(0.1), 0, 9, 3, None) == EINVAL
+    assert lib.qnn_simquant_backward(p, null, p, 16, C.c_float(0.1), 0, 0, 255, None) == EINVAL
+    assert lib.qnn_simquant(null, null, 0, C.c_float(0.1), 0, 0, 255, None) == 0
     # asymmetric weights: the zero-point array is required, and K is limited to 32768
     asym = lambda z_w=p, K=64: lib.qnn_qgemm_asym(p, K, 0, p, K, 0, 8, z_w, 64, 64, K, null, p, p, 0, 0, 255, p, 64, None)
     assert asym(z_w=null) == EINVAL

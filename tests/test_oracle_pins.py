@@ -461,3 +461,57 @@ def test_qadd_within_one_lsb_of_real_arithmetic():
         inside = (real > 0.5) & (real < 254.5)
         assert np.abs(y - real)[inside].max() <= 1.0
         assert (y[real <= -1] == 0).all() and (y[real >= 256] == 255).all()
+
+
+# ------------------------------------------------ ranges from the data, simulated quantization
+
+def test_finite_range_and_moving_average_against_plain_loops():
+    rng = np.random.default_rng(77)
+    x = rng.normal(0, 3, 1000).astype(np.float32)
+    x[[3, 500, 999]] = [np.nan, np.inf, -np.inf]
+    lo, hi = oracle.finite_range(x)
+    want_lo = min(float(v) for v in x if np.isfinite(v))
+    want_hi = max(float(v) for v in x if np.isfinite(v))
+    assert (float(lo), float(hi)) == (want_lo, want_hi)
+    assert oracle.finite_range(np.array([np.nan, np.inf], np.float32)) == (0.0, 0.0)
+    # momentum 0.75 between exactly representable values: 0.75 * 8 + 0.25 * 4 = 7 exactly
+    assert float(oracle.moving_average(8.0, 4.0, 0.75)) == 7.0
+    # a constant batch range is a fixed point, and the average converges to it geometrically
+    v = np.float32(0.0)
+    for _ in range(200):
+        v = oracle.moving_average(v, 2.5, 0.9)
+    assert abs(float(v) - 2.5) < 1e-6 and float(oracle.moving_average(2.5, 2.5, 0.9)) == 2.5
+    s, z, lo2, hi2 = oracle.dynamic_qparams(np.array([2.1, 3.5, 2.7], np.float32))
+    assert (s, z) == oracle.choose_qparams(float(np.float32(2.1)), float(np.float32(3.5)))  # Sec. 2.1: range widened to hold 0
+    assert z == 0 and float(lo2) == float(np.float32(2.1))
+
+
+def test_simquant_is_eq_13_idempotent_and_bounded():
+    rng = np.random.default_rng(78)
+    x = rng.normal(0, 2, 5000).astype(np.float32)
+    scale, z = 2.0 ** -5, 100  # a power-of-two step keeps the fp64 form below exact
+    y = oracle.simquant(x, scale, z)
+    # eq. 13 in fp64: Delta * (clamp(0, N-1, round(x/Delta) + z) - z)
+    r = np.where(x >= 0, np.floor(x.astype(np.float64) / scale + 0.5), -np.floor(-x.astype(np.float64) / scale + 0.5))
+    want = (np.clip(r + z, 0, 255) - z) * scale
+    assert np.array_equal(y.astype(np.float64), want)
+    assert np.array_equal(oracle.simquant(y, scale, z), y)                      # a fixed point of itself
+    inside = (x >= (0 - z) * scale) & (x <= (255 - z) * scale)
+    assert np.max(np.abs(y[inside] - x[inside])) <= scale / 2                    # half a step inside the range
+    assert np.all(y[~inside & (x > 0)] == (255 - z) * scale) and np.all(y[~inside & (x < 0)] == -z * scale)
+    y4 = oracle.simquant(x, 0.25, 8, 0, 15)                                      # 4-bit codes
+    assert len(np.unique(y4)) <= 16 and y4.min() == -2.0 and y4.max() == 1.75
+
+
+def test_simquant_backward_is_the_indicator_of_the_range():
+    x = np.array([-10.0, -3.2, -3.1875, 0.0, 4.78125, 4.8, 100.0, np.nan], np.float32)
+    g = np.arange(1, 9, dtype=np.float32)
+    scale, z = 2.0 ** -5, 102  # range [-3.1875, 4.78125]
+    gx = oracle.simquant_backward(x, g, scale, z)
+    assert gx.tolist() == [0.0, 0.0, 3.0, 4.0, 5.0, 0.0, 0.0, 0.0]
+    # derivative of the clamp of eq. 14 by finite differences, away from the two corners
+    xs = np.linspace(-6, 6, 241).astype(np.float32)
+    clamp = lambda v: np.clip(v, -3.1875, 4.78125)
+    fd = (clamp(xs + 1e-3) - clamp(xs - 1e-3)) / 2e-3
+    away = (np.abs(xs + 3.1875) > 1e-2) & (np.abs(xs - 4.78125) > 1e-2)
+    assert np.allclose(oracle.simquant_backward(xs, np.ones_like(xs), scale, z)[away], fd[away], atol=1e-3)
