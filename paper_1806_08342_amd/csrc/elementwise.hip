@@ -282,30 +282,69 @@ __global__ void __launch_bounds__(kThreads)
     const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t nthreads = (size_t)gridDim.x * blockDim.x;
     RescaleParams uni = make_rescale(mult[0], shift[0]);
+    const int32_t uni_shift = shift[0];
     if (VEC == 4) {
         const size_t nvec = total / 4;
         const i32x4 *av = reinterpret_cast<const i32x4 *>(acc);
         uint32_t *yv = reinterpret_cast<uint32_t *>(y);
-        for (size_t v = tid; v < nvec; v += nthreads) {
-            i32x4 a = __builtin_nontemporal_load(&av[v]);
-            int32_t in[4] = {a.x, a.y, a.z, a.w};
-            uint32_t packed = 0;
-            uint32_t c = PER_CHANNEL ? (uint32_t)((v * 4) % channels) : 0u;
-            i32x4 m4 = {0, 0, 0, 0}, s4 = {0, 0, 0, 0};
+        // four accumulators of one lane -> four codes.  When every lane of the wave has 1 <= shift <= 20 and
+        // |acc| < 2^29 the rescale runs in its 7-operation 32-bit form, else in the general 64-bit form.
+        auto four = [&](const i32x4 a, uint32_t c) -> uint32_t {
+            i32x4 m4 = {uni.mult, uni.mult, uni.mult, uni.mult}, s4 = {uni_shift, uni_shift, uni_shift, uni_shift};
             if (PER_CHANNEL) {
                 m4 = *reinterpret_cast<const i32x4 *>(mult + c);
                 s4 = *reinterpret_cast<const i32x4 *>(shift + c);
             }
-            const int32_t mm[4] = {m4.x, m4.y, m4.z, m4.w};
-            const int32_t ss[4] = {s4.x, s4.y, s4.z, s4.w};
+            bool ok = true;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                RescaleParams p = PER_CHANNEL ? make_rescale(mm[j], ss[j]) : uni;
-                // clamp before adding z_out: the rescaled value may sit at the int32 limits
-                int32_t r = clamp_i32(act_min - z_out, act_max - z_out, rescale_general(in[j], p)) + z_out;
-                packed |= (uint32_t)r << (8 * j);
+            for (int j = 0; j < 4; ++j) ok = ok && s4[j] >= 1 && s4[j] <= 20 && a[j] > -(1 << 29) && a[j] < (1 << 29);
+            uint32_t packed = 0;
+            if (__all(ok)) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int32_t n1 = s4[j] + 1;
+                    FusedRescale f;
+                    f.mult = m4[j], f.corr4 = 0, f.n1 = n1;
+                    f.c = (1 << s4[j]) + (z_out << n1) + 1;
+                    f.lo = act_min << n1;
+                    f.hi = ((act_max + 1) << n1) - 1;
+                    packed = shift_into_byte(packed, rescale_fused_w(a[j], f), n1, j);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const RescaleParams p = make_rescale(m4[j], s4[j]);
+                    // clamp before adding z_out: the rescaled value may sit at the int32 limits
+                    const int32_t r = clamp_i32(act_min - z_out, act_max - z_out, rescale_general(a[j], p)) + z_out;
+                    packed |= (uint32_t)r << (8 * j);
+                }
             }
-            __builtin_nontemporal_store(packed, &yv[v]);
+            return packed;
+        };
+        // channel of a lane's first element, advanced without a 64-bit division per step (rows are a
+        // multiple of 4 long, so a vector never straddles a row)
+        const uint32_t step = PER_CHANNEL ? (uint32_t)((nthreads * 4) % channels) : 0u;
+        uint32_t c = PER_CHANNEL ? (uint32_t)((tid * 4) % channels) : 0u;
+        auto advance = [&](uint32_t ch) {
+            ch += step;
+            return ch >= channels ? ch - channels : ch;
+        };
+        size_t v = tid;
+        for (; v + 3 * nthreads < nvec; v += 4 * nthreads) { // four independent 16-byte loads in flight per lane
+            i32x4 a[4];
+            uint32_t cs[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                a[u] = __builtin_nontemporal_load(&av[v + u * nthreads]);
+                cs[u] = c;
+                c = advance(c);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) __builtin_nontemporal_store(four(a[u], cs[u]), &yv[v + u * nthreads]);
+        }
+        for (; v < nvec; v += nthreads) {
+            yv[v] = four(av[v], c);
+            c = advance(c);
         }
     } else {
         for (size_t i = tid; i < total; i += nthreads) {
