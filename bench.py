@@ -74,14 +74,19 @@ def run_gemm(qnn, c):
     c["launch"]()  # arguments marshalled once (binding.prepare_qgemm); same C-ABI call as qnn.qgemm
 
 
-def time_gemm_sweep(torch, qnn, cases, steps, warmup, eager=False):
+def time_gemm_sweep(torch, qnn, cases, steps, warmup, eager=False, streams=4):
     """Returns (seconds for `steps` passes, per-case milliseconds).
 
     Timed region: `steps` replays of one HIP graph that holds the 71 launches of a pass (the
     library calls are captured from the stream they run on), so that the short products are
     timed at GPU speed and not at the speed of the Python launch loop; with eager=True the
-    launches are issued one by one instead.  The per-case durations come from a second,
-    instrumented pass of the same launches with one HIP event between consecutive launches.
+    launches are issued one by one instead.  The products of a pass are independent problems, so
+    the graph spreads them round-robin over `streams` streams of equal (default) priority that fork
+    from and join the capturing stream: short products then overlap with long ones instead of each
+    paying a full launch-to-launch latency.  Products that use the library's scratch block (split-K)
+    all stay on the capturing stream, in order, because captured launches are not ordered by the
+    library itself.  The per-case durations come from a second, instrumented pass of the same
+    launches, one by one on one stream, with one HIP event between consecutive launches.
     """
     for _ in range(warmup):
         for c in cases:
@@ -95,10 +100,22 @@ def time_gemm_sweep(torch, qnn, cases, steps, warmup, eager=False):
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
     else:
+        side = [torch.cuda.Stream() for _ in range(max(streams, 1) - 1)]
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
+            main = torch.cuda.current_stream()
+            for st in side:
+                st.wait_stream(main)
+            lanes, k = [main] + side, 0
             for c in cases:
-                run_gemm(qnn, c)
+                if "/k" in c["plan"] or not side:
+                    run_gemm(qnn, c)
+                else:
+                    with torch.cuda.stream(lanes[k % len(lanes)]):
+                        run_gemm(qnn, c)
+                    k += 1
+            for st in side:
+                main.wait_stream(st)
         graph.replay()  # untimed: first replay uploads the graph
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -280,6 +297,8 @@ def main():
     ap.add_argument("--no-secondary", action="store_true", help="skip the conv stacks and streaming kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="time the sweep as single launches instead of a graph replay")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="streams the independent products of a sweep pass are spread over inside the graph (1: one after another)")
     ap.add_argument("--layers", action="store_true", help="include per-layer rows of the conv stacks in the JSON")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for the HBM byte counters)")
@@ -300,7 +319,8 @@ def main():
     torch.cuda.set_device(0)
 
     cases = build_gemm_sweep(torch, qnn, workloads, synth)
-    elapsed, per_case_ms = time_gemm_sweep(torch, qnn, cases, args.steps, args.warmup, eager=args.eager)
+    elapsed, per_case_ms = time_gemm_sweep(torch, qnn, cases, args.steps, args.warmup, eager=args.eager,
+                                           streams=args.streams)
     ops_per_step = sum(c["ops"] for c in cases)
     value = ops_per_step * args.steps / elapsed * 1e-12
 
@@ -344,7 +364,8 @@ def main():
         "data": "synthetic (seeded; shapes and value distributions of BASELINE configuration 2)",
         "config": {"workload": "config2 quantized GEMM sweep: 64 triples of {256,1024,4096,8192}^3 + M in {1..64} x 4096 x 4096",
                    "gemms_per_step": len(cases), "ops_per_step": ops_per_step,
-                   "launch": "eager" if args.eager else "hip graph replay (one graph = one pass)"},
+                   "launch": "eager" if args.eager else
+                   f"hip graph replay (one graph = one pass; independent products on {max(args.streams, 1)} streams)"},
         "frac_of_int8_peak": round(value / PEAK_INT8_TOPS, 4),
         "roofline": roofline,
         "tops_by_shape": big,
