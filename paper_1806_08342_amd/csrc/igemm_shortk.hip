@@ -7,28 +7,48 @@ namespace qnn {
 
 // Short reduction (K <= 256): weight-stationary kernel of shortk.h.  Returns false when the
 // operands do not meet its alignment rules (the caller then takes the general route).
-template <int KS, bool INT4, int VEC> static void launch_shortk_one(const ShortKArgs &a, unsigned blocks, hipStream_t s)
+template <int NB, int KS, bool INT4, int VEC, int BVEC, int ADD>
+static void launch_shortk_add(const ShortKArgs &a, int64_t waves, hipStream_t s)
+{
+    // the waves of a workgroup (8 with the 64 KB table of code pairs, else 4) share the table(s); their tiles behind
+    constexpr int kWaves = ADD == 2 ? 8 : 4;
+    constexpr int kLds = (ADD == 2 ? 65536 : 2048) + kWaves * 32 * (32 * NB + 32);
+    auto kernel = shortk_kernel<NB, KS, INT4, VEC, BVEC, ADD>;
+    static bool configured = false; // per instantiation
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLds) !=
+            hipSuccess)
+            return; // the error stays pending for the caller's hipGetLastError
+        configured = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)((waves + kWaves - 1) / kWaves)), dim3(kWaves * 64), kLds, s, a);
+}
+
+template <int KS, bool INT4, int VEC> static void launch_shortk_one(const ShortKArgs &a, int64_t waves, hipStream_t s)
 {
     constexpr int NB = KS <= 4 ? 4 : 2;
     // weights: 16-byte loads when every 16-element piece of a column is 16-byte aligned, else dwords
     const bool b16 = !INT4 && aligned_to(a.g.B, 16) && (a.g.ldb % 16) == 0 && (a.g.K % 16) == 0;
     if constexpr (VEC == 16) {
         if (a.g.R) { // residual add in the store phase (the launcher only leaves R set for VEC == 16)
-            if (b16) hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 16, true>), dim3(blocks), dim3(256), 0, s, a);
-            else hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 4, true>), dim3(blocks), dim3(256), 0, s, a);
+            // from 2^24 outputs on the 65536-entry pair table pays for itself; below, two 256-entry tables
+            const bool pairs = a.g.M * (int64_t)a.g.N >= ((int64_t)1 << 24);
+            if (b16) pairs ? launch_shortk_add<NB, KS, INT4, VEC, 16, 2>(a, waves, s) : launch_shortk_add<NB, KS, INT4, VEC, 16, 1>(a, waves, s);
+            else pairs ? launch_shortk_add<NB, KS, INT4, VEC, 4, 2>(a, waves, s) : launch_shortk_add<NB, KS, INT4, VEC, 4, 1>(a, waves, s);
             return;
         }
     }
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
     if (b16) hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 16>), dim3(blocks), dim3(256), 0, s, a);
     else hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 4>), dim3(blocks), dim3(256), 0, s, a);
 }
 
-template <bool INT4, int VEC> static void launch_shortk_ks(const ShortKArgs &a, int ks, unsigned blocks, hipStream_t s)
+template <bool INT4, int VEC> static void launch_shortk_ks(const ShortKArgs &a, int ks, int64_t waves, hipStream_t s)
 {
-    if (ks <= 1) launch_shortk_one<1, INT4, VEC>(a, blocks, s);
-    else if (ks <= 2) launch_shortk_one<2, INT4, VEC>(a, blocks, s);
-    else if (ks <= 4) launch_shortk_one<4, INT4, VEC>(a, blocks, s);
-    else launch_shortk_one<8, INT4, VEC>(a, blocks, s);
+    if (ks <= 1) launch_shortk_one<1, INT4, VEC>(a, waves, s);
+    else if (ks <= 2) launch_shortk_one<2, INT4, VEC>(a, waves, s);
+    else if (ks <= 4) launch_shortk_one<4, INT4, VEC>(a, waves, s);
+    else launch_shortk_one<8, INT4, VEC>(a, waves, s);
 }
 
 bool shortk_eligible(const IgemmArgs &g, int b_mode, bool strided)
@@ -54,7 +74,10 @@ qnn_status launch_shortk(IgemmArgs &g, int b_mode, bool strided, hipStream_t s)
     const int64_t row_blocks = (g.M + 31) / 32;
     // as many waves as stay resident together (3 per SIMD for K <= 32, else 2, on 256 CUs), spread
     // over the column groups, then trimmed so that every wave walks the same number of row blocks
-    const int64_t resident = 256 * 4 * (ks <= 1 ? 3 : 2);
+    const int64_t row_pitch0 = strided ? g.Cin : g.lda;
+    const bool add_fused = g.R != nullptr && aligned_to(g.A, 16) && (row_pitch0 % 16) == 0 && (g.K % 16) == 0 && g.c_vec16 &&
+                           g.r_vec16 && (g.N % 16) == 0; // the variant with the add built in: 8-wave workgroups, one per CU
+    const int64_t resident = 256 * 4 * ((ks <= 1 && !add_fused) ? 3 : 2);
     int64_t walkers = resident / a.col_groups;
     walkers = walkers < 1 ? 1 : (walkers > row_blocks ? row_blocks : walkers);
     const int64_t per_walker = (row_blocks + walkers - 1) / walkers;
@@ -62,18 +85,17 @@ qnn_status launch_shortk(IgemmArgs &g, int b_mode, bool strided, hipStream_t s)
     a.walkers = (int)walkers;
     const int64_t waves = walkers * a.col_groups;
     if (waves > 0x7fffffff) return QNN_EINVAL;
-    const unsigned blocks = (unsigned)((waves + 3) / 4);
     const int64_t row_pitch = strided ? g.Cin : g.lda;
     const bool v16 = aligned_to(g.A, 16) && (row_pitch % 16) == 0 && (g.K % 16) == 0;
     // the add is built into the 16-byte variants only, for outputs and residuals made of whole aligned chunks
-    const bool add_pass = g.R != nullptr && !(v16 && g.c_vec16 && g.r_vec16 && (g.N % 16) == 0);
+    const bool add_pass = g.R != nullptr && !add_fused;
     if (add_pass) a.g.R = nullptr;
     if (b_mode == B_INT4) {
-        if (v16) launch_shortk_ks<true, 16>(a, ks, blocks, s);
-        else launch_shortk_ks<true, 8>(a, ks, blocks, s);
+        if (v16) launch_shortk_ks<true, 16>(a, ks, waves, s);
+        else launch_shortk_ks<true, 8>(a, ks, waves, s);
     } else {
-        if (v16) launch_shortk_ks<false, 16>(a, ks, blocks, s);
-        else launch_shortk_ks<false, 8>(a, ks, blocks, s);
+        if (v16) launch_shortk_ks<false, 16>(a, ks, waves, s);
+        else launch_shortk_ks<false, 8>(a, ks, waves, s);
     }
     const qnn_status st = launch_status(hipGetLastError());
     if (st != QNN_OK || !add_pass) return st;

@@ -62,24 +62,45 @@ struct ShortKColumn {
 
 // ADD: the rescaling add with a residual tensor (g.R) is applied to the output tile on its way
 // from LDS to global memory; the residual chunks of a row block are requested one round ahead.
-template <int NB, int KS, bool INT4, int VEC, int BVEC, bool ADD = false>
-__global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const ShortKArgs s)
+// The add is a function of two 8-bit codes, so the workgroup (8 waves here, to share it) first
+// tabulates all 65536 results in LDS; combining a pair of codes is then one byte gather.
+template <int NB, int KS, bool INT4, int VEC, int BVEC, int ADD = 0> // ADD: 0 none, 1 two 256-entry tables, 2 pair table
+__global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 ? 3 : 2)) shortk_kernel(const ShortKArgs s)
 {
     constexpr int PITCH = 32 * NB + 32; // bytes per staged output row: the 8 rows a store instruction touches fall in distinct banks
-    __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][32 * PITCH];
-    __shared__ int32_t add_tab[ADD ? 512 : 1];
+    constexpr int WAVES = ADD == 2 ? 8 : 4; // the pair table is shared by 8 waves (one workgroup per CU)
+    __shared__ __attribute__((aligned(16))) uint8_t stage_static[ADD ? 16 : 4 * 32 * PITCH];
+    extern __shared__ __attribute__((aligned(16))) uint8_t dyn_lds[]; // ADD: [table(s)][output tiles of the waves]
+    uint8_t *const pair_tab = dyn_lds;
+    constexpr int TAB_BYTES = ADD == 2 ? 65536 : 2048; // pair table, or the two 256-entry tables
+    uint8_t *const stage_all = ADD ? dyn_lds + TAB_BYTES : stage_static;
     const IgemmArgs &g = s.g;
-    if constexpr (ADD) { // the only workgroup barrier, before any wave may leave
-        add_fill_tables(add_tab, g.add, threadIdx.x, 256);
+    // small layers skip the pair table (building it would cost more than it saves) and combine through
+    // the two 256-entry tables of rescaled codes instead
+    constexpr bool use_pairs = ADD == 2;
+    int32_t *const tab = reinterpret_cast<int32_t *>(use_pairs ? stage_all : pair_tab); // pairs: in the tile area for now
+    if constexpr (ADD) { // the only workgroup barriers, before any wave may leave
+        add_fill_tables(tab, g.add, threadIdx.x, WAVES * 64);
         __syncthreads();
+        if constexpr (use_pairs) {
+            const AddOut ao = make_add_out(g.add);
+            // entry [m][r] = code of the sum; a lane fills 4 consecutive r of one m per step
+            for (int q = threadIdx.x; q < 65536 / 4; q += 512) {
+                const uint32_t m = (uint32_t)q >> 6, r0 = ((uint32_t)q & 63u) * 4u;
+                const uint32_t mm = m * 0x01010101u, rr = (r0 * 0x01010101u) + 0x03020100u;
+                reinterpret_cast<uint32_t *>(pair_tab)[q] =
+                    ao.fused ? add_codes4<true>(mm, rr, tab, ao) : add_codes4<false>(mm, rr, tab, ao);
+            }
+            __syncthreads();
+        }
     }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); // wave-uniform: row-block arithmetic stays scalar
-    uint8_t *stage = stage_all[wave];
+    uint8_t *stage = stage_all + wave * (32 * PITCH);
     const int frow = lane & 31, fhalf = lane >> 5;
 
     // wave -> (column group, walker): neighbouring waves take neighbouring column groups of the same rows
-    const int64_t gw = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t gw = (int64_t)blockIdx.x * WAVES + wave;
     const int cg = (int)(gw % s.col_groups), walker = (int)(gw / s.col_groups);
     if (walker >= s.walkers) return; // no barriers below: a wave may leave alone
     const int n0 = cg * 32 * NB;
@@ -179,7 +200,6 @@ __global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const Sh
     const int32_t lo_rel = g.lo_rel, hi_rel = g.hi_rel, z_out = g.z_out;
 
     // residual chunks of a row block (ADD): same lanes and addresses as the stores of that block
-    const AddOut ao = make_add_out(g.add);
     int64_t st_roff[NB];
     u32x4 rres[NB];
 #pragma unroll
@@ -193,17 +213,27 @@ __global__ void __launch_bounds__(256, (KS <= 1 ? 3 : 2)) shortk_kernel(const Sh
         for (int i = 0; i < NB; ++i)
             if (st_col_ok[i] && rbx * 32 + st_row[i] < M) rres[i] = *reinterpret_cast<const u32x4 *>(r_block + st_roff[i]);
     };
+    // 16 codes of the layer (v) and of the residual (r) -> 16 output codes: the byte pairs are
+    // interleaved into 16-bit table indices [m << 8 | r], one byte gather each
+    const AddOut ao = make_add_out(g.add);
     auto add16 = [&](u32x4 v, u32x4 r) __attribute__((always_inline)) {
         u32x4 y;
-        if (ao.fused) {
+        if constexpr (use_pairs) {
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                y[d] = add_codes4<true>(v[d], r[d], add_tab, ao);
+                const uint32_t i01 = __builtin_amdgcn_perm(v[d], r[d], 0x05010400u), i23 = __builtin_amdgcn_perm(v[d], r[d], 0x07030602u);
+                const uint32_t t0 = pair_tab[i01 & 0xffffu], t1 = pair_tab[i01 >> 16], t2 = pair_tab[i23 & 0xffffu], t3 = pair_tab[i23 >> 16];
+                y[d] = t0 | (t1 << 8) | (t2 << 16) | (t3 << 24);
+            }
+        } else if (ao.fused) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                y[d] = add_codes4<true>(v[d], r[d], tab, ao);
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
 #pragma nounroll
-            for (int d = 0; d < 4; ++d) y[d] = add_codes4<false>(v[d], r[d], add_tab, ao);
+            for (int d = 0; d < 4; ++d) y[d] = add_codes4<false>(v[d], r[d], tab, ao);
         }
         return y;
     };

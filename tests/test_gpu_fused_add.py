@@ -67,6 +67,15 @@ def test_qgemm_add_short_k(M, N, K, bits):
                     bits=bits, odd=True, act="none")
 
 
+@pytest.mark.parametrize("M,N,K,bits", [(70001, 256, 64, 8), (33000, 512, 160, 4)])
+def test_qgemm_add_pair_table(M, N, K, bits):
+    # from 2^24 outputs on, the short-K kernel combines the two codes through a 65536-entry table
+    assert M * N >= 2 ** 24 and qnn.qgemm_plan(M, N, K) == "shortk"
+    _check_gemm_add(M, N, K, 4150 + K, f"qgemm_add pair table {M}x{N}x{K} bits={bits}", bits=bits, mid=(2, 251))
+    _check_gemm_add(M, N, K, 4160 + K, f"qgemm_add pair table {M}x{N}x{K} bits={bits}, general add rescale", bits=bits, odd=True,
+                    act="none")
+
+
 @pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma64x64",
                                   "dma256x64s3", "128x128", "64x64"])
 @pytest.mark.parametrize("M,N,K", [(300, 270, 512), (513, 130, 320)])
