@@ -170,13 +170,8 @@ static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = Spli
     constexpr int kOut = BM * (BN + 16) + 4 * WM * WN * (BN / WN / 32) * 64 + 2048 + 4 * BM; // + add tables + row sums
     constexpr int kLds = kStages > kOut ? kStages : kOut; // operand ring, reused for the output tile + column sums + add tables
     auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE, SPLIT, ZW>;
-    static bool configured = false; // per instantiation
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static LdsOptIn opt_in; // per instantiation
+    if (hipError_t e = opt_in.ensure(reinterpret_cast<const void *>(kernel), kLds); e != hipSuccess) return e;
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (g.N + BN - 1) / BN;
     const int64_t work = (int64_t)tiles_m * tiles_n * sk.splits;
     int per_xcd = (int)((work + 7) / 8), xcd_rows = 0;

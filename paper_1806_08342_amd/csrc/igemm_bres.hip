@@ -10,12 +10,8 @@ template <int NB, int KC, bool INT4, bool CONV, bool PAD = false>
 static hipError_t launch_bres_one(const BResArgs &a, unsigned blocks, int lds, hipStream_t s)
 {
     auto kernel = bres_kernel<NB, KC, INT4, CONV, PAD>;
-    static int configured = 0; // per instantiation: largest dynamic LDS size enabled so far
-    if (lds > configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        configured = lds;
-    }
+    static LdsOptIn opt_in; // per instantiation
+    if (hipError_t e = opt_in.ensure(reinterpret_cast<const void *>(kernel), lds); e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(blocks), dim3(512), lds, s, a);
     return hipGetLastError();
 }

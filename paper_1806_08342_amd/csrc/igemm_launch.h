@@ -2,6 +2,7 @@
 // translation unit of its own (igemm_*.hip) and called from the dispatcher in igemm.hip.
 #pragma once
 
+#include <atomic>
 #include <cstdint>
 #include <cstdlib>
 
@@ -11,6 +12,23 @@ namespace qnn {
 
 // magic number for dividing by d with a multiply-high (see the kernels that take it)
 inline uint32_t magic_for(uint32_t d) { return d <= 1 ? 0u : (uint32_t)(((1ull << 32) + d - 1) / d); }
+
+// Kernels that use more than 64 KB of dynamic LDS must opt in once per device.  One object per kernel
+// instantiation (a function-local static); safe to call from several threads (setting the attribute
+// twice is harmless).
+struct LdsOptIn {
+    std::atomic<int> enabled[64] = {}; // bytes enabled so far, per device
+    hipError_t ensure(const void *kernel, int bytes)
+    {
+        int dev = 0;
+        if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (enabled[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+        if (hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); e != hipSuccess) return e;
+        enabled[dev].store(bytes, std::memory_order_release);
+        return hipSuccess;
+    }
+};
 
 inline bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 

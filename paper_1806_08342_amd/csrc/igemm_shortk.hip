@@ -14,13 +14,8 @@ static void launch_shortk_add(const ShortKArgs &a, int64_t waves, hipStream_t s)
     constexpr int kWaves = ADD == 2 ? 8 : 4;
     constexpr int kLds = (ADD == 2 ? 65536 : 2048) + kWaves * 32 * (32 * NB + 32);
     auto kernel = shortk_kernel<NB, KS, INT4, VEC, BVEC, ADD>;
-    static bool configured = false; // per instantiation
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLds) !=
-            hipSuccess)
-            return; // the error stays pending for the caller's hipGetLastError
-        configured = true;
-    }
+    static LdsOptIn opt_in; // per instantiation
+    if (opt_in.ensure(reinterpret_cast<const void *>(kernel), kLds) != hipSuccess) return; // the error stays pending for the caller
     hipLaunchKernelGGL(kernel, dim3((unsigned)((waves + kWaves - 1) / kWaves)), dim3(kWaves * 64), kLds, s, a);
 }
 
