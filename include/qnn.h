@@ -163,6 +163,16 @@ qnn_status qnn_qadd(const uint8_t *a, int32_t z_a, int32_t mult_a, int32_t shift
                     int32_t mult_b, int32_t shift_b, int32_t left_shift, int32_t mult_o, int32_t shift_o,
                     int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *y, size_t n, void *stream);
 
+/* Re-quantization of uint8 codes from one quantizer to another (Sec. 3.2.1: the inputs of a
+ * concatenation have to be rescaled to the output's quantizer before they are laid side by side):
+ *   y[m][c] = clamp(act_min, act_max, z_out + RESCALE(x[m][c] - z_in; mult, shift)),
+ * mult, shift from qnn_quantize_multiplier(s_in / s_out).  rows x cols elements with row pitches
+ * ldx, ldy >= cols, so y can be a channel slice of the concatenated NHWC tensor (ldy = its channel count).
+ * x: DEVICE uint8 (read); y: DEVICE uint8 (written); the two must not overlap. */
+qnn_status qnn_rescale_u8(const uint8_t *x, int64_t ldx, int32_t z_in, int32_t mult, int32_t shift, int32_t z_out,
+                          int32_t act_min, int32_t act_max, uint8_t *y, int64_t ldy, int64_t rows, int64_t cols,
+                          void *stream);
+
 /* The add of Sec. 3.2.1 fused behind the layer that produces one of its operands (the last 1x1
  * convolution of a residual block; fusing operators is what Sec. 3.2 and the recommendations of
  * Sec. 5 advise): the layer's uint8 result never goes to memory.  Bit for bit the same as

@@ -20,7 +20,7 @@ B_COLUMNS_CONTIGUOUS, B_ROWS_CONTIGUOUS = 0, 1
 
 EXPORTS = [
     "qnn_last_error", "qnn_version", "qnn_qgemm_plan", "qnn_quantize", "qnn_dequantize", "qnn_requantize", "qnn_qgemm", "qnn_pack_b",
-    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_minmax", "qnn_quantize_with",
+    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_rescale_u8", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_minmax", "qnn_quantize_with",
     "qnn_quantize_dynamic", "qnn_simquant", "qnn_simquant_backward", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
     "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4",
 ]
@@ -66,6 +66,7 @@ def load_library():
         "qnn_simquant_backward": [vp, vp, vp, sz, f32, i32, i32, i32, vp],
         "qnn_qgemm_asym": [vp, i64, i32, vp, i64, ci, ci, vp, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
         "qnn_qconv2d_asym": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
+        "qnn_rescale_u8": [vp, i64, i32, i32, i32, i32, i32, i32, vp, i64, i64, i64, vp],
         "qnn_qgemm_add": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, vp, i64, vp],
         "qnn_qconv2d_add": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp,
                             vp, vp],
@@ -434,6 +435,19 @@ def simquant_backward(x, grad_y, scale, zero_point, qmin=0, qmax=255, out=None):
         _dev(x, torch.float32, "x"), _dev(grad_y, torch.float32, "grad_y"), _dev(gx, torch.float32, "grad_x"), x.numel(),
         float(scale), int(zero_point), int(qmin), int(qmax), _stream()))
     return gx
+
+
+def rescale_u8(x, z_in, mult, shift, z_out, act_min=0, act_max=255, out=None):
+    """uint8 [rows, cols] (rows may be spaced apart) re-quantized to another quantizer; `out` may be a
+    column slice of a wider tensor (the destination of a concatenation)."""
+    torch = _torch()
+    rows, cols = x.shape
+    y = torch.empty((rows, cols), dtype=torch.uint8, device=x.device) if out is None else out
+    xp, ldx = _dev_rows(x, torch.uint8, "x")
+    yp, ldy = _dev_rows(y, torch.uint8, "y")
+    _check("qnn_rescale_u8", load_library().qnn_rescale_u8(xp, ldx, int(z_in), int(mult), int(shift), int(z_out), int(act_min),
+                                                           int(act_max), yp, ldy, rows, cols, _stream()))
+    return y
 
 
 def qdwconv2d(x, z_x, w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, out=None):

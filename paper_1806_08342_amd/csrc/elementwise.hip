@@ -419,6 +419,44 @@ __global__ void __launch_bounds__(kThreads) qadd_kernel(const uint8_t *__restric
 }
 
 
+// ------------------------------------------------------ rescale of uint8 codes (concat)
+
+// Sec. 3.2.1: the inputs of a concatenation carry different quantizers and must be brought to the
+// output's before they are laid side by side.  y[m][c] = clamp(z_out + RESCALE(x[m][c] - z_in)) is a
+// function of one 8-bit code: a 256-entry byte table per workgroup, one gather per element.  Rows
+// have their own pitches, so the destination can be a channel slice of the concatenated tensor.
+__global__ void __launch_bounds__(kThreads) rescale_u8_kernel(const uint8_t *__restrict__ x, int64_t ldx, uint8_t *__restrict__ y,
+                                                              int64_t ldy, int64_t rows, int64_t cols, int32_t z_in, int32_t mult,
+                                                              int32_t shift, int32_t z_out, int32_t act_min, int32_t act_max,
+                                                              int vec16)
+{
+    __shared__ uint8_t lut[256];
+    {
+        const int v = threadIdx.x; // kThreads == 256
+        const int32_t r = rescale_general(v - z_in, make_rescale(mult, shift));
+        lut[v] = (uint8_t)(clamp_i32(act_min - z_out, act_max - z_out, r) + z_out);
+    }
+    __syncthreads();
+    const int64_t chunks_per_row = (cols + 15) / 16, total = rows * chunks_per_row;
+    for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < total; q += (int64_t)gridDim.x * kThreads) {
+        const int64_t m = q / chunks_per_row;
+        const int64_t c = (q - m * chunks_per_row) * 16;
+        const uint8_t *xp = x + m * ldx + c;
+        uint8_t *yp = y + m * ldy + c;
+        if (vec16 && c + 16 <= cols) {
+            const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(xp));
+            u32x4 o;
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                o[d] = (uint32_t)lut[a[d] & 0xffu] | ((uint32_t)lut[(a[d] >> 8) & 0xffu] << 8) |
+                       ((uint32_t)lut[(a[d] >> 16) & 0xffu] << 16) | ((uint32_t)lut[a[d] >> 24] << 24);
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(yp));
+        } else {
+            for (int e = 0; e < 16 && c + e < cols; ++e) yp[e] = lut[xp[e]];
+        }
+    }
+}
+
 // ------------------------------------------------ add behind a product, second-pass form
 
 // y = ADD(y, r) row by row, in place (each 16-byte chunk is read, combined and written by one lane)
@@ -604,6 +642,22 @@ qnn_status qnn_simquant_backward(const float *x, const float *grad_y, float *gra
     const float xmin = (float)(qmin - zero_point) * scale, xmax = (float)(qmax - zero_point) * scale;
     hipLaunchKernelGGL(simquant_backward_kernel, dim3(grid_for(n, kThreads * 4)), dim3(kThreads), 0, as_stream(stream), x, grad_y,
                        grad_x, n, xmin, xmax);
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_rescale_u8(const uint8_t *x, int64_t ldx, int32_t z_in, int32_t mult, int32_t shift, int32_t z_out,
+                          int32_t act_min, int32_t act_max, uint8_t *y, int64_t ldy, int64_t rows, int64_t cols, void *stream)
+{
+    if (rows < 0 || cols < 0 || z_in < 0 || z_in > 255 || shift < -31 || shift > 31) return QNN_EINVAL;
+    if (bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
+    if (rows == 0 || cols == 0) return QNN_OK;
+    if (!x || !y || ldx < cols || ldy < cols) return QNN_EINVAL;
+    int64_t r = rows, c = cols;
+    if (ldx == cols && ldy == cols) r = 1, c = rows * cols, ldx = ldy = c; // dense: one long row, whole chunks throughout
+    const int vec16 = aligned(x, 16) && aligned(y, 16) && (r == 1 || ((ldx % 16) == 0 && (ldy % 16) == 0));
+    const size_t chunks = (size_t)r * (size_t)((c + 15) / 16);
+    hipLaunchKernelGGL(rescale_u8_kernel, dim3(grid_for(chunks, kThreads * 2)), dim3(kThreads), 0, as_stream(stream), x, ldx, y, ldy,
+                       r, c, z_in, mult, shift, z_out, act_min, act_max, vec16);
     return launch_status(hipGetLastError());
 }
 

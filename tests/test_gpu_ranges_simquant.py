@@ -98,3 +98,39 @@ def test_simquant_forward_and_backward_match_oracle(n):
     ends = oracle.dequantize(np.array([0, 255], np.uint8), 2.0 ** -5, 102)
     gx = host(qnn.simquant_backward(dev(ends), dev(np.ones(2, np.float32)), 2.0 ** -5, 102))
     assert gx.tolist() == [1.0, 1.0]
+
+
+# ------------------------------------------------------------ rescale of uint8 codes (concat)
+
+@pytest.mark.parametrize("rows,cols", [(1, 1), (7, 5), (100, 64), (333, 48), (4096, 130)])
+def test_rescale_u8_matches_oracle_requantize(rows, cols):
+    # the oracle side is its pinned requantize applied to (x - z_in): no arithmetic of its own
+    rng = np.random.default_rng(6400 + rows + cols)
+    x = rng.integers(0, 256, (rows, cols)).astype(np.uint8)
+    for s_in, s_out, z_in, z_out, lo, hi in [(0.02, 0.05, 128, 100, 0, 255), (0.07, 0.03, 3, 0, 0, 255), (0.01, 0.01, 255, 255, 0, 255),
+                                              (0.5, 0.001, 17, 128, 5, 250), (1e-3, 1.0, 200, 7, 0, 255)]:
+        mult, shift = oracle.quantize_multiplier(s_in / s_out)
+        want = oracle.requantize(x.astype(np.int32) - z_in, np.array([mult]), np.array([shift]), False, z_out, lo, hi)
+        got = host(qnn.rescale_u8(dev(x), z_in, mult, shift, z_out, lo, hi))
+        assert_same(got, want, f"rescale_u8 {rows}x{cols} s_in={s_in} s_out={s_out}")
+
+
+def test_rescale_u8_writes_a_channel_slice_of_a_concatenation():
+    rng = np.random.default_rng(6500)
+    rows, c1, c2 = 500, 48, 80
+    a = rng.integers(0, 256, (rows, c1)).astype(np.uint8)
+    b = rng.integers(0, 256, (rows, c2)).astype(np.uint8)
+    out = torch.full((rows, c1 + c2), 9, dtype=torch.uint8, device="cuda:0")
+    want = np.empty((rows, c1 + c2), np.uint8)
+    for src, z_in, s_in, off in [(a, 120, 0.031, 0), (b, 7, 0.012, c1)]:
+        mult, shift = oracle.quantize_multiplier(s_in / 0.02)
+        qnn.rescale_u8(dev(src), z_in, mult, shift, 64, 0, 255, out=out[:, off:off + src.shape[1]])
+        want[:, off:off + src.shape[1]] = oracle.requantize(src.astype(np.int32) - z_in, np.array([mult]), np.array([shift]), False,
+                                                           64, 0, 255)
+    assert_same(host(out), want, "concat of two rescaled inputs")
+    # a source that is itself a slice (odd byte offset: byte path)
+    wide = rng.integers(0, 256, (rows, 100)).astype(np.uint8)
+    mult, shift = oracle.quantize_multiplier(1.7)
+    got = host(qnn.rescale_u8(dev(wide)[:, 3:70], 50, mult, shift, 60, 0, 255))
+    assert_same(got, oracle.requantize(wide[:, 3:70].astype(np.int32) - 50, np.array([mult]), np.array([shift]), False, 60, 0, 255),
+                "rescale_u8 from a slice")

@@ -136,6 +136,9 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     assert lib.qnn_simquant_backward(p, p, p, 16, C.c_float(0.1), 0, 9, 3, None) == EINVAL
     assert lib.qnn_simquant_backward(p, null, p, 16, C.c_float(0.1), 0, 0, 255, None) == EINVAL
     assert lib.qnn_simquant(null, null, 0, C.c_float(0.1), 0, 0, 255, None) == 0
+    assert lib.qnn_rescale_u8(p, 8, 0, 1 << 30, 1, 0, 0, 255, p, 4, 2, 8, None) == EINVAL   # ldy < cols
+    assert lib.qnn_rescale_u8(p, 8, 300, 1 << 30, 1, 0, 0, 255, p, 8, 2, 8, None) == EINVAL
+    assert lib.qnn_rescale_u8(null, 8, 0, 1 << 30, 1, 0, 0, 255, null, 8, 0, 8, None) == 0
     # asymmetric weights: the zero-point array is required, and K is limited to 32768
     asym = lambda z_w=p, K=64: lib.qnn_qgemm_asym(p, K, 0, p, K, 0, 8, z_w, 64, 64, K, null, p, p, 0, 0, 255, p, 64, None)
     assert asym(z_w=null) == EINVAL
