@@ -262,6 +262,13 @@ qnn_status qnn_simquant(const float *x, float *y, size_t n, float scale, int32_t
 qnn_status qnn_simquant_backward(const float *x, const float *grad_y, float *grad_x, size_t n, float scale,
                                  int32_t zero_point, int32_t qmin, int32_t qmax, void *stream);
 
+/* Depthwise convolution with a zero-point per channel of the weights (as qnn_qconv2d_asym; one lane per
+ * output evaluates sum (x - z_x)(w - z_w[c]) over the taps inside the image directly).  z_w: DEVICE int32[C]. */
+qnn_status qnn_qdwconv2d_asym(const uint8_t *x, int N, int H, int W, int C, int32_t z_x, const int8_t *w, int kh, int kw,
+                              const int32_t *z_w, int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias,
+                              const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
+                              uint8_t *y, void *stream);
+
 /* ------------------------------------------------------------------ host-only helpers */
 
 /* Quantizer parameters from a real range, Sec. 2.1: the range is first widened to contain 0,

@@ -20,7 +20,7 @@ B_COLUMNS_CONTIGUOUS, B_ROWS_CONTIGUOUS = 0, 1
 
 EXPORTS = [
     "qnn_last_error", "qnn_version", "qnn_qgemm_plan", "qnn_quantize", "qnn_dequantize", "qnn_requantize", "qnn_qgemm", "qnn_pack_b",
-    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_rescale_u8", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_minmax", "qnn_quantize_with",
+    "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_rescale_u8", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_qdwconv2d_asym", "qnn_minmax", "qnn_quantize_with",
     "qnn_quantize_dynamic", "qnn_simquant", "qnn_simquant_backward", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
     "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4",
 ]
@@ -64,6 +64,7 @@ def load_library():
         "qnn_quantize_dynamic": [vp, vp, sz, vp, vp],
         "qnn_simquant": [vp, vp, sz, f32, i32, i32, i32, vp],
         "qnn_simquant_backward": [vp, vp, vp, sz, f32, i32, i32, i32, vp],
+        "qnn_qdwconv2d_asym": [vp, ci, ci, ci, ci, i32, vp, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
         "qnn_qgemm_asym": [vp, i64, i32, vp, i64, ci, ci, vp, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
         "qnn_qconv2d_asym": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
         "qnn_rescale_u8": [vp, i64, i32, i32, i32, i32, i32, i32, vp, i64, i64, i64, vp],
@@ -447,6 +448,20 @@ def rescale_u8(x, z_in, mult, shift, z_out, act_min=0, act_max=255, out=None):
     yp, ldy = _dev_rows(y, torch.uint8, "y")
     _check("qnn_rescale_u8", load_library().qnn_rescale_u8(xp, ldx, int(z_in), int(mult), int(shift), int(z_out), int(act_min),
                                                            int(act_max), yp, ldy, rows, cols, _stream()))
+    return y
+
+
+def qdwconv2d_asym(x, z_x, w, z_w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, out=None):
+    """Depthwise layer with a weight zero-point per channel: z_w int32 [C] on the device."""
+    torch = _torch()
+    N, H, W, Cc = x.shape
+    kh, kw = w.shape[:2]
+    Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
+    y = torch.empty((N, Ho, Wo, Cc), dtype=torch.uint8, device=x.device) if out is None else out
+    _check("qnn_qdwconv2d_asym", load_library().qnn_qdwconv2d_asym(
+        _dev(x, torch.uint8, "x"), N, H, W, Cc, z_x, _dev(w, torch.int8, "w"), kh, kw, _dev(z_w, torch.int32, "z_w"), stride[0],
+        stride[1], pad[0], pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"),
+        _dev(shift, torch.int32, "shift"), z_out, act_min, act_max, _dev(y, torch.uint8, "y"), _stream()))
     return y
 
 

@@ -22,6 +22,7 @@ struct DwArgs {
     const int8_t *w;
     uint8_t *y;
     const int32_t *bias, *mult, *shift;
+    const int32_t *zw; // per-channel weight zero-points, or nullptr (generic kernel only)
     int N, H, W, C, Ho, Wo, kh, kw, sh, sw, ph, pw;
     int32_t z_x, z_out, lo_rel, hi_rel;
     int64_t total_work; // lanes of work
@@ -338,6 +339,7 @@ __global__ void __launch_bounds__(256) dwconv_generic_kernel(const DwArgs g)
     const int ho = (int)(t % g.Ho);
     const int n = (int)(t / g.Ho);
     int32_t acc = g.bias ? g.bias[c] : 0;
+    const int32_t zw = g.zw ? g.zw[c] : 0;
     for (int a = 0; a < g.kh; ++a) {
         const int hi = ho * g.sh - g.ph + a;
         if (hi < 0 || hi >= g.H) continue;
@@ -345,7 +347,7 @@ __global__ void __launch_bounds__(256) dwconv_generic_kernel(const DwArgs g)
             const int wi = wo * g.sw - g.pw + b;
             if (wi < 0 || wi >= g.W) continue;
             const int32_t xv = (int32_t)g.x[(((int64_t)n * g.H + hi) * g.W + wi) * g.C + c] - g.z_x;
-            acc += xv * (int32_t)g.w[((int64_t)a * g.kw + b) * g.C + c];
+            acc += xv * ((int32_t)g.w[((int64_t)a * g.kw + b) * g.C + c] - zw); // eq. 4 taken literally
         }
     }
     const RescaleParams rp = make_rescale(g.mult[c], g.shift[c]);
@@ -356,10 +358,10 @@ __global__ void __launch_bounds__(256) dwconv_generic_kernel(const DwArgs g)
 
 using namespace qnn;
 
-extern "C" qnn_status qnn_qdwconv2d(const uint8_t *x, int N, int H, int W, int C, int32_t z_x, const int8_t *w, int kh,
-                                    int kw, int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias,
-                                    const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min,
-                                    int32_t act_max, uint8_t *y, void *stream)
+static qnn_status qdwconv2d_impl(const uint8_t *x, int N, int H, int W, int C, int32_t z_x, const int8_t *w, int kh, int kw,
+                                 int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias, const int32_t *mult,
+                                 const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *y,
+                                 void *stream, const int32_t *z_w)
 {
     if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || kh <= 0 || kw <= 0 || kh > 7 || kw > 7) return QNN_EINVAL;
@@ -367,7 +369,7 @@ extern "C" qnn_status qnn_qdwconv2d(const uint8_t *x, int N, int H, int W, int C
     if (H + 2 * (int64_t)pad_h < kh || W + 2 * (int64_t)pad_w < kw) return QNN_EINVAL;
     if (z_x < 0 || z_x > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
     DwArgs g = {};
-    g.x = x, g.w = w, g.y = y, g.bias = bias, g.mult = mult, g.shift = shift;
+    g.x = x, g.w = w, g.y = y, g.bias = bias, g.mult = mult, g.shift = shift, g.zw = z_w;
     g.N = N, g.H = H, g.W = W, g.C = C, g.kh = kh, g.kw = kw;
     g.sh = stride_h, g.sw = stride_w, g.ph = pad_h, g.pw = pad_w;
     g.Ho = (H + 2 * pad_h - kh) / stride_h + 1;
@@ -375,7 +377,8 @@ extern "C" qnn_status qnn_qdwconv2d(const uint8_t *x, int N, int H, int W, int C
     g.z_x = z_x, g.z_out = z_out, g.lo_rel = act_min - z_out, g.hi_rel = act_max - z_out;
     const hipStream_t s = as_stream(stream);
     auto al4 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; };
-    const bool c4 = (C % 4 == 0) && al4(x) && al4(w) && al4(y) && kh == 3 && kw == 3 && stride_h == stride_w &&
+    // (weight zero-points: the one-lane-per-output kernel, which evaluates the defining sum directly)
+    const bool c4 = !z_w && (C % 4 == 0) && al4(x) && al4(w) && al4(y) && kh == 3 && kw == 3 && stride_h == stride_w &&
                     (stride_h == 1 || stride_h == 2);
     constexpr int RH = 2, RW = 4;
     if (c4) {
@@ -418,4 +421,23 @@ extern "C" qnn_status qnn_qdwconv2d(const uint8_t *x, int N, int H, int W, int C
     else
         hipLaunchKernelGGL(dwconv_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, g);
     return launch_status(hipGetLastError());
+}
+
+extern "C" qnn_status qnn_qdwconv2d(const uint8_t *x, int N, int H, int W, int C, int32_t z_x, const int8_t *w, int kh,
+                                    int kw, int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias,
+                                    const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min,
+                                    int32_t act_max, uint8_t *y, void *stream)
+{
+    return qdwconv2d_impl(x, N, H, W, C, z_x, w, kh, kw, stride_h, stride_w, pad_h, pad_w, bias, mult, shift, z_out, act_min,
+                          act_max, y, stream, nullptr);
+}
+
+extern "C" qnn_status qnn_qdwconv2d_asym(const uint8_t *x, int N, int H, int W, int C, int32_t z_x, const int8_t *w, int kh,
+                                         int kw, const int32_t *z_w, int stride_h, int stride_w, int pad_h, int pad_w,
+                                         const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_out,
+                                         int32_t act_min, int32_t act_max, uint8_t *y, void *stream)
+{
+    if (!z_w) return QNN_EINVAL;
+    return qdwconv2d_impl(x, N, H, W, C, z_x, w, kh, kw, stride_h, stride_w, pad_h, pad_w, bias, mult, shift, z_out, act_min,
+                          act_max, y, stream, z_w);
 }

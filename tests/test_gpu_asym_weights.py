@@ -104,3 +104,20 @@ def test_qconv2d_asym_matches_oracle(shape, batch):
                                     dev(c["shift"]), c["z_out"], c["act_min"], c["act_max"], bias=dev(c["bias"]),
                                     weight_bits=bits))
         assert_same(got, want, f"qconv2d_asym {shape} batch {batch} z_x={z_x}")
+
+
+@pytest.mark.parametrize("shape", [(12, 12, 32, 3, 1, 1), (15, 9, 8, 3, 2, 1), (8, 8, 5, 5, 1, 2), (14, 14, 144, 3, 2, 1), (7, 7, 64, 3, 1, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_qdwconv2d_asym_matches_oracle(shape):
+    H, W, Cc, k, s, p = shape
+    layer = workloads.Layer("t", "dw", H, W, Cc, Cc, k=k, stride=s, pad=p)
+    c = synth.conv_case(layer, 2, 5400 + sum(shape), oracle)
+    rng = np.random.default_rng(5500 + sum(shape))
+    z_w = rng.integers(-128, 128, Cc).astype(np.int32)
+    z_w[0] = -128
+    for z_x in (c["z_x"], 0, 255):
+        want = oracle.qdwconv2d(c["x"], z_x, c["w"], c["stride"], c["pad"], c["mult"], c["shift"], c["z_out"], c["act_min"],
+                                c["act_max"], bias=c["bias"], z_w=z_w)
+        got = host(qnn.qdwconv2d_asym(dev(c["x"]), z_x, dev(c["w"]), dev(z_w), c["stride"], c["pad"], dev(c["mult"]),
+                                      dev(c["shift"]), c["z_out"], c["act_min"], c["act_max"], bias=dev(c["bias"])))
+        assert_same(got, want, f"qdwconv2d_asym {shape} z_x={z_x}")
