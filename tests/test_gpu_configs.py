@@ -117,9 +117,44 @@ def test_config4_resnet50_layers_batch256(idx):
     _check_layer(RN50[idx], 256, workloads.seed_for(4, idx), f"config 4 {RN50[idx].name} batch 256")
 
 
+def _check_fused_add_layer(layer, batch, seed, what):
+    """A convolution with the residual add of its block fused behind it, as bench.py times it: the
+    oracle evaluates the sampled outputs of the convolution and adds the matching residual elements."""
+    rng = np.random.default_rng(seed)
+    conv = shp.replace(layer, kind="conv", act="none")
+    c = synth.conv_case(conv, batch, seed, oracle)
+    ad = synth.qadd_case((1,), seed + 7, oracle, act=layer.act)
+    w = c.get("w_packed", c["w"])
+    res = rng.integers(0, 256, (batch, layer.Ho, layer.Wo, layer.Cout)).astype(np.uint8)
+    got = host(qnn.qconv2d_add(dev(c["x"]), c["z_x"], dev(w), c["stride"], c["pad"], dev(c["mult"]), dev(c["shift"]), c["z_out"], 0,
+                               255, dev(res), ad["z_b"], ad["params"], ad["z_out"], ad["act_min"], ad["act_max"],
+                               bias=dev(c["bias"]), weight_bits=layer.weight_bits))
+    sample = _sample_indices(rng, batch, layer.Ho, layer.Wo, layer.Cout)
+    mid = oracle.qconv2d(c["x"], c["z_x"], w, c["stride"], c["pad"], c["mult"], c["shift"], c["z_out"], 0, 255, bias=c["bias"],
+                         weight_bits=layer.weight_bits, sample=sample)
+    r = res.ravel() if sample is None else res.ravel()[sample]
+    want = oracle.qadd(mid.ravel(), c["z_out"], r, ad["z_b"], ad["params"], ad["z_out"], ad["act_min"], ad["act_max"])
+    assert_same(got.ravel() if sample is None else got.ravel()[sample], want, what)
+    assert len(np.unique(want)) > 16, f"{what}: parity would be vacuous"
+
+
+RN50_ADD = [l for l in shp.unique_shapes(workloads.fuse_adds(workloads.resnet50())) if l.kind == "conv_add"]
+
+
+@pytest.mark.parametrize("idx", range(len(RN50_ADD)), ids=[l.name for l in RN50_ADD])
+def test_config4_resnet50_fused_add_layers_batch256(idx):
+    _check_fused_add_layer(RN50_ADD[idx], 256, workloads.seed_for(4, 300 + idx), f"config 4 {RN50_ADD[idx].name} batch 256")
+
+
 # ------------------------------------------------------------------ configuration 5
 
 MBV2 = shp.unique_shapes(workloads.mobilenet_v2(4))
+MBV2_ADD = [l for l in shp.unique_shapes(workloads.fuse_adds(workloads.mobilenet_v2(4))) if l.kind == "conv_add"]
+
+
+@pytest.mark.parametrize("idx", range(len(MBV2_ADD)), ids=[l.name for l in MBV2_ADD])
+def test_config5_mobilenet_v2_fused_add_layers_batch32(idx):
+    _check_fused_add_layer(MBV2_ADD[idx], 32, workloads.seed_for(5, 300 + idx), f"config 5 {MBV2_ADD[idx].name} batch 32")
 
 
 @pytest.mark.parametrize("idx", range(len(MBV2)), ids=[l.name for l in MBV2])
