@@ -255,8 +255,15 @@ static qnn_status run_igemm_zw(IgemmArgs &g, int a_mode, int b_mode, int vec, in
         b_mode = B_INT8;
     }
     if (b_mode == B_INT8 && aligned_for_dma && ((g.M + 127) / 128) * ((g.N + 127) / 128) <= 0x7ffffff) {
-        const hipError_t e = a_mode == A_MATRIX ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, false, true>(g, s)
-                                                : launch_dma<128, 128, 2, 2, A_CONV, 4, false, true>(g, s);
+        // large products: the 256x256 tile once it fills most of the chip, else 128x128
+        const bool big = ((g.M + 255) / 256) * ((g.N + 255) / 256) >= 160 && g.K > 256;
+        hipError_t e;
+        if (big)
+            e = a_mode == A_MATRIX ? launch_dma<256, 256, 4, 2, A_MATRIX, 4, false, true>(g, s)
+                                   : launch_dma<256, 256, 4, 2, A_CONV, 4, false, true>(g, s);
+        else
+            e = a_mode == A_MATRIX ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, false, true>(g, s)
+                                   : launch_dma<128, 128, 2, 2, A_CONV, 4, false, true>(g, s);
         return finish(launch_status(e));
     }
     if (((g.M + 63) / 64) * ((g.N + 63) / 64) > 0x7ffffff) return finish(QNN_EINVAL);

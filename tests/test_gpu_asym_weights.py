@@ -55,6 +55,17 @@ def test_qgemm_asym_matches_oracle(M, N, K, bits):
     assert_same(same, sym, "z_w = 0")
 
 
+def test_qgemm_asym_large_tile_sampled_rows():
+    # 3000 x 4100 x 512: enough 256x256 tiles for the large-tile variant; ragged in both directions
+    M, N, K = 3000, 4100, 512
+    rng = np.random.default_rng(5050)
+    A, Bt, z_w, bias, mult, shift = _case(rng, M, N, K, 8)
+    got = host(qnn.qgemm_asym(dev(A), 200, dev(Bt), dev(z_w), dev(mult), dev(shift), 120, 0, 255, bias=dev(bias)))
+    rows = np.r_[0:40, 1500:1540, 2960:3000]
+    want = oracle.qgemm(A[rows], 200, Bt, mult, shift, 120, 0, 255, bias=bias, z_w=z_w)
+    assert_same(got[rows], want, "qgemm_asym 3000x4100x512 sampled rows")
+
+
 def test_qgemm_asym_extreme_operands_and_general_rescale():
     # all-255 activations against all-(-128) weights with z_w = 127 at the largest admissible K:
     # the true sum K * 255 * (-255) is close to -2^31 and every partial term wraps on the way
