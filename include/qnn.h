@@ -174,8 +174,8 @@ qnn_status qnn_rescale_u8(const uint8_t *x, int64_t ldx, int32_t z_in, int32_t m
                           void *stream);
 
 /* The add of Sec. 3.2.1 fused behind the layer that produces one of its operands (the last 1x1
- * convolution of a residual block; fusing operators is what Sec. 3.2 and the recommendations of
- * Sec. 5 advise): the layer's uint8 result never goes to memory.  Bit for bit the same as
+ * convolution of a residual block; fusing operators is what Sec. 3.2.1 and the accelerator
+ * recommendations of Sec. 7 advise): the layer's uint8 result never goes to memory.  Bit for bit the same as
  *   qnn_qgemm / qnn_qconv2d (with z_out = z_mid, act_min = mid_min, act_max = mid_max) into a
  *   temporary t, followed by
  *   qnn_qadd(t, z_mid, mult_m, shift_m, residual, z_r, mult_r, shift_r, left_shift, mult_o, shift_o,
@@ -204,7 +204,7 @@ qnn_status qnn_qconv2d_add(const uint8_t *x, int N, int H, int W, int Cin, int32
                            uint8_t *y, void *stream);
 
 /* The same layers with asymmetric per-channel weights: column / output channel n carries its own
- * zero-point z_w[n] (Sec. 2.1 affine quantizer applied per channel, Sec. 2.2; the scheme the
+ * zero-point z_w[n] (Sec. 2.1 affine quantizer at the per-channel granularity of Sec. 2.6; the scheme the
  * post-training experiments of Sec. 3.1 find most accurate).  The sum becomes
  *   sum_k (A[m][k] - z_a) * (B[k][n] - z_w[n])
  * = sum_k A*B - z_a * sum_k B[k][n] - z_w[n] * sum_k A[m][k] + K * z_a * z_w[n]        (eq. 5-6)

@@ -139,7 +139,7 @@ __device__ __forceinline__ int32_t clamp_i32(int32_t lo, int32_t hi, int32_t v)
 }
 
 // ---- rescaling add behind a product (the residual connection of Sec. 3.2.1 fused into the
-// producing layer, as the operator-fusion advice of Sec. 3.2 / 5 recommends).  The product's uint8
+// producing layer, as Sec. 3.2.1 and the operator-fusion recommendation of Sec. 7 advise).  The product's uint8
 // code m (its own scale and zero-point) and the residual's code r are brought to a common scale
 // and summed: RESCALE_o(RESCALE_m((m - z_m) << L) + RESCALE_r((r - z_r) << L)) + z_out, clamped.
 // The two inner values depend only on an 8-bit code: 2 x 256 entries, tabulated once per workgroup.
