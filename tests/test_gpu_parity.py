@@ -672,3 +672,51 @@ def test_qgemm_few_rows_matches_oracle(M, N, K, bits):
         want = oracle.qgemm(A, z_a, B, mult, shift, 120, 5, 250, bias=bias, weight_bits=bits)
         got = host(qnn.qgemm(dev(A), z_a, dev(B), dev(mult), dev(shift), 120, 5, 250, bias=dev(bias), weight_bits=bits))
         assert_same(got, want, f"few-row qgemm {M}x{N}x{K} bits={bits} z_a={z_a}")
+
+
+# ------------------------------------------------- rectangular kernels, strides and paddings
+
+RECT_CASES = [
+    # N, H, W, Cin, Cout, kh, kw, sh, sw, ph, pw, bits
+    (2, 17, 23, 16, 24, 1, 3, 1, 1, 0, 1, 8),
+    (3, 20, 14, 32, 40, 3, 5, 2, 1, 1, 2, 8),
+    (1, 31, 9, 64, 64, 7, 1, 3, 2, 3, 0, 8),
+    (2, 12, 40, 3, 32, 3, 7, 1, 2, 1, 3, 8),      # few channels, kernel row of 21 bytes: stem kernels
+    (2, 19, 19, 128, 96, 1, 1, 2, 3, 0, 0, 8),    # 1x1 with different strides: strided short-K rows
+    (2, 16, 16, 64, 48, 3, 3, 1, 2, 2, 0, 4),
+    (1, 9, 33, 20, 30, 5, 2, 2, 2, 4, 1, 8),      # padding larger than half the kernel
+]
+
+
+@pytest.mark.parametrize("case", RECT_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_qconv2d_rectangular_geometry_matches_oracle(case):
+    N, H, W, Cin, Cout, kh, kw, sh, sw, ph, pw, bits = case
+    rng = np.random.default_rng(8000 + sum(case))
+    x = rng.integers(0, 256, (N, H, W, Cin)).astype(np.uint8)
+    lim = 8 if bits == 4 else 128
+    w = rng.integers(-lim, lim, (Cout, kh, kw, Cin)).astype(np.int8)
+    K = kh * kw * Cin
+    mult, shift = oracle.quantize_multipliers(10 ** rng.uniform(-4.2, -3.2, Cout) / np.sqrt(K / 64.0) * (16.0 if bits == 4 else 1.0))
+    bias = rng.integers(-20000, 20000, Cout).astype(np.int32)
+    w_o = oracle.pack_int4(w) if bits == 4 else w
+    for z_x in (97, 0, 255):
+        want = oracle.qconv2d(x, z_x, w_o, (sh, sw), (ph, pw), mult, shift, 110, 0, 255, bias=bias, weight_bits=bits)
+        got = host(qnn.qconv2d(dev(x), z_x, dev(w_o), (sh, sw), (ph, pw), dev(mult), dev(shift), 110, 0, 255, bias=dev(bias),
+                               weight_bits=bits))
+        assert_same(got, want, f"qconv2d rectangular {case} z_x={z_x}")
+    assert want.shape == (N, (H + 2 * ph - kh) // sh + 1, (W + 2 * pw - kw) // sw + 1, Cout)
+
+
+@pytest.mark.parametrize("case", [(2, 15, 22, 16, 3, 5, 1, 2, 1, 2), (1, 30, 9, 7, 1, 3, 2, 1, 0, 1), (2, 12, 12, 32, 3, 3, 2, 1, 1, 1),
+                                  (1, 20, 20, 8, 7, 7, 3, 3, 3, 3)], ids=lambda c: "x".join(map(str, c)))
+def test_qdwconv2d_rectangular_geometry_matches_oracle(case):
+    N, H, W, Cc, kh, kw, sh, sw, ph, pw = case
+    rng = np.random.default_rng(8100 + sum(case))
+    x = rng.integers(0, 256, (N, H, W, Cc)).astype(np.uint8)
+    w = rng.integers(-128, 128, (kh, kw, Cc)).astype(np.int8)
+    mult, shift = oracle.quantize_multipliers(10 ** rng.uniform(-3.6, -2.8, Cc) / np.sqrt(kh * kw / 9.0))
+    bias = rng.integers(-5000, 5000, Cc).astype(np.int32)
+    for z_x in (97, 0, 255):
+        want = oracle.qdwconv2d(x, z_x, w, (sh, sw), (ph, pw), mult, shift, 110, 0, 255, bias=bias)
+        got = host(qnn.qdwconv2d(dev(x), z_x, dev(w), (sh, sw), (ph, pw), dev(mult), dev(shift), 110, 0, 255, bias=dev(bias)))
+        assert_same(got, want, f"qdwconv2d rectangular {case} z_x={z_x}")
