@@ -64,10 +64,18 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t k, uint32_t d, uint32_t ma
     return d == 1 ? k : __umulhi(k, magic);
 }
 
+// XOR swizzle of the four 16-byte chunks of a 64-byte tile row.  A 16-byte LDS read serves the
+// 64 lanes in four cycles of 16 lanes, 256 bytes (64 banks) each, and the lanes that share a
+// cycle are {0-3, 12-15, 20-23, 24-27}, {4-11, 16-19, 28-31} and the same sets + 32 (measured).
+// A fragment read has lane = tile row (mod 32): within one such set row / 4 takes four values
+// whose low two bits differ, so XOR-ing the chunk index with (row / 4) % 4 gives every lane of
+// a cycle its own 16-byte bank group.
+__device__ __forceinline__ int lds_swizzle(int row) { return (row >> 2) & 3; }
+
 // swizzled byte offset of 16-byte chunk c (0..3) of a 64-byte tile row
 __device__ __forceinline__ int lds_chunk_offset(int row, int c)
 {
-    return row * 64 + (((c ^ (row >> 1) ^ (row >> 3)) & 3) << 4);
+    return row * 64 + (((c ^ lds_swizzle(row)) & 3) << 4);
 }
 
 template <int VEC> struct PieceLoader;

@@ -124,7 +124,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
         const int row = (wave * A_LOADS + j) * 16 + (lane >> 2);
-        a_koff[j] = (((lane & 3) ^ (row >> 1) ^ (row >> 3)) & 3) * 16;
+        a_koff[j] = (((lane & 3) ^ lds_swizzle(row)) & 3) * 16;
         int64_t m = m0 + row;
         m = m < g.M ? m : g.M - 1;
         a_hi0[j] = a_wi0[j] = 0;
@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
 #pragma unroll
     for (int j = 0; j < B_LOADS; ++j) {
         const int row = (wave * B_LOADS + j) * 16 + (lane >> 2);
-        const int b_koff = (((lane & 3) ^ (row >> 1) ^ (row >> 3)) & 3) * 16;
+        const int b_koff = (((lane & 3) ^ lds_swizzle(row)) & 3) * 16;
         int n = n0 + row;
         n = n < g.N ? n : g.N - 1;
         b_lane_off[j] = (uint32_t)((int64_t)(n - n0) * g.ldb) + (uint32_t)b_koff;
