@@ -163,6 +163,24 @@ static void release_workspace(hipStream_t s, bool capturing)
     if (hipEventRecord(w.done, s) == hipSuccess) w.used = true, w.last = s;
 }
 
+// One rectangle of the tile grid per XCD: pick the cut (8x1, 4x2, 2x4, 1x8) with the least operand
+// traffic from beyond the L2s (8/r copies of A's share + r copies of B's), among those that leave
+// the XCDs within 10 % of an even load; else (xcd_rows stays 0) bands of the linear tile sequence.
+static void choose_xcd_cut(const IgemmArgs &g, int tiles_m, int tiles_n, int64_t work, int &per_xcd, int &xcd_rows)
+{
+    static const int forced = std::getenv("QNN_XCD_ROWS") ? std::atoi(std::getenv("QNN_XCD_ROWS")) : -1;
+    double best = 0.0;
+    for (int r : {8, 4, 2, 1}) {
+        const int c = 8 / r;
+        if (forced >= 0 ? r != forced : false) continue;
+        if (tiles_m < r || tiles_n < c) continue;
+        const int64_t biggest = (int64_t)((tiles_m + r - 1) / r) * ((tiles_n + c - 1) / c);
+        if (forced < 0 && biggest * 8 * 10 > work * 11) continue;
+        const double traffic = (double)c * (double)g.M + (double)r * (double)g.N; // per unit of K
+        if (xcd_rows == 0 || traffic < best) best = traffic, xcd_rows = r, per_xcd = (int)biggest;
+    }
+}
+
 template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false, bool ZW = false>
 static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = SplitK{1, 0, nullptr})
 {
@@ -175,22 +193,7 @@ static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = Spli
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (g.N + BN - 1) / BN;
     const int64_t work = (int64_t)tiles_m * tiles_n * sk.splits;
     int per_xcd = (int)((work + 7) / 8), xcd_rows = 0;
-    if (!SPLIT) {
-        // one rectangle of the tile grid per XCD: pick the cut (8x1, 4x2, 2x4, 1x8) with the least
-        // operand traffic from beyond the L2s (8/r copies of A's share + r copies of B's), among those
-        // that leave the XCDs within 10 % of an even load; else bands of the linear tile sequence
-        static const int forced = std::getenv("QNN_XCD_ROWS") ? std::atoi(std::getenv("QNN_XCD_ROWS")) : -1;
-        double best = 0.0;
-        for (int r : {8, 4, 2, 1}) {
-            const int c = 8 / r;
-            if (forced >= 0 ? r != forced : false) continue;
-            if (tiles_m < r || tiles_n < c) continue;
-            const int64_t biggest = (int64_t)((tiles_m + r - 1) / r) * ((tiles_n + c - 1) / c);
-            if (forced < 0 && biggest * 8 * 10 > work * 11) continue;
-            const double traffic = (double)c * (double)g.M + (double)r * (double)g.N; // per unit of K
-            if (xcd_rows == 0 || traffic < best) best = traffic, xcd_rows = r, per_xcd = (int)biggest;
-        }
-    }
+    if (!SPLIT) choose_xcd_cut(g, tiles_m, tiles_n, work, per_xcd, xcd_rows);
     hipLaunchKernelGGL(kernel, dim3((unsigned)(per_xcd * 8)), dim3(WM * WN * 64), kLds, s, g, tiles_m, tiles_n, per_xcd,
                        xcd_rows, sk);
     hipError_t e = hipGetLastError();

@@ -55,6 +55,50 @@ struct SplitK {
     int32_t *partial; // device memory, splits * M * N int32
 };
 
+// Tile assignment: consecutive workgroup ids go round-robin over the 8 XCDs, each with
+// its own L2.  xcd_rows > 0: the tile grid is cut into xcd_rows x (8 / xcd_rows) rectangles,
+// one per XCD, so that an XCD fetches only 1/xcd_rows of A and xcd_rows/8 of B from beyond
+// its L2.  xcd_rows == 0: every XCD gets one contiguous band of the row-major tile sequence
+// (exact balance; used when the grid does not cut evenly, and with split-K).  Inside its
+// share an XCD walks groups of 4 tile rows column by column, so that tiles running at the
+// same time share A rows and B columns.  Returns false for a workgroup without a tile.
+template <bool SPLIT>
+__device__ __forceinline__ bool assign_tile(int tiles_m, int tiles_n, int per_xcd, int xcd_rows, int splits, int &tile_row,
+                                            int &tile_col, int &split)
+{
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    constexpr int GROUP = 4;
+    split = 0;
+    if (!SPLIT && xcd_rows > 0) {
+        const int xcd_cols = 8 / xcd_rows;
+        const int xr = xcd % xcd_rows, xc = xcd / xcd_rows;
+        const int row_lo = tiles_m * xr / xcd_rows, row_hi = tiles_m * (xr + 1) / xcd_rows;
+        const int col_lo = tiles_n * xc / xcd_cols, col_hi = tiles_n * (xc + 1) / xcd_cols;
+        const int rm = row_hi - row_lo, cn = col_hi - col_lo;
+        if (slot >= rm * cn) return false;
+        const int g_idx = slot / (GROUP * cn), in_group = slot - g_idx * GROUP * cn;
+        const int first_row = g_idx * GROUP;
+        const int rows_here = (rm - first_row) < GROUP ? (rm - first_row) : GROUP;
+        tile_row = row_lo + first_row + in_group % rows_here;
+        tile_col = col_lo + in_group / rows_here;
+    } else {
+        const int64_t tiles_total = (int64_t)tiles_m * tiles_n;
+        int64_t lin = (int64_t)xcd * per_xcd + slot;
+        if (slot >= per_xcd || lin >= tiles_total * (SPLIT ? splits : 1)) return false;
+        // split-K: the workgroups of one K range are neighbours (they share the A rows / B columns
+        // of that range in their XCD's L2)
+        split = SPLIT ? (int)(lin / tiles_total) : 0;
+        lin -= split * tiles_total;
+        const int64_t group_span = (int64_t)GROUP * tiles_n;
+        const int first_row = (int)(lin / group_span) * GROUP;
+        const int rows_here = (tiles_m - first_row) < GROUP ? (tiles_m - first_row) : GROUP;
+        const int in_group = (int)(lin % group_span);
+        tile_row = first_row + in_group % rows_here;
+        tile_col = in_group / rows_here;
+    }
+    return true;
+}
+
 template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false, bool ZW = false>
 __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs g, const int tiles_m, const int tiles_n,
                                                                 const int per_xcd, const int xcd_rows, const SplitK sk)
@@ -68,43 +112,8 @@ __global__ void __launch_bounds__(WM *WN * 64) igemm_dma_kernel(const IgemmArgs 
     constexpr int LOADS = A_LOADS + B_LOADS;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
-    // ---- tile assignment: consecutive workgroup ids go round-robin over the 8 XCDs, each with
-    // its own L2.  xcd_rows > 0: the tile grid is cut into xcd_rows x (8 / xcd_rows) rectangles,
-    // one per XCD, so that an XCD fetches only 1/xcd_rows of A and xcd_rows/8 of B from beyond
-    // its L2.  xcd_rows == 0: every XCD gets one contiguous band of the row-major tile sequence
-    // (exact balance; used when the grid does not cut evenly, and with split-K).  Inside its
-    // share an XCD walks groups of 4 tile rows column by column, so that tiles running at the
-    // same time share A rows and B columns.
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    constexpr int GROUP = 4;
-    int tile_row, tile_col, split = 0;
-    if (!SPLIT && xcd_rows > 0) {
-        const int xcd_cols = 8 / xcd_rows;
-        const int xr = xcd % xcd_rows, xc = xcd / xcd_rows;
-        const int row_lo = tiles_m * xr / xcd_rows, row_hi = tiles_m * (xr + 1) / xcd_rows;
-        const int col_lo = tiles_n * xc / xcd_cols, col_hi = tiles_n * (xc + 1) / xcd_cols;
-        const int rm = row_hi - row_lo, cn = col_hi - col_lo;
-        if (slot >= rm * cn) return;
-        const int g_idx = slot / (GROUP * cn), in_group = slot - g_idx * GROUP * cn;
-        const int first_row = g_idx * GROUP;
-        const int rows_here = (rm - first_row) < GROUP ? (rm - first_row) : GROUP;
-        tile_row = row_lo + first_row + in_group % rows_here;
-        tile_col = col_lo + in_group / rows_here;
-    } else {
-        const int64_t tiles_total = (int64_t)tiles_m * tiles_n;
-        int64_t lin = (int64_t)xcd * per_xcd + slot;
-        if (slot >= per_xcd || lin >= tiles_total * (SPLIT ? sk.splits : 1)) return;
-        // split-K: the workgroups of one K range are neighbours (they share the A rows / B columns
-        // of that range in their XCD's L2)
-        split = SPLIT ? (int)(lin / tiles_total) : 0;
-        lin -= split * tiles_total;
-        const int64_t group_span = (int64_t)GROUP * tiles_n;
-        const int first_row = (int)(lin / group_span) * GROUP;
-        const int rows_here = (tiles_m - first_row) < GROUP ? (tiles_m - first_row) : GROUP;
-        const int in_group = (int)(lin % group_span);
-        tile_row = first_row + in_group % rows_here;
-        tile_col = in_group / rows_here;
-    }
+    int tile_row, tile_col, split;
+    if (!assign_tile<SPLIT>(tiles_m, tiles_n, per_xcd, xcd_rows, sk.splits, tile_row, tile_col, split)) return;
     const int64_t m0 = (int64_t)tile_row * BM;
     const int n0 = tile_col * BN;
 
