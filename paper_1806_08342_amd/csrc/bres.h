@@ -212,7 +212,7 @@ __global__ void __launch_bounds__(512, 2) bres_kernel(const BResArgs s)
     };
 
     auto walk = [&](auto fused_tag) {
-        constexpr bool FUSED = decltype(fused_tag)::value;
+        constexpr bool FUSED = decltype(fused_tag)::value > 0, TIES = decltype(fused_tag)::value == 1; // 2: without the tie term
         const int chunks = (KS + KC - 1) / KC;
         i32x4 fa0[KC], fa1[KC], fa2[KC]; // the chunk being computed and the next two, in flight
         i32x16 acc[NB];
@@ -305,7 +305,7 @@ __global__ void __launch_bounds__(512, 2) bres_kernel(const BResArgs s)
                             const int32_t a = acc[j][4 * q + e];
                             if constexpr (FUSED) {
                                 const int32_t t = __mulhi((int32_t)((uint32_t)(a + c_corr[j]) << 2), c_mult[j]);
-                                const int32_t w = (int32_t)(((uint32_t)(t >> 31) << 1) + (uint32_t)t + (uint32_t)c_c[j]);
+                                const int32_t w = fused_w_from_t<TIES>(t, c_c[j]);
                                 x = shift_into_byte(x, med3_i32(w, c_lo[j], c_hi[j]), c_n1[j], e);
                             } else {
                                 const int32_t y = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(a + c_corr[j], rp)) + g.z_out;
@@ -331,8 +331,9 @@ __global__ void __launch_bounds__(512, 2) bres_kernel(const BResArgs s)
         }
         if (rb_stored >= 0) store_block(rb_stored);
     };
-    if (fused) walk(std::true_type{});
-    else walk(std::false_type{});
+    if (!fused) walk(std::integral_constant<int, 0>{});
+    else if (g.lo_rel < 0) walk(std::integral_constant<int, 1>{});
+    else walk(std::integral_constant<int, 2>{}); // act_min >= z_out: the clamp absorbs the tie term
 }
 
 } // namespace qnn

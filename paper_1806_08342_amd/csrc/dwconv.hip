@@ -305,11 +305,11 @@ __global__ void __launch_bounds__(256) dwconv3x3_dot_kernel(const DwArgs g)
 #pragma unroll
             for (int p = 0; p < RW; ++p) {
                 uint32_t packed = 0;
-                if constexpr (decltype(fused_tag)::value) {
+                if constexpr (decltype(fused_tag)::value > 0) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int32_t tt = __mulhi((int32_t)((uint32_t)acc[r][p][j] << 2), mu[j]);
-                        const int32_t w = (int32_t)(((uint32_t)(tt >> 31) << 1) + (uint32_t)tt + (uint32_t)cc[j]);
+                        const int32_t w = fused_w_from_t<decltype(fused_tag)::value == 1>(tt, cc[j]); // 2: without the tie term
                         packed = shift_into_byte(packed, med3_i32(w, lo[j], hi_[j]), n1[j], j);
                     }
                 } else {
@@ -323,8 +323,9 @@ __global__ void __launch_bounds__(256) dwconv3x3_dot_kernel(const DwArgs g)
             }
         }
     };
-    if (fused) finish(std::true_type{});
-    else finish(std::false_type{});
+    if (!fused) finish(std::integral_constant<int, 0>{});
+    else if (g.lo_rel < 0) finish(std::integral_constant<int, 1>{});
+    else finish(std::integral_constant<int, 2>{}); // act_min >= z_out: the clamp absorbs the tie term
 }
 
 // any kernel size / stride / channel count: one lane per output element

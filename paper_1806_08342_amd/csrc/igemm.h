@@ -300,11 +300,18 @@ __device__ __forceinline__ void igemm_epilogue_impl(const IgemmArgs &g, i32x16 (
     auto pack_values = [&](const int32_t (&y)[4]) {
         return (uint32_t)y[0] | ((uint32_t)y[1] << 8) | ((uint32_t)y[2] << 16) | ((uint32_t)y[3] << 24);
     };
-    if (fused) {
+    if (fused && g.lo_rel >= 0) { // act_min >= z_out: the clamp absorbs the tie term
         run([&](const int32_t (&a)[4], int j) {
             uint32_t x = 0;
 #pragma clang loop unroll(full)
-            for (int e = 0; e < 4; ++e) x = shift_into_byte(x, rescale_fused_w(a[e], fr[j]), fr[j].n1, e);
+            for (int e = 0; e < 4; ++e) x = shift_into_byte(x, rescale_fused_w<false>(a[e], fr[j]), fr[j].n1, e);
+            return x;
+        });
+    } else if (fused) {
+        run([&](const int32_t (&a)[4], int j) {
+            uint32_t x = 0;
+#pragma clang loop unroll(full)
+            for (int e = 0; e < 4; ++e) x = shift_into_byte(x, rescale_fused_w<true>(a[e], fr[j]), fr[j].n1, e);
             return x;
         });
     } else if (fast) {

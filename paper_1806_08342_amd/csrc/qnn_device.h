@@ -96,14 +96,23 @@ __device__ __forceinline__ FusedRescale make_fused(int32_t mult, int32_t shift, 
     return f;
 }
 
+// w of the comment above from T.  TIES = false drops the term 2s (two instructions fewer).  That
+// is exact whenever act_min >= z_out (every ReLU-like output range): the term only acts for T < 0,
+// where both T + c and T - 2 + c stay below (z_out + 1) << (n+1) <= (act_min + 1) << (n+1), so
+// after the clamp from below the shifted result is act_min either way.
+template <bool TIES> __device__ __forceinline__ int32_t fused_w_from_t(int32_t t, int32_t c)
+{
+    if constexpr (TIES) return (int32_t)(((uint32_t)(t >> 31) << 1) + (uint32_t)t + (uint32_t)c);
+    else return (int32_t)((uint32_t)t + (uint32_t)c);
+}
+
 // w of the comment above, clamped; the caller shifts it right by n1
 __device__ __forceinline__ int32_t med3_i32(int32_t v, int32_t lo, int32_t hi);
-__device__ __forceinline__ int32_t rescale_fused_w(int32_t acc, const FusedRescale &p)
+template <bool TIES = true> __device__ __forceinline__ int32_t rescale_fused_w(int32_t acc, const FusedRescale &p)
 {
     const int32_t a4 = (int32_t)(((uint32_t)acc << 2) + (uint32_t)p.corr4);
     const int32_t t = __mulhi(a4, p.mult);
-    const int32_t w = (int32_t)(((uint32_t)(t >> 31) << 1) + (uint32_t)t + (uint32_t)p.c);
-    return med3_i32(w, p.lo, p.hi);
+    return med3_i32(fused_w_from_t<TIES>(t, p.c), p.lo, p.hi);
 }
 
 // complete value (already clamped to [act_min, act_max])

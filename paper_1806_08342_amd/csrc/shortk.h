@@ -284,8 +284,8 @@ __global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 
 
     // the row loop exists twice (fast and general epilogue) and the choice is made once, outside:
     // inside the loop the compiler would evaluate both forms for every output and select
-    auto walk = [&](auto fused_tag) {
-    constexpr bool FUSED = decltype(fused_tag)::value;
+    auto walk = [&](auto mode_tag) { // 0: general rescale, 1: fused form, 2: fused form without the tie term
+    constexpr bool FUSED = decltype(mode_tag)::value > 0, TIES = decltype(mode_tag)::value == 1;
     i32x4 fa[KS];
     int rb = walker, rb_stored = -1;
     if (rb < row_blocks) load_rows(rb, fa);
@@ -329,8 +329,7 @@ __global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 
                         int32_t a = acc[j][4 * q + e];
                         if (INT4) a >>= 4;
                         const int32_t t = __mulhi((int32_t)((uint32_t)(a + col[j].corr) << 2), col[j].mult);
-                        const int32_t w = (int32_t)(((uint32_t)(t >> 31) << 1) + (uint32_t)t + (uint32_t)col[j].c);
-                        x = shift_into_byte(x, med3_i32(w, col[j].lo, col[j].hi), col[j].n1, e);
+                        x = shift_into_byte(x, med3_i32(fused_w_from_t<TIES>(t, col[j].c), col[j].lo, col[j].hi), col[j].n1, e);
                     }
                     put(j, q, x);
                 }
@@ -364,8 +363,9 @@ __global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 
     }
     if (rb_stored >= 0) store_block(rb_stored);
     };
-    if (fused) walk(std::true_type{});
-    else walk(std::false_type{});
+    if (!fused) walk(std::integral_constant<int, 0>{});
+    else if (g.lo_rel < 0) walk(std::integral_constant<int, 1>{});
+    else walk(std::integral_constant<int, 2>{}); // act_min >= z_out: the clamp absorbs the tie term
 }
 
 } // namespace qnn

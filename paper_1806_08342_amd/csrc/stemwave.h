@@ -194,7 +194,7 @@ __global__ void __launch_bounds__(256) stemwave_kernel(const StemWaveArgs s)
     };
 
     auto walk = [&](auto fused_tag) {
-        constexpr bool FUSED = decltype(fused_tag)::value;
+        constexpr bool FUSED = decltype(fused_tag)::value > 0, TIES = decltype(fused_tag)::value == 1; // 2: without the tie term
         // the first output row of the segment needs all KH image rows; afterwards NEW new ones
         uint32_t fresh[NEW];
         {
@@ -264,7 +264,7 @@ __global__ void __launch_bounds__(256) stemwave_kernel(const StemWaveArgs s)
                         const int32_t a = acc[j][4 * q + e];
                         if constexpr (FUSED) {
                             const int32_t t = __mulhi((int32_t)((uint32_t)(a + c_corr[j]) << 2), c_mult[j]);
-                            const int32_t wv = (int32_t)(((uint32_t)(t >> 31) << 1) + (uint32_t)t + (uint32_t)c_c[j]);
+                            const int32_t wv = fused_w_from_t<TIES>(t, c_c[j]);
                             x = shift_into_byte(x, med3_i32(wv, c_lo[j], c_hi[j]), c_n1[j], e);
                         } else {
                             const int32_t y = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(a + c_corr[j], rp)) + g.z_out;
@@ -279,8 +279,9 @@ __global__ void __launch_bounds__(256) stemwave_kernel(const StemWaveArgs s)
         }
         if (ho_stored >= 0) store_row(ho_stored);
     };
-    if (fused) walk(std::true_type{});
-    else walk(std::false_type{});
+    if (!fused) walk(std::integral_constant<int, 0>{});
+    else if (g.lo_rel < 0) walk(std::integral_constant<int, 1>{});
+    else walk(std::integral_constant<int, 2>{}); // act_min >= z_out: the clamp absorbs the tie term
 }
 
 } // namespace qnn

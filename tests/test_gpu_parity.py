@@ -720,3 +720,47 @@ def test_qdwconv2d_rectangular_geometry_matches_oracle(case):
         want = oracle.qdwconv2d(x, z_x, w, (sh, sw), (ph, pw), mult, shift, 110, 0, 255, bias=bias)
         got = host(qnn.qdwconv2d(dev(x), z_x, dev(w), (sh, sw), (ph, pw), dev(mult), dev(shift), 110, 0, 255, bias=dev(bias)))
         assert_same(got, want, f"qdwconv2d rectangular {case} z_x={z_x}")
+
+
+# ------------------------------------------------------------------ exact ties below the lower clamp
+
+@pytest.mark.parametrize("z_out,act_min,act_max", [(0, 0, 255), (7, 7, 130), (3, 10, 200), (40, 0, 255), (128, 5, 250)])
+def test_rounding_ties_next_to_the_lower_clamp(monkeypatch, z_out, act_min, act_max):
+    """Small accumulators with multipliers 2^30 and 3 * 2^29 and shifts 1..4: every second or fourth
+    sum is an exact tie, negative ones included.  With act_min >= z_out the kernels drop the
+    ties-away term for negative values (the clamp decides there); the result must not change."""
+    rng = np.random.default_rng(977 + z_out + act_min)
+    z_a = 77
+    for M, N, K, tile in [(200, 48, 16, None), (300, 130, 64, None), (256, 128, 64, "dma128x128"), (130, 70, 64, "64x64"),
+                          (4096, 64, 288, None), (32768, 64, 288, None)]:
+        A = (z_a + rng.integers(-1, 2, (M, K))).astype(np.uint8)
+        Bt = rng.integers(-1, 2, (N, K)).astype(np.int8)
+        bias = rng.integers(-24, 25, N).astype(np.int32)
+        mult = np.where(rng.integers(0, 2, N) == 0, 1 << 30, 3 << 29).astype(np.int32)
+        shift = rng.integers(1, 5, N).astype(np.int32)
+        if tile:
+            monkeypatch.setenv("QNN_FORCE_TILE", tile)
+        else:
+            monkeypatch.delenv("QNN_FORCE_TILE", raising=False)
+        want = oracle.qgemm(A, z_a, Bt, mult, shift, z_out, act_min, act_max, bias=bias)
+        got = host(qnn.qgemm(dev(A), z_a, dev(Bt), dev(mult), dev(shift), z_out, act_min, act_max, bias=dev(bias)))
+        assert_same(got, want, f"ties {M}x{N}x{K} tile={tile} z_out={z_out} act=[{act_min},{act_max}] ({qnn.qgemm_plan(M, N, K)})")
+    monkeypatch.delenv("QNN_FORCE_TILE", raising=False)
+    # depthwise 3x3 and a stem-shaped convolution
+    C = 32
+    x = (z_a + rng.integers(-1, 2, (2, 12, 12, C))).astype(np.uint8)
+    w = rng.integers(-1, 2, (3, 3, C)).astype(np.int8)
+    bias = rng.integers(-8, 9, C).astype(np.int32)
+    mult = np.where(rng.integers(0, 2, C) == 0, 1 << 30, 3 << 29).astype(np.int32)
+    shift = rng.integers(1, 4, C).astype(np.int32)
+    want = oracle.qdwconv2d(x, z_a, w, (1, 1), (1, 1), mult, shift, z_out, act_min, act_max, bias=bias)
+    got = host(qnn.qdwconv2d(dev(x), z_a, dev(w), (1, 1), (1, 1), dev(mult), dev(shift), z_out, act_min, act_max, bias=dev(bias)))
+    assert_same(got, want, f"ties depthwise z_out={z_out} act=[{act_min},{act_max}]")
+    xs = (z_a + rng.integers(-1, 2, (2, 20, 20, 3))).astype(np.uint8)
+    ws = rng.integers(-1, 2, (32, 3, 3, 3)).astype(np.int8)
+    bias = rng.integers(-12, 13, 32).astype(np.int32)
+    mult = np.where(rng.integers(0, 2, 32) == 0, 1 << 30, 3 << 29).astype(np.int32)
+    shift = rng.integers(1, 4, 32).astype(np.int32)
+    want = oracle.qconv2d(xs, z_a, ws, (2, 2), (1, 1), mult, shift, z_out, act_min, act_max, bias=bias)
+    got = host(qnn.qconv2d(dev(xs), z_a, dev(ws), (2, 2), (1, 1), dev(mult), dev(shift), z_out, act_min, act_max, bias=dev(bias)))
+    assert_same(got, want, f"ties stem conv z_out={z_out} act=[{act_min},{act_max}]")
