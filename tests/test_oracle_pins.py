@@ -411,6 +411,47 @@ def test_depthwise_matches_per_channel_library_cross_correlation():
     assert (ys == y.ravel()[sample]).all()
 
 
+def test_depthwise_with_weight_zero_points_matches_cross_correlation_of_shifted_operands():
+    # eq. 4 with groups = channels: every channel is a 2-D cross-correlation of (x - z_x) with
+    # (w - z_w[c]); taps outside the image contribute nothing.  The rescale (mult = 2^30, shift = 11)
+    # is a division by 2 rounded to nearest with ties toward +inf followed by a division by 2048
+    # rounded to nearest with ties away from zero, both written out here with integers
+    rng = np.random.default_rng(181)
+    N, H, W, Cc = 2, 8, 11, 6
+    x = rng.integers(0, 256, (N, H, W, Cc)).astype(np.uint8)
+    w = rng.integers(-128, 128, (3, 3, Cc)).astype(np.int8)
+    z_w = np.array([-128, -7, 0, 5, 90, 127], dtype=np.int32)
+    z_x = 201
+    bias = rng.integers(-3000, 3000, Cc).astype(np.int32)
+    mult = np.full(Cc, 2 ** 30, np.int32)
+    shift = np.full(Cc, 11, np.int32)
+    for stride, pad in (((1, 1), (1, 1)), ((2, 2), (1, 1)), ((1, 2), (1, 1))):
+        y = oracle.qdwconv2d(x, z_x, w, stride, pad, mult, shift, 100, 0, 255, bias=bias, z_w=z_w)
+        clamped = 0
+        for n in range(N):
+            for c in range(Cc):
+                full = correlate2d(x[n, :, :, c].astype(np.int64) - z_x, w[:, :, c].astype(np.int64) - int(z_w[c]),
+                                   mode="same")
+                acc = full[:: stride[0], :: stride[1]] + int(bias[c])
+                want = np.empty(acc.shape, dtype=np.int64)
+                for idx in np.ndindex(*acc.shape):
+                    h = Fraction(int(acc[idx]), 2)
+                    h = int(h) if h.denominator == 1 else int(np.floor(float(h) + 0.5))  # stage 1: ties toward +inf
+                    q, r = divmod(abs(h), 2048)  # stage 2: ties away from zero
+                    r2 = q + (1 if r >= 1024 else 0)
+                    want[idx] = min(255, max(0, (r2 if h >= 0 else -r2) + 100))
+                assert (y[n, :, :, c] == want).all(), (stride, n, c)
+                clamped += int(((want == 0) | (want == 255)).sum())
+        assert clamped < 0.9 * y.size  # the comparison is not vacuous
+    # z_w = 0 given explicitly equals the symmetric path, and the sampled form agrees with the dense one
+    y0 = oracle.qdwconv2d(x, z_x, w, (1, 1), (1, 1), mult, shift, 100, 0, 255, bias=bias)
+    yz = oracle.qdwconv2d(x, z_x, w, (1, 1), (1, 1), mult, shift, 100, 0, 255, bias=bias, z_w=np.zeros(Cc, np.int32))
+    assert (y0 == yz).all()
+    sample = rng.integers(0, y.size, 60)
+    ys = oracle.qdwconv2d(x, z_x, w, (1, 2), (1, 1), mult, shift, 100, 0, 255, bias=bias, z_w=z_w, sample=sample)
+    assert (ys == y.ravel()[sample]).all()
+
+
 def test_whole_layer_against_float_convolution():
     # quantize -> integer conv + ReLU6 -> dequantize tracks the float layer within the error
     # budget: one output LSB plus the propagated input / weight rounding errors
