@@ -13,16 +13,19 @@
  *   - Pointers marked DEVICE are HIP device pointers owned by the caller
  *     (for example the storage of a torch tensor).  Pointers marked HOST are
  *     ordinary host pointers.  The library never allocates, frees or keeps
- *     any of them.
- *   - Scratch memory: qnn_qgemm and qnn_qconv2d may use one library-owned
- *     64 MiB device block per GPU (partial sums of products whose K is divided
- *     over several workgroups; int8 copy of 4-bit weights).  It is allocated
- *     with hipMalloc at the first call that needs it, never while `stream` is
- *     being captured into a graph (such a call takes a route without scratch),
- *     and kept until the process ends.  Eager calls on different streams that
- *     use the block are ordered by the library with an event; captured graphs
- *     that use it must not be replayed concurrently with each other or with
- *     such calls.
+ *     any of them, and never allocates device memory of its own.
+ *   - Scratch memory comes from the caller: the dense entry points take
+ *     `workspace` (DEVICE, 16-byte aligned, may be NULL) and `workspace_bytes`.
+ *     qnn_qgemm_workspace_bytes / qnn_qconv2d_workspace_bytes say how much a
+ *     shape can use (0 for most): the int32 partial sums of products whose K
+ *     is divided over several workgroups because they have too few output
+ *     tiles for the chip, and the activation row sums of the asymmetric-weight
+ *     entry points.  With a smaller or NULL workspace the symmetric entry
+ *     points take a route that needs none (same result, possibly slower); the
+ *     asymmetric ones return QNN_EINVAL.  The workspace is written and read by
+ *     the kernels of that one call only; its contents need no initialisation
+ *     and mean nothing afterwards.  Calls that may run concurrently (different
+ *     streams, graph branches) need workspaces that do not overlap.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Device entry points only enqueue work on that stream and return; they
  *     never synchronise.  Output buffers must not overlap input buffers.
@@ -108,11 +111,28 @@ qnn_status qnn_requantize(const int32_t *acc, uint8_t *y, size_t rows, size_t ch
  *    QNN_B_COLUMNS_CONTIGUOUS is the fast layout; QNN_B_ROWS_CONTIGUOUS is accepted for int8
  *    and runs a slower gather path (use qnn_pack_b once, weights being constant at inference).
  * bias: DEVICE int32[N] or NULL (scale s_a * Delta_n, zero-point 0); mult, shift: DEVICE int32[N].
- * C: DEVICE uint8, M x N row-major, row pitch ldc >= N (written). */
+ * C: DEVICE uint8, M x N row-major, row pitch ldc >= N (written).
+ * workspace: DEVICE scratch of workspace_bytes bytes or NULL (see the general rules). */
 qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
                      int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
                      const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
-                     void *stream);
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scratch bytes that qnn_qgemm / qnn_qgemm_add (asym == 0) or qnn_qgemm_asym (asym != 0) can use for an
+ * M x N x K product with weight_bits-bit weights, and the same for the convolution entry points
+ * (Sec. 2.1 eq. 4-6: the partial sums are pieces of the same integer sum, so the result does not
+ * depend on whether they are used).  Host-only; 0 when the shape needs none. */
+size_t qnn_qgemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int weight_bits, int asym);
+size_t qnn_qconv2d_workspace_bytes(int N, int H, int W, int Cin, int Cout, int kh, int kw, int weight_bits, int stride_h,
+                                   int stride_w, int pad_h, int pad_w, int asym);
+
+/* Tuning switch `name` ("QNN_FORCE_TILE", "QNN_FORCE_SPLIT", "QNN_NO_SHORTK", "QNN_BRES", "QNN_STEM_BLOCK",
+ * "QNN_XCD_ROWS", "QNN_DW_RH", "QNN_DW_MAD", "QNN_GEMM_PRIO", "QNN_PERSIST", "QNN_DW_VARIANT") set to the
+ * HOST string `value`, or back to its default with value == NULL.  The switches start from the
+ * environment variables of the same names, read once when the library is first used; they select among
+ * kernels that give identical results (the parity tests use them to reach every variant on small shapes).
+ * Not synchronised: change them only while no other thread is inside a library call. */
+qnn_status qnn_tuning_set(const char *name, const char *value);
 
 /* Name of the kernel configuration (a tile "<BM>x<BN>", with "/k<n>" when K is divided over n
  * workgroups per tile, or "shortk" / "skinny16") that qnn_qgemm and the convolution entry points
@@ -140,7 +160,7 @@ qnn_status qnn_pack_b(const int8_t *src, int64_t ld_src, int64_t K, int64_t N, i
 qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
                        int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias,
                        const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
-                       uint8_t *y, void *stream);
+                       uint8_t *y, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Depthwise convolution (one kh x kw kernel per channel; the separable layers of the
  * MobileNet family the paper evaluates), same arithmetic as qnn_qconv2d per channel:
@@ -195,13 +215,14 @@ typedef struct qnn_add_params {
 qnn_status qnn_qgemm_add(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
                          int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
                          const int32_t *shift, int32_t z_mid, int32_t mid_min, int32_t mid_max, const uint8_t *residual,
-                         int64_t ldr, const qnn_add_params *add, uint8_t *C, int64_t ldc, void *stream);
+                         int64_t ldr, const qnn_add_params *add, uint8_t *C, int64_t ldc, void *workspace,
+                         size_t workspace_bytes, void *stream);
 
 qnn_status qnn_qconv2d_add(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
                            int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w,
                            const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_mid,
                            int32_t mid_min, int32_t mid_max, const uint8_t *residual, const qnn_add_params *add,
-                           uint8_t *y, void *stream);
+                           uint8_t *y, void *workspace, size_t workspace_bytes, void *stream);
 
 /* The same layers with asymmetric per-channel weights: column / output channel n carries its own
  * zero-point z_w[n] (Sec. 2.1 affine quantizer at the per-channel granularity of Sec. 2.6; the scheme the
@@ -210,20 +231,21 @@ qnn_status qnn_qconv2d_add(const uint8_t *x, int N, int H, int W, int Cin, int32
  * = sum_k A*B - z_a * sum_k B[k][n] - z_w[n] * sum_k A[m][k] + K * z_a * z_w[n]        (eq. 5-6)
  * The activation sums of the third term are shared by all channels: one extra pass over A forms
  * them per output row (for a convolution: over the taps inside the image; padding holds the code
- * z_x and adds nothing), into the library's scratch block (see above; QNN_EUNSUPPORTED if the block
- * cannot be had, e.g. first use during stream capture, or M > 8 Mi rows).
+ * z_x and adds nothing), into the caller's workspace (required here: QNN_EINVAL when it is NULL,
+ * misaligned or smaller than the workspace query says).
  * z_w: DEVICE int32[N] (resp. [Cout]), each in [-128, 127] for 8-bit and [-8, 7] for 4-bit weights.
  * K (resp. kh*kw*Cin) <= 32768, which keeps |sum| below 2^31.  Everything else as in qnn_qgemm /
  * qnn_qconv2d. */
 qnn_status qnn_qgemm_asym(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
                           int weight_bits, const int32_t *z_w, int64_t M, int64_t N, int64_t K, const int32_t *bias,
                           const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
-                          uint8_t *C, int64_t ldc, void *stream);
+                          uint8_t *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream);
 
 qnn_status qnn_qconv2d_asym(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
                             int kw, int weight_bits, const int32_t *z_w, int stride_h, int stride_w, int pad_h, int pad_w,
                             const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_out,
-                            int32_t act_min, int32_t act_max, uint8_t *y, void *stream);
+                            int32_t act_min, int32_t act_max, uint8_t *y, void *workspace, size_t workspace_bytes,
+                            void *stream);
 
 /* Quantizer parameters from the data, on the device (Sec. 2.5: activation ranges are the minimum and
  * maximum of the tensor, or their moving average across batches; Sec. 2.1 turns a range into scale
@@ -268,6 +290,17 @@ qnn_status qnn_qdwconv2d_asym(const uint8_t *x, int N, int H, int W, int C, int3
                               const int32_t *z_w, int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias,
                               const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
                               uint8_t *y, void *stream);
+
+/* Calibration of the machine for the benchmark (not part of the inference path).
+ * qnn_calibrate_mfma: `workgroups` workgroups of 8 waves each issue iters x 4 independent
+ *   v_mfma_i32_32x32x32_i8 from registers only (random_operands != 0: a different pseudo-random
+ *   byte pattern in every operand register; 0: all bytes equal); *ops (HOST) receives the number of
+ *   integer operations the launch performs (2 per multiply-accumulate).  sink: DEVICE int32
+ *   [workgroups * 512] (written).
+ * qnn_calibrate_copy: dst[0..bytes) = src[0..bytes), 16 bytes per lane and access; bytes % 16 == 0,
+ *   both DEVICE pointers 16-byte aligned. */
+qnn_status qnn_calibrate_mfma(int workgroups, int iters, int random_operands, int32_t *sink, double *ops, void *stream);
+qnn_status qnn_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 /* ------------------------------------------------------------------ host-only helpers */
 

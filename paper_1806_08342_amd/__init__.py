@@ -6,6 +6,8 @@ library's own kernels.  Importing the package does not load the library; the fir
 does, and fails loudly when it has not been built.
 """
 from .binding import (  # noqa: F401
+    calibrate_copy,
+    calibrate_mfma,
     QnnError,
     act_range,
     choose_qparams,
@@ -22,12 +24,14 @@ from .binding import (  # noqa: F401
     qconv2d,
     qconv2d_add,
     qconv2d_asym,
+    qconv2d_workspace_bytes,
     qdwconv2d,
     qdwconv2d_asym,
     qgemm,
     qgemm_add,
     qgemm_asym,
     qgemm_plan,
+    qgemm_workspace_bytes,
     quantize,
     quantize_dynamic,
     quantize_with,
@@ -39,10 +43,11 @@ from .binding import (  # noqa: F401
     quantize_weights,
     requantize,
     rescale_u8,
+    tuning_set,
 )
 
 __all__ = [
     "QnnError", "act_range", "choose_qparams", "dequantize", "library_path", "load_library", "minmax", "new_range_state", "pack_b", "pack_int4", "prepare_qgemm",
     "qadd", "qadd_params", "qconv2d", "qconv2d_add", "qconv2d_asym", "qdwconv2d", "qdwconv2d_asym", "qgemm", "qgemm_add", "qgemm_asym", "qgemm_plan", "quantize", "quantize_dynamic", "quantize_with", "read_range_state", "simquant", "simquant_backward", "quantize_multiplier",
-    "quantize_multipliers", "quantize_weights", "requantize", "rescale_u8",
+    "quantize_multipliers", "quantize_weights", "requantize", "rescale_u8", "qgemm_workspace_bytes", "qconv2d_workspace_bytes", "tuning_set", "calibrate_copy", "calibrate_mfma",
 ]

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqnn.so")
 SOURCES = ["host_helpers.hip", "elementwise.hip", "igemm.hip", "igemm_tiles.hip", "igemm_shortk.hip", "igemm_bres.hip",
-           "igemm_stem.hip", "igemm_rowsum.hip", "dwconv.hip"]
+           "igemm_stem.hip", "igemm_rowsum.hip", "dwconv.hip", "calibrate.hip"]
 FLAGS = [
     "-O3",
     "--offload-arch=gfx950",

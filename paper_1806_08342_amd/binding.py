@@ -22,7 +22,8 @@ EXPORTS = [
     "qnn_last_error", "qnn_version", "qnn_qgemm_plan", "qnn_quantize", "qnn_dequantize", "qnn_requantize", "qnn_qgemm", "qnn_pack_b",
     "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_rescale_u8", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_qdwconv2d_asym", "qnn_minmax", "qnn_quantize_with",
     "qnn_quantize_dynamic", "qnn_simquant", "qnn_simquant_backward", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
-    "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4",
+    "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4", "qnn_qgemm_workspace_bytes", "qnn_qconv2d_workspace_bytes",
+    "qnn_tuning_set", "qnn_calibrate_mfma", "qnn_calibrate_copy",
 ]
 
 
@@ -56,21 +57,26 @@ def load_library():
         "qnn_quantize": [vp, vp, sz, f32, i32, i32, i32, vp],
         "qnn_dequantize": [vp, vp, sz, f32, i32, vp],
         "qnn_requantize": [vp, vp, sz, sz, vp, vp, ci, i32, i32, i32, vp],
-        "qnn_qgemm": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
+        "qnn_qgemm": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, sz, vp],
         "qnn_pack_b": [vp, i64, i64, i64, vp, i64, vp],
-        "qnn_qconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
+        "qnn_qconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp],
+        "qnn_tuning_set": [C.c_char_p, C.c_char_p],
+        "qnn_calibrate_mfma": [ci, ci, ci, vp, C.POINTER(f64), vp],
+        "qnn_calibrate_copy": [vp, vp, sz, vp],
         "qnn_minmax": [vp, sz, f32, ci, vp, vp],
         "qnn_quantize_with": [vp, vp, sz, vp, vp],
         "qnn_quantize_dynamic": [vp, vp, sz, vp, vp],
         "qnn_simquant": [vp, vp, sz, f32, i32, i32, i32, vp],
         "qnn_simquant_backward": [vp, vp, vp, sz, f32, i32, i32, i32, vp],
         "qnn_qdwconv2d_asym": [vp, ci, ci, ci, ci, i32, vp, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
-        "qnn_qgemm_asym": [vp, i64, i32, vp, i64, ci, ci, vp, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
-        "qnn_qconv2d_asym": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
+        "qnn_qgemm_asym": [vp, i64, i32, vp, i64, ci, ci, vp, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, sz, vp],
+        "qnn_qconv2d_asym": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, vp, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp,
+                             sz, vp],
         "qnn_rescale_u8": [vp, i64, i32, i32, i32, i32, i32, i32, vp, i64, i64, i64, vp],
-        "qnn_qgemm_add": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, vp, i64, vp],
+        "qnn_qgemm_add": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, vp, i64, vp,
+                          sz, vp],
         "qnn_qconv2d_add": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp,
-                            vp, vp],
+                            vp, vp, sz, vp],
         "qnn_qdwconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp],
         "qnn_qadd": [vp, i32, i32, i32, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp],
         "qnn_choose_qparams": [f64, f64, ci, C.POINTER(f32), C.POINTER(i32)],
@@ -84,6 +90,10 @@ def load_library():
         fn = getattr(lib, name)
         fn.argtypes = args
         fn.restype = C.c_int
+    lib.qnn_qgemm_workspace_bytes.restype = sz
+    lib.qnn_qgemm_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
+    lib.qnn_qconv2d_workspace_bytes.restype = sz
+    lib.qnn_qconv2d_workspace_bytes.argtypes = [ci] * 13
     _lib = lib
     return lib
 
@@ -122,6 +132,65 @@ def _dev_rows(t, dtype, name):
             (t.shape[1] == 1 or t.stride(1) == 1) and (t.shape[0] == 1 or t.stride(0) >= t.shape[1])):
         raise TypeError(f"{name}: expected a 2-D device tensor of {dtype} with contiguous rows")
     return C.c_void_p(t.data_ptr()), (t.stride(0) if t.shape[0] > 1 else t.shape[1])
+
+
+def _out(out, shape, device, name="out"):
+    """The output tensor: a new uint8 tensor of `shape`, or the caller's `out` after a shape check (the
+    kernels write shape-many elements through its pointer)."""
+    torch = _torch()
+    if out is None:
+        return torch.empty(shape, dtype=torch.uint8, device=device)
+    if tuple(out.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(out.shape)}, expected {tuple(shape)}")
+    return out
+
+
+def _workspace(nbytes, device, workspace):
+    """(pointer, size) of the scratch memory of a dense call: the caller's uint8 tensor, else a fresh
+    one of the size the library asks for (none when that is 0).  The tensor is returned too, so that it
+    stays referenced until the call has been enqueued (torch frees memory in stream order)."""
+    torch = _torch()
+    if workspace is not None:
+        if not (isinstance(workspace, torch.Tensor) and workspace.is_cuda and workspace.dtype == torch.uint8 and
+                workspace.is_contiguous()):
+            raise TypeError("workspace: expected a contiguous uint8 device tensor")
+        return C.c_void_p(workspace.data_ptr()), workspace.numel(), workspace
+    if nbytes == 0:
+        return None, 0, None
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return C.c_void_p(ws.data_ptr()), nbytes, ws
+
+
+def qgemm_workspace_bytes(M, N, K, weight_bits=8, asym=False):
+    return int(load_library().qnn_qgemm_workspace_bytes(int(M), int(N), int(K), int(weight_bits), int(bool(asym))))
+
+
+def qconv2d_workspace_bytes(N, H, W, Cin, Cout, kh, kw, stride, pad, weight_bits=8, asym=False):
+    return int(load_library().qnn_qconv2d_workspace_bytes(int(N), int(H), int(W), int(Cin), int(Cout), int(kh), int(kw),
+                                                          int(weight_bits), stride[0], stride[1], pad[0], pad[1],
+                                                          int(bool(asym))))
+
+
+def calibrate_mfma(workgroups, iters, random_operands, sink):
+    """Enqueue the register-only MFMA loop; returns the integer operations of the launch."""
+    torch = _torch()
+    ops = C.c_double()
+    _check("qnn_calibrate_mfma", load_library().qnn_calibrate_mfma(int(workgroups), int(iters), int(bool(random_operands)),
+                                                                   _dev(sink, torch.int32, "sink"), C.byref(ops), _stream()))
+    return float(ops.value)
+
+
+def calibrate_copy(src, dst):
+    torch = _torch()
+    _check("qnn_calibrate_copy", load_library().qnn_calibrate_copy(_dev(src, torch.uint8, "src"), _dev(dst, torch.uint8, "dst"),
+                                                                   src.numel(), _stream()))
+    return dst
+
+
+def tuning_set(name, value=None):
+    """Set a tuning switch of the library (see qnn_tuning_set); value None restores the default."""
+    v = None if value is None else str(value).encode()
+    _check("qnn_tuning_set", load_library().qnn_tuning_set(name.encode(), v))
 
 
 # ------------------------------------------------------------------ host helpers
@@ -185,7 +254,7 @@ def qgemm_plan(M, N, K):
 
 def quantize(x, scale, zero_point, qmin=0, qmax=255, out=None):
     torch = _torch()
-    q = torch.empty(x.shape, dtype=torch.uint8, device=x.device) if out is None else out
+    q = _out(out, x.shape, x.device)
     _check("qnn_quantize", load_library().qnn_quantize(_dev(x, torch.float32, "x"), _dev(q, torch.uint8, "q"),
                                                       x.numel(), scale, zero_point, qmin, qmax, _stream()))
     return q
@@ -202,7 +271,7 @@ def dequantize(q, scale, zero_point, out=None):
 def requantize(acc, mult, shift, per_channel, z_out, act_min, act_max, out=None):
     torch = _torch()
     rows, ch = acc.shape
-    y = torch.empty((rows, ch), dtype=torch.uint8, device=acc.device) if out is None else out
+    y = _out(out, (rows, ch), acc.device)
     _check("qnn_requantize", load_library().qnn_requantize(
         _dev(acc, torch.int32, "acc"), _dev(y, torch.uint8, "y"), rows, ch, _dev(mult, torch.int32, "mult"),
         _dev(shift, torch.int32, "shift"), int(bool(per_channel)), z_out, act_min, act_max, _stream()))
@@ -210,7 +279,7 @@ def requantize(acc, mult, shift, per_channel, z_out, act_min, act_max, out=None)
 
 
 def qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8,
-          b_layout=B_COLUMNS_CONTIGUOUS, out=None):
+          b_layout=B_COLUMNS_CONTIGUOUS, out=None, workspace=None):
     """A: uint8 [M,K] (rows may be spaced apart: a column slice of a wider matrix; same for `out`).  B: int8 [N,K] (columns contiguous), int8 [K,N] (rows contiguous), or uint8
     [N,K/2] nibble-packed when weight_bits == 4.  Returns uint8 [M,N]."""
     torch = _torch()
@@ -224,18 +293,19 @@ def qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, bias=None, weight_bit
     else:
         ldb = N = B.shape[1]
         bp = _dev(B, torch.int8, "B")
-    Cm = torch.empty((M, N), dtype=torch.uint8, device=A.device) if out is None else out
+    Cm = _out(out, (M, N), A.device)
     ap, lda = _dev_rows(A, torch.uint8, "A")
     cp, ldc = _dev_rows(Cm, torch.uint8, "C")
+    wp, wbytes, _ws = _workspace(qgemm_workspace_bytes(M, N, K, weight_bits), A.device, workspace)
     _check("qnn_qgemm", load_library().qnn_qgemm(
         ap, lda, z_a, bp, ldb, b_layout, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
         _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max,
-        cp, ldc, _stream()))
+        cp, ldc, wp, wbytes, _stream()))
     return Cm
 
 
 def prepare_qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, out, bias=None, weight_bits=8,
-                  b_layout=B_COLUMNS_CONTIGUOUS):
+                  b_layout=B_COLUMNS_CONTIGUOUS, workspace=None):
     """Marshal the arguments of `qgemm` once and return a zero-argument callable that enqueues the
     product on the current stream.  For launch-bound loops: the per-call Python work shrinks to one
     foreign call.  The tensors must stay alive and unchanged in shape while the callable is used."""
@@ -251,9 +321,11 @@ def prepare_qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, out, bias=Non
     fn = load_library().qnn_qgemm
     ap, lda = _dev_rows(A, torch.uint8, "A")
     cp, ldc = _dev_rows(out, torch.uint8, "C")
+    wp, wbytes, ws = _workspace(qgemm_workspace_bytes(M, N, K, weight_bits), A.device, workspace)
     args = (ap, lda, z_a, bp, ldb, b_layout, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
-            _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max, cp, ldc)
-    keep = (A, B, mult, shift, bias, out)
+            _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max, cp, ldc,
+            wp, wbytes)
+    keep = (A, B, mult, shift, bias, out, ws)
     current_stream = torch.cuda.current_stream
 
     def launch(_keep=keep):
@@ -278,18 +350,21 @@ def _out_hw(H, W, kh, kw, stride, pad):
     return (H + 2 * pad[0] - kh) // stride[0] + 1, (W + 2 * pad[1] - kw) // stride[1] + 1
 
 
-def qconv2d(x, z_x, w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8, out=None):
+def qconv2d(x, z_x, w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8, out=None,
+            workspace=None):
     """x: uint8 NHWC.  w: int8 [Cout,kh,kw,Cin], or uint8 [Cout,kh,kw,Cin/2] packed 4-bit."""
     torch = _torch()
     N, H, W, Cin = x.shape
     Cout, kh, kw = w.shape[:3]
     wp = _dev(w, torch.uint8 if weight_bits == 4 else torch.int8, "w")
     Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
-    y = torch.empty((N, Ho, Wo, Cout), dtype=torch.uint8, device=x.device) if out is None else out
+    y = _out(out, (N, Ho, Wo, Cout), x.device)
+    sp, sbytes, _ws = _workspace(qconv2d_workspace_bytes(N, H, W, Cin, Cout, kh, kw, stride, pad, weight_bits), x.device,
+                                 workspace)
     _check("qnn_qconv2d", load_library().qnn_qconv2d(
         _dev(x, torch.uint8, "x"), N, H, W, Cin, z_x, wp, Cout, kh, kw, weight_bits, stride[0], stride[1], pad[0],
         pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"),
-        z_out, act_min, act_max, _dev(y, torch.uint8, "y"), _stream()))
+        z_out, act_min, act_max, _dev(y, torch.uint8, "y"), sp, sbytes, _stream()))
     return y
 
 
@@ -306,7 +381,7 @@ def _add_struct(z_r, params, z_out, act_min, act_max):
 
 
 def qgemm_add(A, z_a, B, mult, shift, z_mid, mid_min, mid_max, residual, z_r, params, z_out, act_min, act_max,
-              bias=None, weight_bits=8, out=None):
+              bias=None, weight_bits=8, out=None, workspace=None):
     """qgemm (columns-contiguous B) whose uint8 result, quantized with (z_mid, mid_min, mid_max), is added to
     `residual` (uint8 [M,N], rows may be spaced apart) with the rescaling add of `params`; returns uint8 [M,N]."""
     torch = _torch()
@@ -315,39 +390,42 @@ def qgemm_add(A, z_a, B, mult, shift, z_mid, mid_min, mid_max, residual, z_r, pa
         N, ldb, bp = B.shape[0], B.shape[1] * 2, _dev(B, torch.uint8, "B")
     else:
         (N, ldb), bp = B.shape, _dev(B, torch.int8, "B")
-    Cm = torch.empty((M, N), dtype=torch.uint8, device=A.device) if out is None else out
+    Cm = _out(out, (M, N), A.device)
     ap, lda = _dev_rows(A, torch.uint8, "A")
     cp, ldc = _dev_rows(Cm, torch.uint8, "C")
     rp, ldr = _dev_rows(residual, torch.uint8, "residual")
     add = _add_struct(z_r, params, z_out, act_min, act_max)
+    wp, wbytes, _ws = _workspace(qgemm_workspace_bytes(M, N, K, weight_bits), A.device, workspace)
     _check("qnn_qgemm_add", load_library().qnn_qgemm_add(
         ap, lda, z_a, bp, ldb, B_COLUMNS_CONTIGUOUS, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
         _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_mid, mid_min, mid_max, rp, ldr,
-        C.addressof(add), cp, ldc, _stream()))
+        C.addressof(add), cp, ldc, wp, wbytes, _stream()))
     return Cm
 
 
 def qconv2d_add(x, z_x, w, stride, pad, mult, shift, z_mid, mid_min, mid_max, residual, z_r, params, z_out, act_min,
-                act_max, bias=None, weight_bits=8, out=None):
+                act_max, bias=None, weight_bits=8, out=None, workspace=None):
     """qconv2d followed by the rescaling add with `residual` (uint8 NHWC, the shape of the output), fused."""
     torch = _torch()
     N, H, W, Cin = x.shape
     Cout, kh, kw = w.shape[:3]
     wp = _dev(w, torch.uint8 if weight_bits == 4 else torch.int8, "w")
     Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
-    y = torch.empty((N, Ho, Wo, Cout), dtype=torch.uint8, device=x.device) if out is None else out
+    y = _out(out, (N, Ho, Wo, Cout), x.device)
     if tuple(residual.shape) != (N, Ho, Wo, Cout):
         raise ValueError(f"residual has shape {tuple(residual.shape)}, the output {(N, Ho, Wo, Cout)}")
     add = _add_struct(z_r, params, z_out, act_min, act_max)
+    sp, sbytes, _ws = _workspace(qconv2d_workspace_bytes(N, H, W, Cin, Cout, kh, kw, stride, pad, weight_bits), x.device,
+                                 workspace)
     _check("qnn_qconv2d_add", load_library().qnn_qconv2d_add(
         _dev(x, torch.uint8, "x"), N, H, W, Cin, z_x, wp, Cout, kh, kw, weight_bits, stride[0], stride[1], pad[0],
         pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"),
         z_mid, mid_min, mid_max, _dev(residual, torch.uint8, "residual"), C.addressof(add),
-        _dev(y, torch.uint8, "y"), _stream()))
+        _dev(y, torch.uint8, "y"), sp, sbytes, _stream()))
     return y
 
 
-def qgemm_asym(A, z_a, B, z_w, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8, out=None):
+def qgemm_asym(A, z_a, B, z_w, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8, out=None, workspace=None):
     """qgemm with a zero-point per weight column: z_w int32 [N] on the device.  B: int8 [N,K] (columns
     contiguous) or uint8 [N,K/2] nibble-packed."""
     torch = _torch()
@@ -356,28 +434,32 @@ def qgemm_asym(A, z_a, B, z_w, mult, shift, z_out, act_min, act_max, bias=None, 
         N, ldb, bp = B.shape[0], B.shape[1] * 2, _dev(B, torch.uint8, "B")
     else:
         (N, ldb), bp = B.shape, _dev(B, torch.int8, "B")
-    Cm = torch.empty((M, N), dtype=torch.uint8, device=A.device) if out is None else out
+    Cm = _out(out, (M, N), A.device)
     ap, lda = _dev_rows(A, torch.uint8, "A")
     cp, ldc = _dev_rows(Cm, torch.uint8, "C")
+    wp, wbytes, _ws = _workspace(qgemm_workspace_bytes(M, N, K, weight_bits, True), A.device, workspace)
     _check("qnn_qgemm_asym", load_library().qnn_qgemm_asym(
         ap, lda, z_a, bp, ldb, B_COLUMNS_CONTIGUOUS, weight_bits, _dev(z_w, torch.int32, "z_w"), M, N, K,
         _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out,
-        act_min, act_max, cp, ldc, _stream()))
+        act_min, act_max, cp, ldc, wp, wbytes, _stream()))
     return Cm
 
 
-def qconv2d_asym(x, z_x, w, z_w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8, out=None):
+def qconv2d_asym(x, z_x, w, z_w, stride, pad, mult, shift, z_out, act_min, act_max, bias=None, weight_bits=8, out=None,
+                 workspace=None):
     """qconv2d with a zero-point per output channel: z_w int32 [Cout] on the device."""
     torch = _torch()
     N, H, W, Cin = x.shape
     Cout, kh, kw = w.shape[:3]
     wp = _dev(w, torch.uint8 if weight_bits == 4 else torch.int8, "w")
     Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
-    y = torch.empty((N, Ho, Wo, Cout), dtype=torch.uint8, device=x.device) if out is None else out
+    y = _out(out, (N, Ho, Wo, Cout), x.device)
+    sp, sbytes, _ws = _workspace(qconv2d_workspace_bytes(N, H, W, Cin, Cout, kh, kw, stride, pad, weight_bits, True), x.device,
+                                 workspace)
     _check("qnn_qconv2d_asym", load_library().qnn_qconv2d_asym(
         _dev(x, torch.uint8, "x"), N, H, W, Cin, z_x, wp, Cout, kh, kw, weight_bits, _dev(z_w, torch.int32, "z_w"),
         stride[0], stride[1], pad[0], pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"),
-        _dev(shift, torch.int32, "shift"), z_out, act_min, act_max, _dev(y, torch.uint8, "y"), _stream()))
+        _dev(shift, torch.int32, "shift"), z_out, act_min, act_max, _dev(y, torch.uint8, "y"), sp, sbytes, _stream()))
     return y
 
 
@@ -406,7 +488,7 @@ def minmax(x, state, momentum=0.0, bits=8):
 
 def quantize_with(x, state, out=None):
     torch = _torch()
-    q = torch.empty(x.shape, dtype=torch.uint8, device=x.device) if out is None else out
+    q = _out(out, x.shape, x.device)
     _check("qnn_quantize_with", load_library().qnn_quantize_with(_dev(x, torch.float32, "x"), _dev(q, torch.uint8, "q"),
                                                                  x.numel(), _dev(state, torch.int32, "state"), _stream()))
     return q
@@ -415,7 +497,7 @@ def quantize_with(x, state, out=None):
 def quantize_dynamic(x, state, out=None):
     """uint8 codes of x with the quantizer of its own range; the parameters are left in `state`."""
     torch = _torch()
-    q = torch.empty(x.shape, dtype=torch.uint8, device=x.device) if out is None else out
+    q = _out(out, x.shape, x.device)
     _check("qnn_quantize_dynamic", load_library().qnn_quantize_dynamic(
         _dev(x, torch.float32, "x"), _dev(q, torch.uint8, "q"), x.numel(), _dev(state, torch.int32, "state"), _stream()))
     return q
@@ -443,7 +525,7 @@ def rescale_u8(x, z_in, mult, shift, z_out, act_min=0, act_max=255, out=None):
     column slice of a wider tensor (the destination of a concatenation)."""
     torch = _torch()
     rows, cols = x.shape
-    y = torch.empty((rows, cols), dtype=torch.uint8, device=x.device) if out is None else out
+    y = _out(out, (rows, cols), x.device)
     xp, ldx = _dev_rows(x, torch.uint8, "x")
     yp, ldy = _dev_rows(y, torch.uint8, "y")
     _check("qnn_rescale_u8", load_library().qnn_rescale_u8(xp, ldx, int(z_in), int(mult), int(shift), int(z_out), int(act_min),
@@ -457,7 +539,7 @@ def qdwconv2d_asym(x, z_x, w, z_w, stride, pad, mult, shift, z_out, act_min, act
     N, H, W, Cc = x.shape
     kh, kw = w.shape[:2]
     Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
-    y = torch.empty((N, Ho, Wo, Cc), dtype=torch.uint8, device=x.device) if out is None else out
+    y = _out(out, (N, Ho, Wo, Cc), x.device)
     _check("qnn_qdwconv2d_asym", load_library().qnn_qdwconv2d_asym(
         _dev(x, torch.uint8, "x"), N, H, W, Cc, z_x, _dev(w, torch.int8, "w"), kh, kw, _dev(z_w, torch.int32, "z_w"), stride[0],
         stride[1], pad[0], pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"),
@@ -471,7 +553,7 @@ def qdwconv2d(x, z_x, w, stride, pad, mult, shift, z_out, act_min, act_max, bias
     N, H, W, Cc = x.shape
     kh, kw = w.shape[:2]
     Ho, Wo = _out_hw(H, W, kh, kw, stride, pad)
-    y = torch.empty((N, Ho, Wo, Cc), dtype=torch.uint8, device=x.device) if out is None else out
+    y = _out(out, (N, Ho, Wo, Cc), x.device)
     _check("qnn_qdwconv2d", load_library().qnn_qdwconv2d(
         _dev(x, torch.uint8, "x"), N, H, W, Cc, z_x, _dev(w, torch.int8, "w"), kh, kw, stride[0], stride[1], pad[0],
         pad[1], _dev(bias, torch.int32, "bias"), _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"),
@@ -481,7 +563,7 @@ def qdwconv2d(x, z_x, w, stride, pad, mult, shift, z_out, act_min, act_max, bias
 
 def qadd(a, z_a, b, z_b, params, z_out, act_min, act_max, out=None):
     torch = _torch()
-    y = torch.empty(a.shape, dtype=torch.uint8, device=a.device) if out is None else out
+    y = _out(out, a.shape, a.device)
     p = params
     _check("qnn_qadd", load_library().qnn_qadd(
         _dev(a, torch.uint8, "a"), z_a, p["mult_a"], p["shift_a"], _dev(b, torch.uint8, "b"), z_b, p["mult_b"],

@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #include "qnn_device.h"
+#include "tuning.h"
 
 namespace qnn {
 
@@ -391,7 +392,7 @@ static qnn_status qdwconv2d_impl(const uint8_t *x, int N, int H, int W, int C, i
     }
     const int64_t blocks = (g.total_work + 255) / 256;
     if (blocks > 0x7fffffff) return QNN_EINVAL;
-    const bool old_form = std::getenv("QNN_DW_MAD") != nullptr; // tuning aid: the multiply-add form
+    const bool old_form = tuning().dw_mad != 0; // tuning aid: the multiply-add form
     const int64_t lanes_x = (int64_t)g.wruns * (C / 4);
     const bool dot_ok = c4 && !old_form && N <= 65535 && g.hruns <= 65535 && lanes_x < (1ll << 31) - 256 &&
                         (int64_t)W * C < (1ll << 31) && (int64_t)g.Wo * C < (1ll << 31);
@@ -405,8 +406,7 @@ static qnn_status qdwconv2d_impl(const uint8_t *x, int N, int H, int W, int C, i
         g.magic_cgroups = d > 1 ? (uint32_t)((((uint64_t)1 << (31 + l)) + d - 1) / d) : 0u;
         // taller patches (4 output rows per lane) reuse more of the window, but need enough lanes to
         // give the chip something to do (tiny layers keep 2-row patches: twice the lanes)
-        const char *rh_env = std::getenv("QNN_DW_RH"); // tuning aid: 2 or 4 forces the patch height
-        const int tall_env = rh_env ? std::atoi(rh_env) : 0;
+        const int tall_env = tuning().dw_rh; // tuning aid: 2 or 4 forces the patch height
         const int64_t lanes_tall = lanes_x * ((g.Ho + 3) / 4) * N;
         const bool tall = tall_env ? tall_env == 4 : lanes_tall >= 16384;
         if (tall) g.hruns = (g.Ho + 3) / 4;

@@ -5,7 +5,10 @@
 #include <cstring>
 #include <limits>
 
+#include <cstdlib>
+
 #include "qnn_device.h"
+#include "tuning.h"
 
 namespace qnn {
 
@@ -18,6 +21,45 @@ qnn_status launch_status(hipError_t e)
     return QNN_ELAUNCH;
 }
 
+struct TuningField {
+    const char *name;
+    int Tuning::*field;
+    int unset;
+};
+static const TuningField kTuningFields[] = {
+    {"QNN_FORCE_SPLIT", &Tuning::force_split, 0}, {"QNN_NO_SHORTK", &Tuning::no_shortk, 0},
+    {"QNN_BRES", &Tuning::bres, -1},              {"QNN_STEM_BLOCK", &Tuning::stem_block, 0},
+    {"QNN_XCD_ROWS", &Tuning::xcd_rows, -1},      {"QNN_DW_RH", &Tuning::dw_rh, 0},
+    {"QNN_DW_MAD", &Tuning::dw_mad, 0},           {"QNN_GEMM_PRIO", &Tuning::gemm_prio, -1},
+    {"QNN_PERSIST", &Tuning::persist, -1},        {"QNN_DW_VARIANT", &Tuning::dw_variant, -1},
+};
+
+static bool tuning_assign(Tuning &t, const char *name, const char *value)
+{
+    if (std::strcmp(name, "QNN_FORCE_TILE") == 0) {
+        std::snprintf(t.force_tile, sizeof t.force_tile, "%s", value ? value : "");
+        return true;
+    }
+    for (const TuningField &f : kTuningFields)
+        if (std::strcmp(name, f.name) == 0) {
+            // a switch that is set without a number counts as 1, as the bare environment variable did
+            t.*(f.field) = value ? ((*value == 0) ? 1 : std::atoi(value)) : f.unset;
+            return true;
+        }
+    return false;
+}
+
+Tuning &tuning()
+{
+    static Tuning t = [] {
+        Tuning init;
+        (void)tuning_assign(init, "QNN_FORCE_TILE", std::getenv("QNN_FORCE_TILE"));
+        for (const TuningField &f : kTuningFields) (void)tuning_assign(init, f.name, std::getenv(f.name));
+        return init;
+    }();
+    return t;
+}
+
 // nearest integer, halves go away from zero
 static double nearest_away(double v) { return std::copysign(std::floor(std::fabs(v) + 0.5), v); }
 
@@ -27,7 +69,13 @@ extern "C" {
 
 const char *qnn_last_error(void) { return qnn::g_last_error; }
 
-const char *qnn_version(void) { return "0.1"; }
+const char *qnn_version(void) { return "0.2"; }
+
+qnn_status qnn_tuning_set(const char *name, const char *value)
+{
+    if (!name) return QNN_EINVAL;
+    return qnn::tuning_assign(qnn::tuning(), name, value) ? QNN_OK : QNN_EINVAL;
+}
 
 // Sec. 2.1: the range is widened to hold 0 so that real 0 maps to the integer z exactly.
 qnn_status qnn_choose_qparams(double xmin, double xmax, int bits, float *scale, int32_t *zero_point)

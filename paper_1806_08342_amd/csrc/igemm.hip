@@ -8,9 +8,9 @@
 
 #include "igemm_dma.h"
 #include "igemm_launch.h"
+#include "tuning.h"
 
 namespace qnn {
-
 
 enum TileConfig {
     TILE_64x64 = 0,
@@ -22,47 +22,51 @@ enum TileConfig {
     TILE_DMA_256x64_S3,
     TILE_DMA_256x128,
     TILE_DMA_64x64,
+    TILE_DMA_128x256_P, // 4 waves of 64x128, 3 stages, two persistent workgroups per CU
+    TILE_DMA_256x128_P, // 4 waves of 128x64, 3 stages, two persistent workgroups per CU
+    TILE_DMA_256x256_W4, // 4 waves of 128x128 (one per SIMD, accumulators in the second half of the register file)
     TILE_COUNT
 };
 
-static const char *const kTileNames[TILE_COUNT] = {"64x64",     "128x128",      "dma128x128",  "dma256x256",
-                                                   "dma256x64", "dma128x128s3", "dma256x64s3", "dma256x128", "dma64x64"};
-static const int kTileM[TILE_COUNT] = {64, 128, 128, 256, 256, 128, 256, 256, 64};
-static const int kTileN[TILE_COUNT] = {64, 128, 128, 256, 64, 128, 64, 128, 64};
-
-// scratch block per device: split-K partial sums in the first half, unpacked 4-bit weights in the second
-constexpr size_t kSplitBytes = (size_t)32 << 20, kUnpackBytes = (size_t)32 << 20;
-constexpr size_t kWorkspaceBytes = kSplitBytes + kUnpackBytes;
+static const char *const kTileNames[TILE_COUNT] = {"64x64",     "128x128",      "dma128x128",  "dma256x256", "dma256x64",
+                                                   "dma128x128s3", "dma256x64s3", "dma256x128", "dma64x64",  "p128x256",
+                                                   "p256x128",  "dma256x256w4"};
+static const int kTileM[TILE_COUNT] = {64, 128, 128, 256, 256, 128, 256, 256, 64, 128, 256, 256};
+static const int kTileN[TILE_COUNT] = {64, 128, 128, 256, 64, 128, 64, 128, 64, 256, 128, 256};
 
 struct Plan {
     TileConfig tile;
     int splits; // > 1: split-K (128x128 and 64x64 pipelined tiles only)
 };
 
-static int env_int(const char *name, int fallback)
-{
-    const char *e = std::getenv(name);
-    return e ? std::atoi(e) : fallback;
-}
-
-// Tile choice.  `dma_ok`: int8 weights with contiguous columns, 16-byte aligned chunks, K % 64 == 0.
+// Tile choice.  `dma_ok`: weights with contiguous columns, 16-byte aligned chunks, K % 64 == 0.
 //  - large products: 256x256 tiles (8 waves, 4 LDS stages, one workgroup per CU), or the
 //    256x128 / 128x128 / 256x64 tile that wastes the least work in partly filled rounds;
 //  - short K (<= 256): 3 LDS stages instead of 4, so that more workgroups fit a CU and one
 //    workgroup's epilogue overlaps another one's loads and MFMAs;
-//  - products with too few output tiles for 256 CUs: split-K over 128x128 or 64x64 tiles.
-static Plan choose_plan(int64_t M, int64_t N, int64_t K, bool dma_ok)
+//  - products with too few output tiles for 256 CUs: split-K over 128x128 or 64x64 tiles
+//    (`split_bytes`: scratch memory the caller offers for the partial sums; 4-bit weights run unsplit).
+static Plan choose_plan(int64_t M, int64_t N, int64_t K, bool dma_ok, bool int4, size_t split_bytes)
 {
-    if (const char *force = std::getenv("QNN_FORCE_TILE")) { // tuning aid: force one configuration
+    const Tuning &tu = tuning();
+    auto fits = [&](int splits) { return (uint64_t)splits * (uint64_t)M * (uint64_t)N * 4u <= (uint64_t)split_bytes; };
+    if (tu.forced()) { // tuning aid: force one configuration
         for (int t = 0; t < TILE_COUNT; ++t)
-            if (std::strcmp(force, kTileNames[t]) == 0 && (t < TILE_DMA_128x128 || dma_ok)) {
+            if (std::strcmp(tu.force_tile, kTileNames[t]) == 0 && (t < TILE_DMA_128x128 || dma_ok)) {
+                if (int4 && t >= TILE_DMA_128x128 && t != TILE_DMA_128x128 && t != TILE_DMA_256x256 && t != TILE_DMA_64x64) break;
                 int splits = 1;
-                if (t == TILE_DMA_128x128 || t == TILE_DMA_64x64) splits = env_int("QNN_FORCE_SPLIT", 1);
+                if (!int4 && (t == TILE_DMA_128x128 || t == TILE_DMA_64x64)) splits = tu.force_split > 0 ? tu.force_split : 1;
                 const int ksteps = (int)(K / 64);
                 splits = splits < 1 ? 1 : (splits > ksteps ? ksteps : splits);
-                if ((int64_t)splits * M * N * 4 > (int64_t)kSplitBytes) splits = 1;
+                if (!fits(splits)) splits = 1;
                 return Plan{(TileConfig)t, splits};
             }
+    }
+    if (dma_ok && M >= 128 && int4) { // the pipelined kernel expands nibbles for three tile shapes
+        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
+        if (K > 256 && N >= 128 && t256 >= 160) return Plan{TILE_DMA_256x256, 1};
+        if (N >= 128 && t128 >= 192) return Plan{TILE_DMA_128x128, 1};
+        return Plan{TILE_DMA_64x64, 1};
     }
     if (dma_ok && M >= 128) {
         if (K <= 256) { // epilogue-bound: small tiles, several workgroups per CU
@@ -101,66 +105,30 @@ static Plan choose_plan(int64_t M, int64_t N, int64_t K, bool dma_ok)
                 const int64_t want = (256 + tiles64 - 1) / tiles64, most = ksteps / 16;
                 plan.splits = (int)(want < most ? want : most);
             }
-            while (plan.splits > 1 && (int64_t)plan.splits * M * N * 4 > (int64_t)kSplitBytes) --plan.splits;
+            while (plan.splits > 1 && !fits(plan.splits)) --plan.splits;
             return plan;
         }
     }
     return Plan{(N <= 64 || M <= 64) ? TILE_64x64 : TILE_128x128, 1};
 }
 
-// Scratch memory of the split-K path and of the 4-bit weight unpacking pass: one fixed block per device, allocated at the first call
-// that needs it and kept until the process ends.  Calls on different streams are ordered with
-// an event (the block is shared); while a stream is being captured into a graph no event is
-// recorded, and no block is allocated if none exists yet (the caller then runs unsplit).
-constexpr int kMaxDevices = 64;
-struct Workspace {
-    int32_t *ptr = nullptr;
-    hipEvent_t done = nullptr;
-    hipStream_t last = nullptr;
-    bool used = false;
-};
-static Workspace g_workspace[kMaxDevices];
-static std::mutex g_workspace_mutex;
+// Scratch memory comes from the caller (`workspace` of the entry points): the int32 activation row
+// sums of the asymmetric-weight entry points (M values, first) and the partial sums of split-K
+// (splits x M x N values, behind them at the next multiple of 256 bytes).
+constexpr uint64_t kMaxSplitBytes = (uint64_t)1 << 40;
+static size_t rowsum_bytes(int64_t M) { return (size_t)((M * 4 + 255) / 256 * 256); }
 
-static bool stream_is_capturing(hipStream_t s)
+static size_t workspace_bytes_for(int64_t M, int64_t N, int64_t K, int weight_bits, bool asym)
 {
-    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(s, &st) != hipSuccess) {
-        (void)hipGetLastError();
-        return false;
-    }
-    return st != hipStreamCaptureStatusNone;
-}
-
-// the device's scratch block, made safe to overwrite from stream `s`; nullptr if unavailable
-static int32_t *acquire_workspace(hipStream_t s, bool capturing)
-{
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-    std::lock_guard<std::mutex> lock(g_workspace_mutex);
-    Workspace &w = g_workspace[dev];
-    if (!w.ptr) {
-        if (capturing) return nullptr; // allocation is not allowed during capture
-        if (hipMalloc(reinterpret_cast<void **>(&w.ptr), kWorkspaceBytes) != hipSuccess ||
-            hipEventCreateWithFlags(&w.done, hipEventDisableTiming) != hipSuccess) {
-            (void)hipGetLastError();
-            if (w.ptr) (void)hipFree(w.ptr);
-            w.ptr = nullptr;
-            return nullptr;
-        }
-    }
-    if (!capturing && w.used && w.last != s) (void)hipStreamWaitEvent(s, w.done, 0);
-    return w.ptr;
-}
-
-static void release_workspace(hipStream_t s, bool capturing)
-{
-    if (capturing) return;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return;
-    std::lock_guard<std::mutex> lock(g_workspace_mutex);
-    Workspace &w = g_workspace[dev];
-    if (hipEventRecord(w.done, s) == hipSuccess) w.used = true, w.last = s;
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    if (asym) return rowsum_bytes(M);
+    if ((K % 64) != 0) return 0;                                  // unaligned: the staged kernel, never split
+    if (!tuning().forced() && (M <= 64 || K <= 256)) return 0; // few-row and short-K kernels
+    const Plan plan = choose_plan(M, N, K, true, weight_bits == 4, (size_t)kMaxSplitBytes);
+    if (plan.splits <= 1) return 0;
+    const int ksteps = (int)((K / 64 + plan.splits - 1) / plan.splits);
+    const int splits = (int)((K / 64 + ksteps - 1) / ksteps);
+    return splits > 1 ? (size_t)splits * (size_t)M * (size_t)N * 4 : 0;
 }
 
 // One rectangle of the tile grid per XCD: pick the cut (8x1, 4x2, 2x4, 1x8) with the least operand
@@ -168,7 +136,7 @@ static void release_workspace(hipStream_t s, bool capturing)
 // the XCDs within 10 % of an even load; else (xcd_rows stays 0) bands of the linear tile sequence.
 static void choose_xcd_cut(const IgemmArgs &g, int tiles_m, int tiles_n, int64_t work, int &per_xcd, int &xcd_rows)
 {
-    static const int forced = std::getenv("QNN_XCD_ROWS") ? std::atoi(std::getenv("QNN_XCD_ROWS")) : -1;
+    const int forced = tuning().xcd_rows;
     double best = 0.0;
     for (int r : {8, 4, 2, 1}) {
         const int c = 8 / r;
@@ -181,21 +149,30 @@ static void choose_xcd_cut(const IgemmArgs &g, int tiles_m, int tiles_n, int64_t
     }
 }
 
-template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false, bool ZW = false>
-static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = SplitK{1, 0, nullptr})
+// `per_cu` > 0: persistent launch with that many workgroups per CU (each walks its XCD's tile
+// sequence); 0: one workgroup per tile.  `prio`: issue-priority scheme of the main loop (see the kernel).
+template <int BM, int BN, int WM, int WN, int A_MODE, int NSTAGE, bool SPLIT = false, bool ZW = false, bool B4 = false,
+          int MINW = 1>
+static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = SplitK{1, 0, nullptr}, int per_cu = 0, int prio = 0)
 {
     constexpr int kStages = NSTAGE * (BM + BN) * 64;
     constexpr int kOut = BM * (BN + 16) + 4 * WM * WN * (BN / WN / 32) * 64 + 2048 + 4 * BM; // + add tables + row sums
     constexpr int kLds = kStages > kOut ? kStages : kOut; // operand ring, reused for the output tile + column sums + add tables
-    auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE, SPLIT, ZW>;
+    auto kernel = igemm_dma_kernel<BM, BN, WM, WN, A_MODE, NSTAGE, SPLIT, ZW, B4, MINW>;
     static LdsOptIn opt_in; // per instantiation
     if (hipError_t e = opt_in.ensure(reinterpret_cast<const void *>(kernel), kLds); e != hipSuccess) return e;
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (g.N + BN - 1) / BN;
     const int64_t work = (int64_t)tiles_m * tiles_n * sk.splits;
     int per_xcd = (int)((work + 7) / 8), xcd_rows = 0;
     if (!SPLIT) choose_xcd_cut(g, tiles_m, tiles_n, work, per_xcd, xcd_rows);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(per_xcd * 8)), dim3(WM * WN * 64), kLds, s, g, tiles_m, tiles_n, per_xcd,
-                       xcd_rows, sk);
+    const Tuning &tu = tuning();
+    if (tu.persist == 0) per_cu = 0;
+    else if (tu.persist > 0) per_cu = tu.persist;
+    if (tu.gemm_prio >= 0) prio = tu.gemm_prio;
+    int slots = per_xcd; // workgroups per XCD
+    if (per_cu > 0 && slots > 32 * per_cu) slots = 32 * per_cu;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(slots * 8)), dim3(WM * WN * 64), kLds, s, g, tiles_m, tiles_n, per_xcd, xcd_rows,
+                       sk, prio);
     hipError_t e = hipGetLastError();
     if (SPLIT && e == hipSuccess) {
         const int64_t threads = g.M * (((int64_t)g.N + 3) / 4);
@@ -205,84 +182,49 @@ static hipError_t launch_dma(const IgemmArgs &g, hipStream_t s, SplitK sk = Spli
     return e;
 }
 
-
-
-// 4-bit weights for the pipelined kernel: one pass turns the nibble pairs of B ([N][K/2] bytes,
-// element 2j in the low nibble of byte j) into int8 [N][K] in scratch memory; the product then runs
-// on the int8 path.  Weights are small next to the activations of the layers this is used for
-// (M > 64), and the short-K and few-row kernels unpack in registers instead.
-__global__ void __launch_bounds__(256) unpack_int4_kernel(const uint8_t *__restrict__ src, int64_t ld_src_bytes, int N, int K,
-                                                         int8_t *__restrict__ dst)
+// Per-column weight zero-points (eq. 5-6 with z_w != 0): the activation row sums go to the caller's
+// scratch memory first (one pass over A), then one tile configuration whose epilogue subtracts
+// z_w[n] * rowsum[m]: a pipelined tile when the operands are aligned, else the staged 64x64 tile.
+static qnn_status run_igemm_zw(IgemmArgs &g, int a_mode, int b_mode, int vec, int kh, void *workspace, size_t workspace_bytes,
+                               hipStream_t s)
 {
-    const int pieces = K / 16; // 16 elements = 8 packed bytes -> 16 bytes
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (int64_t)N * pieces) return;
-    const int n = (int)(idx / pieces), p = (int)(idx - (int64_t)n * pieces);
-    const u32x2 raw = *reinterpret_cast<const u32x2 *>(src + n * ld_src_bytes + p * 8);
-    const uint32_t r2[2] = {raw.x, raw.y};
-    u32x4 out;
-#pragma unroll
-    for (int d = 0; d < 2; ++d) {
-        uint32_t lo = r2[d] & 0x0F0F0F0Fu, hi = (r2[d] >> 4) & 0x0F0F0F0Fu; // elements 0,2,4,6 / 1,3,5,7 of this dword
-        lo |= ((lo >> 3) & 0x01010101u) * 0xF0u;                           // sign-extend each nibble to a byte
-        hi |= ((hi >> 3) & 0x01010101u) * 0xF0u;
-        out[2 * d] = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
-        out[2 * d + 1] = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
-    }
-    *reinterpret_cast<u32x4 *>(dst + (int64_t)n * K + p * 16) = out;
-}
-
-// Per-column weight zero-points (eq. 5-6 with z_w != 0): the activation row sums go to the scratch
-// block first (one pass over A), then one tile configuration whose epilogue subtracts
-// z_w[n] * rowsum[m]: the pipelined 128x128 tile when the operands are aligned, else the staged
-// 64x64 tile.  No split-K (the scratch block holds the row sums).
-static qnn_status run_igemm_zw(IgemmArgs &g, int a_mode, int b_mode, int vec, int kh, hipStream_t s)
-{
-    if (g.M * 4 > (int64_t)kSplitBytes) return QNN_EUNSUPPORTED;
-    const bool capturing = stream_is_capturing(s);
-    int32_t *workspace = acquire_workspace(s, capturing);
-    if (!workspace) return QNN_EUNSUPPORTED; // no scratch block yet and none may be allocated during capture
-    auto finish = [&](qnn_status st) {
-        release_workspace(s, capturing);
-        return st;
-    };
-    if (qnn_status st = launch_rowsum(g, a_mode, kh, workspace, s); st != QNN_OK) return finish(st);
-    g.rowsum = workspace;
-    const bool aligned_for_dma = vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23);
-    if (b_mode == B_INT4 && aligned_for_dma && (int64_t)g.N * g.K <= (int64_t)kUnpackBytes) {
-        int8_t *unpacked = reinterpret_cast<int8_t *>(workspace) + kSplitBytes;
-        const int64_t threads = (int64_t)g.N * (g.K / 16);
-        hipLaunchKernelGGL(unpack_int4_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, g.B, g.ldb / 2, g.N,
-                           g.K, unpacked);
-        g.B = reinterpret_cast<const uint8_t *>(unpacked), g.ldb = g.K;
-        b_mode = B_INT8;
-    }
-    if (b_mode == B_INT8 && aligned_for_dma && ((g.M + 127) / 128) * ((g.N + 127) / 128) <= 0x7ffffff) {
+    if (!workspace || workspace_bytes < rowsum_bytes(g.M) || !aligned_to(workspace, 16)) return QNN_EINVAL;
+    int32_t *rowsum = static_cast<int32_t *>(workspace);
+    if (qnn_status st = launch_rowsum(g, a_mode, kh, rowsum, s); st != QNN_OK) return st;
+    g.rowsum = rowsum;
+    const bool i4 = b_mode == B_INT4;
+    const bool aligned_for_dma = vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23) &&
+                                 (!i4 || (aligned_to(g.B, 16) && (g.ldb % 32) == 0));
+    if ((b_mode == B_INT8 || i4) && aligned_for_dma && ((g.M + 127) / 128) * ((g.N + 127) / 128) <= 0x7ffffff) {
         // large products: the 256x256 tile once it fills most of the chip, else 128x128
         const bool big = ((g.M + 255) / 256) * ((g.N + 255) / 256) >= 160 && g.K > 256;
+        const bool mat = a_mode == A_MATRIX;
         hipError_t e;
-        if (big)
-            e = a_mode == A_MATRIX ? launch_dma<256, 256, 4, 2, A_MATRIX, 4, false, true>(g, s)
-                                   : launch_dma<256, 256, 4, 2, A_CONV, 4, false, true>(g, s);
+        if (big && i4)
+            e = mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4, false, true, true>(g, s) : launch_dma<256, 256, 4, 2, A_CONV, 4, false, true, true>(g, s);
+        else if (big)
+            e = mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4, false, true>(g, s) : launch_dma<256, 256, 4, 2, A_CONV, 4, false, true>(g, s);
+        else if (i4)
+            e = mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, false, true, true>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 4, false, true, true>(g, s);
         else
-            e = a_mode == A_MATRIX ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, false, true>(g, s)
-                                   : launch_dma<128, 128, 2, 2, A_CONV, 4, false, true>(g, s);
-        return finish(launch_status(e));
+            e = mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, false, true>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 4, false, true>(g, s);
+        return launch_status(e);
     }
-    if (((g.M + 63) / 64) * ((g.N + 63) / 64) > 0x7ffffff) return finish(QNN_EINVAL);
+    if (((g.M + 63) / 64) * ((g.N + 63) / 64) > 0x7ffffff) return QNN_EINVAL;
     launch_plain_tile_zw(g, a_mode, b_mode, vec, s);
-    return finish(launch_status(hipGetLastError()));
+    return launch_status(hipGetLastError());
 }
 
 // Shared back end.  `vec` is the widest staging vector (in k elements) that the alignment
 // of A, B and K allows.
-static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t s, int kh = 1)
+static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, void *workspace, size_t workspace_bytes,
+                            hipStream_t s, int kh = 1)
 {
     const int64_t max_tiles = 0x7ffffff;
     g.small_acc = g.K <= 8192 ? 2 : (g.K <= 16384 ? 1 : 0); // |acc| <= K * 2^14
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
     g.r_vec16 = g.R != nullptr && aligned_to(g.R, 16) && (g.ldr % 16 == 0);
-    if (g.zw) return run_igemm_zw(g, a_mode, b_mode, vec, kh, s);
+    if (g.zw) return run_igemm_zw(g, a_mode, b_mode, vec, kh, workspace, workspace_bytes, s);
     if (a_mode == A_MATRIX && shortk_eligible(g, b_mode, false)) return launch_shortk(g, b_mode, false, s);
     // kernels that do not apply a residual add themselves run without it; the add follows as a second pass
     auto add_pass = [&](qnn_status st) {
@@ -296,58 +238,33 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
         if (try_skinny(plain, a_mode, b_mode, vec, s, &st)) return add_pass(st);
         if (try_bres(plain, a_mode, b_mode, s, &st)) return add_pass(st);
     }
-    const bool mat_or_conv = a_mode == A_MATRIX;
-    bool capturing = false, workspace_used = false;
-    int32_t *workspace = nullptr;
-    const bool aligned_for_dma = vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23);
-    // 4-bit weights: unpack once into scratch memory, then the int8 pipelined kernel
-    if (b_mode == B_INT4 && aligned_for_dma && (int64_t)g.N * g.K <= (int64_t)kUnpackBytes &&
-        std::getenv("QNN_FORCE_TILE") == nullptr) {
-        capturing = stream_is_capturing(s);
-        workspace = acquire_workspace(s, capturing);
-        if (workspace) {
-            int8_t *unpacked = reinterpret_cast<int8_t *>(workspace) + kSplitBytes;
-            const int64_t threads = (int64_t)g.N * (g.K / 16);
-            hipLaunchKernelGGL(unpack_int4_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, g.B, g.ldb / 2,
-                               g.N, g.K, unpacked);
-            g.B = reinterpret_cast<const uint8_t *>(unpacked), g.ldb = g.K;
-            b_mode = B_INT8;
-            workspace_used = true;
-        }
-    }
-    const bool dma_ok = b_mode == B_INT8 && aligned_for_dma;
-    const Plan plan = choose_plan(g.M, g.N, g.K, dma_ok);
+    const bool mat = a_mode == A_MATRIX;
+    const bool i4 = b_mode == B_INT4;
+    // the pipelined kernel: 16-byte aligned chunks of A and B (4-bit: 32 elements per chunk), whole K-steps
+    const bool dma_ok = (b_mode == B_INT8 || i4) && vec == 16 && (g.K % 64) == 0 && g.lda < (1 << 23) && g.ldb < (1 << 23) &&
+                        (!i4 || (aligned_to(g.B, 16) && (g.ldb % 32) == 0));
+    if (!aligned_to(workspace, 16)) workspace = nullptr;
+    const Plan plan = choose_plan(g.M, g.N, g.K, dma_ok, i4, workspace ? workspace_bytes : 0);
     const TileConfig cfg = plan.tile;
     const int64_t bm = kTileM[cfg], bn = kTileN[cfg];
-    auto finish = [&](qnn_status st) { // the scratch block is free again after what was enqueued so far
-        if (workspace_used) release_workspace(s, capturing);
-        return st;
-    };
     if (plan.splits > 1) {
-        if (!workspace) {
-            capturing = stream_is_capturing(s);
-            workspace = acquire_workspace(s, capturing);
-        }
         SplitK sk;
         sk.ksteps = (g.K / 64 + plan.splits - 1) / plan.splits;
         sk.splits = (g.K / 64 + sk.ksteps - 1) / sk.ksteps; // no empty K range
-        sk.partial = workspace;
+        sk.partial = static_cast<int32_t *>(workspace);
         if (sk.partial && sk.splits > 1) {
-            workspace_used = true;
             hipError_t e;
             IgemmArgs plain = g; // the reduction kernel writes the product's code; the add follows
             plain.R = nullptr;
             if (cfg == TILE_DMA_128x128)
-                e = mat_or_conv ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, true>(plain, s, sk)
-                                : launch_dma<128, 128, 2, 2, A_CONV, 4, true>(plain, s, sk);
+                e = mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, true>(plain, s, sk) : launch_dma<128, 128, 2, 2, A_CONV, 4, true>(plain, s, sk);
             else
-                e = mat_or_conv ? launch_dma<64, 64, 2, 2, A_MATRIX, 4, true>(plain, s, sk)
-                                : launch_dma<64, 64, 2, 2, A_CONV, 4, true>(plain, s, sk);
-            return finish(add_pass(launch_status(e)));
+                e = mat ? launch_dma<64, 64, 2, 2, A_MATRIX, 4, true>(plain, s, sk) : launch_dma<64, 64, 2, 2, A_CONV, 4, true>(plain, s, sk);
+            return add_pass(launch_status(e));
         }
     }
-    if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return finish(QNN_EINVAL);
-    const bool mat = a_mode == A_MATRIX;
+    if (((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) > max_tiles) return QNN_EINVAL;
+    const SplitK one{1, 0, nullptr};
     switch (cfg) {
     case TILE_64x64:
         launch_plain_tile(false, g, a_mode, b_mode, vec, s);
@@ -356,23 +273,36 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, hipSt
         launch_plain_tile(true, g, a_mode, b_mode, vec, s);
         break;
     case TILE_DMA_128x128:
-        return finish(launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 4>(g, s)));
+        if (i4) return launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4, false, false, true>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 4, false, false, true>(g, s));
+        return launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 4>(g, s));
     case TILE_DMA_128x128_S3:
-        return finish(launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 3>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 3>(g, s)));
+        return launch_status(mat ? launch_dma<128, 128, 2, 2, A_MATRIX, 3>(g, s) : launch_dma<128, 128, 2, 2, A_CONV, 3>(g, s));
     case TILE_DMA_256x256:
-        return finish(launch_status(mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 256, 4, 2, A_CONV, 4>(g, s)));
+        if (i4) return launch_status(mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4, false, false, true>(g, s) : launch_dma<256, 256, 4, 2, A_CONV, 4, false, false, true>(g, s));
+        // persistent workgroups (one per CU) whose second wave of every SIMD trails the first: measured
+        // 5-10 % faster than one workgroup per tile on products of several rounds, equal on one round
+        return launch_status(mat ? launch_dma<256, 256, 4, 2, A_MATRIX, 4>(g, s, one, 1, 1) : launch_dma<256, 256, 4, 2, A_CONV, 4>(g, s, one, 1, 1));
     case TILE_DMA_256x64:
-        return finish(launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 4>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 4>(g, s)));
+        return launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 4>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 4>(g, s));
     case TILE_DMA_64x64:
-        return finish(launch_status(mat ? launch_dma<64, 64, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<64, 64, 2, 2, A_CONV, 4>(g, s)));
+        if (i4) return launch_status(mat ? launch_dma<64, 64, 2, 2, A_MATRIX, 4, false, false, true>(g, s) : launch_dma<64, 64, 2, 2, A_CONV, 4, false, false, true>(g, s));
+        return launch_status(mat ? launch_dma<64, 64, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<64, 64, 2, 2, A_CONV, 4>(g, s));
     case TILE_DMA_256x128:
-        return finish(launch_status(mat ? launch_dma<256, 128, 4, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 128, 4, 2, A_CONV, 4>(g, s)));
+        return launch_status(mat ? launch_dma<256, 128, 4, 2, A_MATRIX, 4>(g, s, one, 1, 0) : launch_dma<256, 128, 4, 2, A_CONV, 4>(g, s, one, 1, 0));
     case TILE_DMA_256x64_S3:
-        return finish(launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 3>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 3>(g, s)));
+        return launch_status(mat ? launch_dma<256, 64, 4, 1, A_MATRIX, 3>(g, s) : launch_dma<256, 64, 4, 1, A_CONV, 3>(g, s));
+    case TILE_DMA_128x256_P:
+        return launch_status(mat ? launch_dma<128, 256, 2, 2, A_MATRIX, 3, false, false, false, 2>(g, s, one, 2, 2)
+                                 : launch_dma<128, 256, 2, 2, A_CONV, 3, false, false, false, 2>(g, s, one, 2, 2));
+    case TILE_DMA_256x128_P:
+        return launch_status(mat ? launch_dma<256, 128, 2, 2, A_MATRIX, 3, false, false, false, 2>(g, s, one, 2, 2)
+                                 : launch_dma<256, 128, 2, 2, A_CONV, 3, false, false, false, 2>(g, s, one, 2, 2));
+    case TILE_DMA_256x256_W4:
+        return launch_status(mat ? launch_dma<256, 256, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 256, 2, 2, A_CONV, 4>(g, s));
     default:
-        return finish(QNN_EINVAL);
+        return QNN_EINVAL;
     }
-    return finish(launch_status(hipGetLastError()));
+    return launch_status(hipGetLastError());
 }
 
 static int pick_vec(int64_t k_like, std::initializer_list<const void *> ptrs, std::initializer_list<int64_t> pitches,
@@ -413,8 +343,8 @@ static qnn_status fill_add(IgemmArgs &g, const uint8_t *residual, int64_t ldr, c
 static qnn_status qgemm_impl(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
                              int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
                              const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C,
-                             int64_t ldc, void *stream, const uint8_t *residual, int64_t ldr, const qnn_add_params *add,
-                             const int32_t *z_w = nullptr)
+                             int64_t ldc, void *workspace, size_t workspace_bytes, void *stream, const uint8_t *residual,
+                             int64_t ldr, const qnn_add_params *add, const int32_t *z_w = nullptr)
 {
     if (!A || !B || !mult || !shift || !C) return QNN_EINVAL;
     if (M <= 0 || N <= 0 || K <= 0 || K > 65536 || N > 0x7fffffff || lda < K || ldc < N) return QNN_EINVAL;
@@ -437,15 +367,16 @@ static qnn_status qgemm_impl(const uint8_t *A, int64_t lda, int32_t z_a, const v
     int b_mode = weight_bits == 4 ? B_INT4 : (b_layout == QNN_B_ROWS_CONTIGUOUS ? B_INT8_ROWS : B_INT8);
     int vec = 1;
     if (b_mode != B_INT8_ROWS) vec = pick_vec(K, {A, B}, {lda, ldb}, weight_bits);
-    return run_igemm(g, A_MATRIX, b_mode, vec, as_stream(stream));
+    return run_igemm(g, A_MATRIX, b_mode, vec, workspace, workspace_bytes, as_stream(stream));
 }
 
 
 static qnn_status qconv2d_impl(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
                                int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w,
                                const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_out,
-                               int32_t act_min, int32_t act_max, uint8_t *y, void *stream, const uint8_t *residual,
-                               const qnn_add_params *add, const int32_t *z_w = nullptr)
+                               int32_t act_min, int32_t act_max, uint8_t *y, void *workspace, size_t workspace_bytes,
+                               void *stream, const uint8_t *residual, const qnn_add_params *add,
+                               const int32_t *z_w = nullptr)
 {
     if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
     if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0) return QNN_EINVAL;
@@ -485,12 +416,14 @@ static qnn_status qconv2d_impl(const uint8_t *x, int N, int H, int W, int Cin, i
     const bool pointwise = kh == 1 && kw == 1 && stride_h == 1 && stride_w == 1 && pad_h == 0 && pad_w == 0;
     if (pointwise) { // a 1x1 convolution over NHWC is a plain matrix product
         g.lda = Cin;
-        return run_igemm(g, A_MATRIX, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream));
+        return run_igemm(g, A_MATRIX, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), workspace, workspace_bytes,
+                         as_stream(stream));
     }
     if (!z_w && kh == 1 && kw == 1 && pad_h == 0 && pad_w == 0 && shortk_eligible(g, b_mode, true)) // strided 1x1: rows are pixels
         return launch_shortk(g, b_mode, true, as_stream(stream));
     // pieces must not straddle a tap: the vector width divides Cin
-    return run_igemm(g, A_CONV, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), as_stream(stream), kh);
+    return run_igemm(g, A_CONV, b_mode, pick_vec(Cin, {x, w}, {(int64_t)Cin}, weight_bits), workspace, workspace_bytes,
+                     as_stream(stream), kh);
 }
 
 
@@ -500,77 +433,92 @@ extern "C" {
 const char *qnn_qgemm_plan(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 0 || N <= 0 || K <= 0) return "";
-    if (M > 64 && K <= 256 && (K % 8) == 0 && std::getenv("QNN_FORCE_TILE") == nullptr && std::getenv("QNN_NO_SHORTK") == nullptr)
-        return "shortk";
+    const Tuning &tu = tuning();
+    if (M > 64 && K <= 256 && (K % 8) == 0 && !tu.forced() && !tu.no_shortk) return "shortk";
     if (M <= 64 && (K % 64) == 0) return "skinny16";
-    if (M >= 32768 && K > 256 && K <= 1024 && (K % 32) == 0 && N <= 256 && std::getenv("QNN_FORCE_TILE") == nullptr &&
-        (std::getenv("QNN_BRES") == nullptr || std::atoi(std::getenv("QNN_BRES")) != 0))
-        return "bres";
-    // reported for the aligned int8 case (what the benchmark shapes are)
-    const Plan plan = choose_plan(M, N, K, (K % 64) == 0);
+    if (M >= 32768 && K > 256 && K <= 1024 && (K % 32) == 0 && N <= 256 && !tu.forced() && tu.bres != 0) return "bres";
+    // reported for the aligned int8 case (what the benchmark shapes are), with all the scratch memory it asks for
+    const Plan plan = choose_plan(M, N, K, (K % 64) == 0, false, (size_t)kMaxSplitBytes);
     if (plan.splits <= 1) return kTileNames[plan.tile];
     static thread_local char name[48];
     std::snprintf(name, sizeof name, "%s/k%d", kTileNames[plan.tile], plan.splits);
     return name;
 }
 
+size_t qnn_qgemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int weight_bits, int asym)
+{
+    return workspace_bytes_for(M, N, K, weight_bits, asym != 0);
+}
+
+size_t qnn_qconv2d_workspace_bytes(int N, int H, int W, int Cin, int Cout, int kh, int kw, int weight_bits, int stride_h,
+                                   int stride_w, int pad_h, int pad_w, int asym)
+{
+    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 ||
+        pad_h < 0 || pad_w < 0 || H + 2 * (int64_t)pad_h < kh || W + 2 * (int64_t)pad_w < kw)
+        return 0;
+    const int64_t Ho = (H + 2 * (int64_t)pad_h - kh) / stride_h + 1, Wo = (W + 2 * (int64_t)pad_w - kw) / stride_w + 1;
+    return workspace_bytes_for((int64_t)N * Ho * Wo, Cout, (int64_t)kh * kw * Cin, weight_bits, asym != 0);
+}
+
 qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
                      int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
                      const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
-                     void *stream)
+                     void *workspace, size_t workspace_bytes, void *stream)
 {
     return qgemm_impl(A, lda, z_a, B, ldb, b_layout, weight_bits, M, N, K, bias, mult, shift, z_out, act_min, act_max, C,
-                      ldc, stream, nullptr, 0, nullptr);
+                      ldc, workspace, workspace_bytes, stream, nullptr, 0, nullptr);
 }
 
 qnn_status qnn_qgemm_add(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
                          int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
                          const int32_t *shift, int32_t z_mid, int32_t mid_min, int32_t mid_max, const uint8_t *residual,
-                         int64_t ldr, const qnn_add_params *add, uint8_t *C, int64_t ldc, void *stream)
+                         int64_t ldr, const qnn_add_params *add, uint8_t *C, int64_t ldc, void *workspace,
+                         size_t workspace_bytes, void *stream)
 {
     if (!residual || !add) return QNN_EINVAL;
     return qgemm_impl(A, lda, z_a, B, ldb, b_layout, weight_bits, M, N, K, bias, mult, shift, z_mid, mid_min, mid_max, C,
-                      ldc, stream, residual, ldr, add);
+                      ldc, workspace, workspace_bytes, stream, residual, ldr, add);
 }
 
 qnn_status qnn_qgemm_asym(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
                           int weight_bits, const int32_t *z_w, int64_t M, int64_t N, int64_t K, const int32_t *bias,
                           const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
-                          uint8_t *C, int64_t ldc, void *stream)
+                          uint8_t *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!z_w) return QNN_EINVAL;
     return qgemm_impl(A, lda, z_a, B, ldb, b_layout, weight_bits, M, N, K, bias, mult, shift, z_out, act_min, act_max, C,
-                      ldc, stream, nullptr, 0, nullptr, z_w);
+                      ldc, workspace, workspace_bytes, stream, nullptr, 0, nullptr, z_w);
 }
 
 qnn_status qnn_qconv2d_asym(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
                             int kw, int weight_bits, const int32_t *z_w, int stride_h, int stride_w, int pad_h, int pad_w,
                             const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_out,
-                            int32_t act_min, int32_t act_max, uint8_t *y, void *stream)
+                            int32_t act_min, int32_t act_max, uint8_t *y, void *workspace, size_t workspace_bytes,
+                            void *stream)
 {
     if (!z_w) return QNN_EINVAL;
     return qconv2d_impl(x, N, H, W, Cin, z_x, w, Cout, kh, kw, weight_bits, stride_h, stride_w, pad_h, pad_w, bias, mult,
-                        shift, z_out, act_min, act_max, y, stream, nullptr, nullptr, z_w);
+                        shift, z_out, act_min, act_max, y, workspace, workspace_bytes, stream, nullptr, nullptr, z_w);
 }
 
 qnn_status qnn_qconv2d(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
                        int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w, const int32_t *bias,
                        const int32_t *mult, const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max,
-                       uint8_t *y, void *stream)
+                       uint8_t *y, void *workspace, size_t workspace_bytes, void *stream)
 {
     return qconv2d_impl(x, N, H, W, Cin, z_x, w, Cout, kh, kw, weight_bits, stride_h, stride_w, pad_h, pad_w, bias, mult,
-                        shift, z_out, act_min, act_max, y, stream, nullptr, nullptr);
+                        shift, z_out, act_min, act_max, y, workspace, workspace_bytes, stream, nullptr, nullptr);
 }
 
 qnn_status qnn_qconv2d_add(const uint8_t *x, int N, int H, int W, int Cin, int32_t z_x, const void *w, int Cout, int kh,
                            int kw, int weight_bits, int stride_h, int stride_w, int pad_h, int pad_w,
                            const int32_t *bias, const int32_t *mult, const int32_t *shift, int32_t z_mid,
                            int32_t mid_min, int32_t mid_max, const uint8_t *residual, const qnn_add_params *add,
-                           uint8_t *y, void *stream)
+                           uint8_t *y, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!residual || !add) return QNN_EINVAL;
     return qconv2d_impl(x, N, H, W, Cin, z_x, w, Cout, kh, kw, weight_bits, stride_h, stride_w, pad_h, pad_w, bias, mult,
-                        shift, z_mid, mid_min, mid_max, y, stream, residual, add);
+                        shift, z_mid, mid_min, mid_max, y, workspace, workspace_bytes, stream, residual, add);
 }
 
 } // extern "C"

@@ -1,5 +1,6 @@
 // Launch routine of the weight-resident kernel.
 #include "igemm_launch.h"
+#include "tuning.h"
 #include "bres.h"
 
 namespace qnn {
@@ -35,9 +36,8 @@ template <int NB> static hipError_t launch_bres_nb(const BResArgs &a, bool i4, b
 
 bool try_bres(IgemmArgs &g, int a_mode, int b_mode, hipStream_t s, qnn_status *status)
 {
-    const char *env = std::getenv("QNN_BRES"); // tuning aid: 0 = never, 1 = whenever the shape fits
-    const int mode = env ? std::atoi(env) : -1;
-    if (mode == 0 || std::getenv("QNN_FORCE_TILE") != nullptr) return false;
+    const int mode = tuning().bres; // tuning aid: 0 = never, 1 = whenever the shape fits
+    if (mode == 0 || tuning().forced()) return false;
     if (b_mode == B_INT8_ROWS || (g.K % 32) != 0 || g.K <= 256 || g.M < 4096 || g.M >= 0x7fffffe0) return false;
     const bool conv = a_mode == A_CONV;
     if (conv) {

@@ -1,5 +1,6 @@
 // Launch routines of the weight-stationary short-K kernel and of the few-row kernel.
 #include "igemm_launch.h"
+#include "tuning.h"
 #include "shortk.h"
 #include "skinny.h"
 
@@ -49,7 +50,7 @@ template <bool INT4, int VEC> static void launch_shortk_ks(const ShortKArgs &a, 
 bool shortk_eligible(const IgemmArgs &g, int b_mode, bool strided)
 {
     if (g.K > 256 || (g.K % 8) != 0 || g.M <= 64 || g.M >= 0x7fffffe0 || b_mode == B_INT8_ROWS) return false;
-    if (std::getenv("QNN_FORCE_TILE") != nullptr || std::getenv("QNN_NO_SHORTK") != nullptr) return false;
+    if (tuning().forced() || tuning().no_shortk) return false;
     const int64_t row_pitch = strided ? g.Cin : g.lda;
     if (!aligned_to(g.A, 8) || (row_pitch % 8) != 0) return false;
     if (!aligned_to(g.B, 4) || (g.ldb % 8) != 0) return false;
@@ -101,7 +102,7 @@ bool try_skinny(const IgemmArgs &g, int a_mode, int b_mode, int vec, hipStream_t
 {
     // few rows: weight-streaming kernel (one workgroup per 16 output columns, K split over 8 waves)
     if (a_mode == A_MATRIX && g.M <= 64 && vec == 16 && (g.K % 64) == 0 && b_mode != B_INT8_ROWS &&
-        std::getenv("QNN_FORCE_TILE") == nullptr) {
+        !tuning().forced()) {
         const unsigned blocks = (unsigned)((g.N + 15) / 16);
         const int mt = g.M <= 16 ? 1 : (g.M <= 32 ? 2 : 4);
         const bool i4 = b_mode == B_INT4;

@@ -1,5 +1,6 @@
 // Launch routine of the stem convolution kernels.
 #include "igemm_launch.h"
+#include "tuning.h"
 #include "stemconv.h"
 #include "stemwave.h"
 
@@ -15,7 +16,7 @@ bool try_stem(IgemmArgs &g, int batch, int kh, int stride_h, int stride_w, int w
     g.small_acc = 2;
     g.c_vec16 = aligned_to(g.C, 16) && (g.ldc % 16 == 0);
     // default: the barrier-free kernel (one wave per 32-pixel strip), built for row strides 1 and 2
-    if (std::getenv("QNN_STEM_BLOCK") == nullptr && (stride_h == 1 || stride_h == 2)) {
+    if (!tuning().stem_block && (stride_h == 1 || stride_h == 2)) {
         StemWaveArgs sw = {};
         sw.g = g, sw.kh = kh, sw.run = kw * Cin;
         sw.strips = (Wo + 31) / 32;

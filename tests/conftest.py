@@ -27,3 +27,34 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+class _Tuning:
+    """Sets tuning switches of the library for one test (qnn_tuning_set) and restores the defaults."""
+
+    def __init__(self):
+        self._touched = set()
+
+    def setenv(self, name, value):
+        import paper_1806_08342_amd as qnn
+
+        qnn.tuning_set(name, value)
+        self._touched.add(name)
+
+    def delenv(self, name, raising=False):
+        import paper_1806_08342_amd as qnn
+
+        qnn.tuning_set(name, None)
+
+    def restore(self):
+        import paper_1806_08342_amd as qnn
+
+        for name in self._touched:
+            qnn.tuning_set(name, None)
+
+
+@pytest.fixture
+def tuning():
+    t = _Tuning()
+    yield t
+    t.restore()

@@ -1,7 +1,8 @@
 """Parity at the full sizes of the five benchmark configurations, in the launch configuration
-bench.py times.  Every output element is an independent dot product, so the oracle evaluates a
-seeded sample of outputs (plus all border pixels of the first and last image, where padding
-matters) when the whole tensor would take too long; small cases are compared in full."""
+bench.py times.  Every output element is an independent dot product, so where the whole tensor
+would take the oracle too long it evaluates a seeded sample of at least 10^6 outputs plus all
+border pixels of the first and last image (where padding matters), and the same layer is
+compared in full at batch 1 and 2; small cases are compared in full at their own batch."""
 import numpy as np
 import pytest
 
@@ -15,7 +16,7 @@ from gpu_util import assert_same, dev, host
 
 pytestmark = pytest.mark.gpu
 
-N_SAMPLES = 150_000
+N_SAMPLES = 1_000_000
 
 
 def _sample_indices(rng, N, Ho, Wo, C):
@@ -35,14 +36,14 @@ def _sample_indices(rng, N, Ho, Wo, C):
     return np.unique(np.concatenate(idx)).astype(np.int64)
 
 
-def _check_layer(layer, batch, seed, what):
+def _check_layer(layer, batch, seed, what, whole=False):
     rng = np.random.default_rng(seed)
     if layer.kind == "qadd":
         n = batch * layer.H * layer.W * layer.Cout
         c = synth.qadd_case((n,), seed, oracle, act=layer.act)
         got = host(qnn.qadd(dev(c["a"]), c["z_a"], dev(c["b"]), c["z_b"], c["params"], c["z_out"], c["act_min"],
                             c["act_max"]))
-        if n > 4_000_000:
+        if n > 4_000_000 and not whole:
             idx = np.unique(np.r_[rng.integers(0, n, 2_000_000), np.arange(4096), np.arange(n - 4096, n)])
         else:
             idx = np.arange(n)
@@ -55,7 +56,7 @@ def _check_layer(layer, batch, seed, what):
     w = c.get("w_packed", c["w"])
     args = (c["stride"], c["pad"], c["mult"], c["shift"], c["z_out"], c["act_min"], c["act_max"])
     dargs = (c["stride"], c["pad"], dev(c["mult"]), dev(c["shift"]), c["z_out"], c["act_min"], c["act_max"])
-    sample = _sample_indices(rng, batch, layer.Ho, layer.Wo, layer.Cout)
+    sample = None if whole else _sample_indices(rng, batch, layer.Ho, layer.Wo, layer.Cout)
     if layer.kind == "dw":
         got = host(qnn.qdwconv2d(dev(c["x"]), c["z_x"], dev(w), *dargs, bias=dev(c["bias"])))
         want = oracle.qdwconv2d(c["x"], c["z_x"], w, *args, bias=c["bias"], sample=sample)
@@ -72,8 +73,7 @@ def _check_layer(layer, batch, seed, what):
 
 # ------------------------------------------------------------------ configuration 2
 
-@pytest.mark.parametrize("M,N,K", [(1024, 1024, 1024), (4096, 4096, 4096), (8192, 8192, 8192), (256, 8192, 8192),
-                                   (8192, 256, 4096), (4096, 1024, 256), (256, 256, 8192)])
+@pytest.mark.parametrize("M,N,K", workloads.gemm_sweep()[0], ids=lambda v: str(v))
 def test_config2_gemm_sweep_shapes_sampled_rows(M, N, K):
     c = synth.gemm_case(M, N, K, workloads.seed_for(2, 100 + (M + 3 * N + 7 * K) % 97), oracle)
     got = host(qnn.qgemm(dev(c["A"]), c["z_a"], dev(c["Bt"]), dev(c["mult"]), dev(c["shift"]), c["z_out"], 0, 255))
@@ -138,6 +138,12 @@ def _check_fused_add_layer(layer, batch, seed, what):
     assert len(np.unique(want)) > 16, f"{what}: parity would be vacuous"
 
 
+@pytest.mark.parametrize("idx", range(len(RN50)), ids=[l.name for l in RN50])
+@pytest.mark.parametrize("batch", [1, 2])
+def test_config4_resnet50_layers_whole_tensor_small_batch(idx, batch):
+    _check_layer(RN50[idx], batch, workloads.seed_for(4, 600 + idx), f"config 4 {RN50[idx].name} batch {batch}", whole=True)
+
+
 RN50_ADD = [l for l in shp.unique_shapes(workloads.fuse_adds(workloads.resnet50())) if l.kind == "conv_add"]
 
 
@@ -160,6 +166,12 @@ def test_config5_mobilenet_v2_fused_add_layers_batch32(idx):
 @pytest.mark.parametrize("idx", range(len(MBV2)), ids=[l.name for l in MBV2])
 def test_config5_mobilenet_v2_int4_layers_batch32(idx):
     _check_layer(MBV2[idx], 32, workloads.seed_for(5, idx), f"config 5 {MBV2[idx].name} batch 32")
+
+
+@pytest.mark.parametrize("idx", range(len(MBV2)), ids=[l.name for l in MBV2])
+@pytest.mark.parametrize("batch", [1, 2])
+def test_config5_mobilenet_v2_int4_layers_whole_tensor_small_batch(idx, batch):
+    _check_layer(MBV2[idx], batch, workloads.seed_for(5, 600 + idx), f"config 5 {MBV2[idx].name} batch {batch}", whole=True)
 
 
 def test_config5_quantize_full_tensor():

@@ -79,8 +79,8 @@ def test_qgemm_add_pair_table(M, N, K, bits):
 @pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma64x64",
                                   "dma256x64s3", "128x128", "64x64"])
 @pytest.mark.parametrize("M,N,K", [(300, 270, 512), (513, 130, 320)])
-def test_qgemm_add_every_tile(monkeypatch, tile, M, N, K):
-    monkeypatch.setenv("QNN_FORCE_TILE", tile)
+def test_qgemm_add_every_tile(tuning, tile, M, N, K):
+    tuning.setenv("QNN_FORCE_TILE", tile)
     _check_gemm_add(M, N, K, 4200 + M + K, f"qgemm_add tile={tile} {M}x{N}x{K}", mid=(3, 250))
     _check_gemm_add(M, N, K, 4300 + M + K, f"qgemm_add tile={tile} {M}x{N}x{K}, general add rescale", odd=True, act="none")
 
@@ -92,8 +92,8 @@ def test_qgemm_add_default_routes():
         _check_gemm_add(M, N, K, 4400 + M + N, f"qgemm_add {M}x{N}x{K} bits={bits} plan={qnn.qgemm_plan(M, N, K)}", bits=bits)
 
 
-def test_qgemm_add_weight_resident(monkeypatch):
-    monkeypatch.setenv("QNN_BRES", "1")
+def test_qgemm_add_weight_resident(tuning):
+    tuning.setenv("QNN_BRES", "1")
     _check_gemm_add(4500, 64, 512, 4500, "qgemm_add weight-resident kernel + second pass")
 
 

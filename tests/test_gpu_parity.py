@@ -320,11 +320,11 @@ STEM_SHAPES = [(65, 70, 3, 64, 7, 2, 3), (50, 130, 3, 32, 3, 2, 1), (23, 301, 3,
 
 @pytest.mark.parametrize("kernel", ["wave", "block"])
 @pytest.mark.parametrize("shape", STEM_SHAPES, ids=lambda s: "x".join(map(str, s)))
-def test_qconv2d_stem_kernels_match_oracle(monkeypatch, kernel, shape):
+def test_qconv2d_stem_kernels_match_oracle(tuning, kernel, shape):
     # both stem kernels (one wave per strip walking row segments: the default; one workgroup per strip: on request),
     # images tall enough for several row segments, fused and general rescale, extreme fill codes
     if kernel == "block":
-        monkeypatch.setenv("QNN_STEM_BLOCK", "1")
+        tuning.setenv("QNN_STEM_BLOCK", "1")
     H, W, Cin, Cout, k, s, p = shape
     layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu")
     c = synth.conv_case(layer, 2, 3100 + sum(shape), oracle, in_range=(-2.0, 2.2))
@@ -371,10 +371,10 @@ def test_qdwconv2d_matches_oracle(shape, batch):
 @pytest.mark.parametrize("shape", [(12, 12, 32, 3, 1, 1), (12, 12, 32, 3, 2, 1), (7, 7, 64, 3, 1, 1), (15, 9, 8, 3, 2, 1),
                                    (9, 11, 4, 3, 1, 0), (30, 17, 24, 3, 1, 1), (29, 31, 96, 3, 2, 1)],
                          ids=lambda s: "x".join(map(str, s)))
-def test_qdwconv2d_every_3x3_variant_matches_oracle(monkeypatch, variant, shape):
+def test_qdwconv2d_every_3x3_variant_matches_oracle(tuning, variant, shape):
     # patch heights 2 and 4 of the dot-product kernel and the multiply-add kernel, forced by environment
     name, value = variant.split("=")
-    monkeypatch.setenv(name, value)
+    tuning.setenv(name, value)
     H, W, C, k, s, p = shape
     layer = workloads.Layer("t", "dw", H, W, C, C, k=k, stride=s, pad=p, act="relu6")
     c = synth.conv_case(layer, 3, 1250 + sum(shape), oracle)
@@ -389,13 +389,14 @@ def test_qdwconv2d_every_3x3_variant_matches_oracle(monkeypatch, variant, shape)
 # ------------------------------------------------ pipelined (LDS-DMA) tile configurations
 
 @pytest.fixture
-def force_tile(monkeypatch):
+def force_tile(tuning):
     def _set(name):
-        monkeypatch.setenv("QNN_FORCE_TILE", name)
+        tuning.setenv("QNN_FORCE_TILE", name)
     return _set
 
 
-@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma64x64", "dma256x64s3", "128x128", "64x64"])
+@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma64x64", "dma256x64s3", "128x128", "64x64",
+                                  "p128x256", "p256x128"])
 @pytest.mark.parametrize("M,N,K", [(128, 128, 64), (256, 256, 256), (300, 270, 192), (1000, 520, 1088), (17, 33, 16),
                                    (515, 700, 64), (700, 64, 128), (300, 50, 320)])
 def test_qgemm_forced_tiles_match_oracle(force_tile, tile, M, N, K):
@@ -410,7 +411,8 @@ def test_qgemm_forced_tiles_match_oracle(force_tile, tile, M, N, K):
         assert_same(got, want, f"qgemm tile={tile} {M}x{N}x{K} z_a={z_a}")
 
 
-@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma64x64", "dma256x64s3"])
+@pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma64x64", "dma256x64s3", "p128x256",
+                                  "p256x128"])
 @pytest.mark.parametrize("shape", [(14, 14, 64, 96, 3, 1, 1), (15, 13, 64, 160, 3, 2, 1), (9, 9, 128, 40, 5, 1, 2),
                                    (16, 16, 128, 256, 1, 2, 0), (12, 12, 192, 300, 3, 1, 0), (20, 20, 64, 64, 3, 1, 1)],
                          ids=lambda s: "x".join(map(str, s)))
@@ -422,6 +424,66 @@ def test_qconv2d_forced_dma_tiles_match_oracle(force_tile, tile, shape):
     for z_x in (c["z_x"], 255):
         c["z_x"] = z_x
         _run_conv(c, f"conv tile={tile} {shape} z_x={z_x}")
+
+
+@pytest.mark.parametrize("tile,M,N,K", [("p128x256", 128 * 41 + 5, 256 * 14 + 9, 192), ("p256x128", 256 * 21 + 77, 128 * 27, 128),
+                                        ("dma256x256", 256 * 19, 256 * 15 + 1, 128), ("dma64x64", 64 * 37, 64 * 31, 64)])
+@pytest.mark.parametrize("prio", [0, 1, 2, 3])
+def test_qgemm_persistent_workgroups_walk_several_tiles(force_tile, tuning, tile, M, N, K, prio):
+    # more tiles than resident workgroups: with QNN_PERSIST every workgroup loops over several tiles
+    # (the operand ring and the output staging area are reused from tile to tile); every issue-priority
+    # scheme of the main loop must give the same bits
+    force_tile(tile)
+    tuning.setenv("QNN_PERSIST", "2" if tile.startswith("p") else "1")
+    tuning.setenv("QNN_GEMM_PRIO", str(prio))
+    rng = np.random.default_rng(1350 + M + N + K)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    bias, mult, shift = _gemm_params(rng, N, K)
+    want = oracle.qgemm(A, 91, Bt, mult, shift, 128, 0, 255, bias=bias)
+    got = host(qnn.qgemm(dev(A), 91, dev(Bt), dev(mult), dev(shift), 128, 0, 255, bias=dev(bias)))
+    assert_same(got, want, f"persistent qgemm tile={tile} {M}x{N}x{K} prio={prio}")
+
+
+def test_qconv2d_persistent_workgroups(force_tile, tuning):
+    force_tile("p256x128")
+    tuning.setenv("QNN_PERSIST", "2")
+    layer = workloads.Layer("t", "conv", 40, 40, 64, 128, k=3, stride=1, pad=1, act="relu")
+    c = synth.conv_case(layer, 96, 1377, oracle)  # 153600 rows = 600 tiles of 256 rows
+    _run_conv(c, "persistent conv p256x128")
+
+
+@pytest.mark.parametrize("tile", ["dma64x64", "dma128x128", "dma256x256", None])
+@pytest.mark.parametrize("M,N,K", [(128, 64, 64), (300, 270, 320), (1000, 520, 1088), (515, 96, 576), (2000, 40, 960)])
+def test_qgemm_packed_4bit_weights_on_the_pipelined_tiles(tuning, tile, M, N, K):
+    # nibble pairs go to LDS as they are and are expanded in registers after the fragment read;
+    # -8 and 7 injected, zero-points away from 128 so that the column sums matter
+    if tile:
+        tuning.setenv("QNN_FORCE_TILE", tile)
+    rng = np.random.default_rng(1360 + M + N + K)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    Bt = rng.integers(-8, 8, (N, K)).astype(np.int8)
+    Bt[0, :4] = (-8, 7, -8, 7)
+    Bt[N - 1, K - 2:] = (-8, -8)
+    B = oracle.pack_int4(Bt)
+    bias, mult, shift = _gemm_params(rng, N, K)
+    mult, shift = oracle.quantize_multipliers(10 ** rng.uniform(-3.2, -2.6, N) / np.sqrt(K / 64.0))
+    for z_a in (0, 128, 255):
+        want = oracle.qgemm(A, z_a, B, mult, shift, 128, 0, 255, bias=bias, weight_bits=4)
+        got = host(qnn.qgemm(dev(A), z_a, dev(B), dev(mult), dev(shift), 128, 0, 255, bias=dev(bias), weight_bits=4))
+        assert_same(got, want, f"int4 qgemm tile={tile} {M}x{N}x{K} z_a={z_a}")
+        assert len(np.unique(want)) > 32
+
+
+@pytest.mark.parametrize("tile", ["dma64x64", "dma128x128", "dma256x256"])
+@pytest.mark.parametrize("shape", [(14, 14, 64, 96, 3, 1, 1), (15, 13, 64, 160, 3, 2, 1), (12, 12, 192, 300, 3, 1, 0)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_qconv2d_packed_4bit_weights_on_the_pipelined_tiles(force_tile, tile, shape):
+    force_tile(tile)
+    H, W, Cin, Cout, k, s, p = shape
+    layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu", weight_bits=4)
+    c = synth.conv_case(layer, 3, 1460 + sum(shape), oracle)
+    _run_conv(c, f"int4 conv tile={tile} {shape}")
 
 
 # ------------------------------------------------------------ short reduction (K <= 256), weight-stationary kernel
@@ -510,8 +572,8 @@ def test_qconv2d_pointwise_short_k_matches_oracle(shape, bits):
 @pytest.mark.parametrize("M,N,K", [(4096, 128, 512), (5000, 200, 320), (4100, 64, 1024), (4096, 30, 288), (6000, 256, 1152),
                                    (4097, 97, 1280), (4500, 100, 352), (4300, 40, 736)])
 @pytest.mark.parametrize("bits", [8, 4])
-def test_qgemm_weight_resident_matches_oracle(monkeypatch, M, N, K, bits):
-    monkeypatch.setenv("QNN_BRES", "1")  # shapes this small take the kernel only on request
+def test_qgemm_weight_resident_matches_oracle(tuning, M, N, K, bits):
+    tuning.setenv("QNN_BRES", "1")  # shapes this small take the kernel only on request
     rng = np.random.default_rng(2400 + M + N + K + bits)
     A = rng.integers(0, 256, (M, K)).astype(np.uint8)
     if bits == 8:
@@ -536,8 +598,8 @@ def test_qgemm_weight_resident_default_plan():
     assert_same(got, want, "weight-resident qgemm 40000x128x512, default plan")
 
 
-def test_qgemm_weight_resident_general_rescale_and_many_column_groups(monkeypatch):
-    monkeypatch.setenv("QNN_BRES", "1")  # also for N > 256 (several column groups)
+def test_qgemm_weight_resident_general_rescale_and_many_column_groups(tuning):
+    tuning.setenv("QNN_BRES", "1")  # also for N > 256 (several column groups)
     M, N, K = 4200, 600, 384
     rng = np.random.default_rng(2500)
     A = rng.integers(0, 256, (M, K)).astype(np.uint8)
@@ -559,10 +621,10 @@ def test_qgemm_weight_resident_general_rescale_and_many_column_groups(monkeypatc
                                          ((64, 64, 512, 128, 1, 2, 0), 4), ((36, 36, 128, 130, 3, 1, 0), 4)],
                          ids=lambda s: "x".join(map(str, s)) if isinstance(s, tuple) else str(s))
 @pytest.mark.parametrize("bits", [8, 4])
-def test_qconv2d_weight_resident_matches_oracle(monkeypatch, shape, batch, bits):
+def test_qconv2d_weight_resident_matches_oracle(tuning, shape, batch, bits):
     H, W, Cin, Cout, k, s, p = shape
     layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu", weight_bits=bits)
-    monkeypatch.setenv("QNN_BRES", "1")
+    tuning.setenv("QNN_BRES", "1")
     c = synth.conv_case(layer, batch, 2600 + sum(shape) + bits, oracle)
     for z_x in (c["z_x"], 255):
         c["z_x"] = z_x
@@ -574,9 +636,9 @@ def test_qconv2d_weight_resident_matches_oracle(monkeypatch, shape, batch, bits)
 @pytest.mark.parametrize("tile", ["dma128x128", "dma64x64"])
 @pytest.mark.parametrize("splits", [2, 3, 7])
 @pytest.mark.parametrize("M,N,K", [(128, 128, 448), (300, 270, 640), (131, 66, 1088), (256, 63, 8192)])
-def test_qgemm_split_k_matches_oracle(force_tile, monkeypatch, tile, splits, M, N, K):
+def test_qgemm_split_k_matches_oracle(force_tile, tuning, tile, splits, M, N, K):
     force_tile(tile)
-    monkeypatch.setenv("QNN_FORCE_SPLIT", str(splits))
+    tuning.setenv("QNN_FORCE_SPLIT", str(splits))
     rng = np.random.default_rng(1600 + M + N + K + splits)
     A = rng.integers(0, 256, (M, K)).astype(np.uint8)
     Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
@@ -592,9 +654,9 @@ def test_qgemm_split_k_matches_oracle(force_tile, monkeypatch, tile, splits, M, 
 @pytest.mark.parametrize("tile", ["dma128x128", "dma64x64"])
 @pytest.mark.parametrize("shape", [(14, 14, 64, 96, 3, 1, 1), (9, 9, 128, 40, 5, 1, 2), (7, 7, 512, 130, 3, 1, 1)],
                          ids=lambda s: "x".join(map(str, s)))
-def test_qconv2d_split_k_matches_oracle(force_tile, monkeypatch, tile, shape):
+def test_qconv2d_split_k_matches_oracle(force_tile, tuning, tile, shape):
     force_tile(tile)
-    monkeypatch.setenv("QNN_FORCE_SPLIT", "4")
+    tuning.setenv("QNN_FORCE_SPLIT", "4")
     H, W, Cin, Cout, k, s, p = shape
     layer = workloads.Layer("t", "conv", H, W, Cin, Cout, k=k, stride=s, pad=p, act="relu6")
     c = synth.conv_case(layer, 3, 1700 + sum(shape), oracle)
@@ -725,7 +787,7 @@ def test_qdwconv2d_rectangular_geometry_matches_oracle(case):
 # ------------------------------------------------------------------ exact ties below the lower clamp
 
 @pytest.mark.parametrize("z_out,act_min,act_max", [(0, 0, 255), (7, 7, 130), (3, 10, 200), (40, 0, 255), (128, 5, 250)])
-def test_rounding_ties_next_to_the_lower_clamp(monkeypatch, z_out, act_min, act_max):
+def test_rounding_ties_next_to_the_lower_clamp(tuning, z_out, act_min, act_max):
     """Small accumulators with multipliers 2^30 and 3 * 2^29 and shifts 1..4: every second or fourth
     sum is an exact tie, negative ones included.  With act_min >= z_out the kernels drop the
     ties-away term for negative values (the clamp decides there); the result must not change."""
@@ -739,13 +801,13 @@ def test_rounding_ties_next_to_the_lower_clamp(monkeypatch, z_out, act_min, act_
         mult = np.where(rng.integers(0, 2, N) == 0, 1 << 30, 3 << 29).astype(np.int32)
         shift = rng.integers(1, 5, N).astype(np.int32)
         if tile:
-            monkeypatch.setenv("QNN_FORCE_TILE", tile)
+            tuning.setenv("QNN_FORCE_TILE", tile)
         else:
-            monkeypatch.delenv("QNN_FORCE_TILE", raising=False)
+            tuning.delenv("QNN_FORCE_TILE", raising=False)
         want = oracle.qgemm(A, z_a, Bt, mult, shift, z_out, act_min, act_max, bias=bias)
         got = host(qnn.qgemm(dev(A), z_a, dev(Bt), dev(mult), dev(shift), z_out, act_min, act_max, bias=dev(bias)))
         assert_same(got, want, f"ties {M}x{N}x{K} tile={tile} z_out={z_out} act=[{act_min},{act_max}] ({qnn.qgemm_plan(M, N, K)})")
-    monkeypatch.delenv("QNN_FORCE_TILE", raising=False)
+    tuning.delenv("QNN_FORCE_TILE", raising=False)
     # depthwise 3x3 and a stem-shaped convolution
     C = 32
     x = (z_a + rng.integers(-1, 2, (2, 12, 12, C))).astype(np.uint8)

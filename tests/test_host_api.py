@@ -95,7 +95,7 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     g = lambda **kw: lib.qnn_qgemm(*[kw.get(k, d) for k, d in [
         ("A", p), ("lda", 64), ("z_a", 128), ("B", p), ("ldb", 64), ("layout", 0), ("bits", 8), ("M", 8), ("N", 8),
         ("K", 64), ("bias", null), ("mult", p), ("shift", p), ("z_out", 0), ("lo", 0), ("hi", 255), ("C", p),
-        ("ldc", 8), ("stream", None)]])
+        ("ldc", 8), ("workspace", null), ("workspace_bytes", 0), ("stream", None)]])
     assert g(K=65537, lda=65537, ldb=65537) == EINVAL      # int32 accumulator bound
     assert g(bits=5) == EINVAL
     assert g(bits=4, K=63, lda=63) == EINVAL                # odd K with nibble pairs
@@ -107,7 +107,7 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     conv = lambda **kw: lib.qnn_qconv2d(*[kw.get(k, d) for k, d in [
         ("x", p), ("N", 1), ("H", 8), ("W", 8), ("Cin", 16), ("z_x", 0), ("w", p), ("Cout", 8), ("kh", 3), ("kw", 3),
         ("bits", 8), ("sh", 1), ("sw", 1), ("ph", 1), ("pw", 1), ("bias", null), ("mult", p), ("shift", p),
-        ("z_out", 0), ("lo", 0), ("hi", 255), ("y", p), ("stream", None)]])
+        ("z_out", 0), ("lo", 0), ("hi", 255), ("y", p), ("workspace", null), ("workspace_bytes", 0), ("stream", None)]])
     assert conv(kh=11, kw=11, ph=0, pw=0) == EINVAL          # kernel larger than the padded image
     assert conv(sh=0) == EINVAL
     assert conv(bits=4, Cin=15) == EINVAL
@@ -140,28 +140,63 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     assert lib.qnn_rescale_u8(p, 8, 300, 1 << 30, 1, 0, 0, 255, p, 8, 2, 8, None) == EINVAL
     assert lib.qnn_rescale_u8(null, 8, 0, 1 << 30, 1, 0, 0, 255, null, 8, 0, 8, None) == 0
     # asymmetric weights: the zero-point array is required, and K is limited to 32768
-    asym = lambda z_w=p, K=64: lib.qnn_qgemm_asym(p, K, 0, p, K, 0, 8, z_w, 64, 64, K, null, p, p, 0, 0, 255, p, 64, None)
+    asym = lambda z_w=p, K=64, ws=p, wsb=4096: lib.qnn_qgemm_asym(p, K, 0, p, K, 0, 8, z_w, 64, 64, K, null, p, p, 0, 0, 255,
+                                                                   p, 64, ws, wsb, None)
     assert asym(z_w=null) == EINVAL
     assert asym(K=32768 + 64) == EINVAL
-    assert lib.qnn_qconv2d_asym(p, 1, 8, 8, 16, 0, p, 8, 3, 3, 8, null, 1, 1, 1, 1, null, p, p, 0, 0, 255, p, None) == EINVAL
-    assert lib.qnn_qconv2d_asym(p, 1, 64, 64, 4096, 0, p, 8, 3, 3, 8, p, 1, 1, 1, 1, null, p, p, 0, 0, 255, p, None) == EINVAL
+    assert asym(ws=null, wsb=0) == EINVAL                    # the row sums need the caller's workspace
+    assert asym(wsb=64) == EINVAL                            # ... all of it
+    assert asym(ws=C.c_void_p(4100)) == EINVAL               # ... 16-byte aligned
+    assert lib.qnn_qgemm_workspace_bytes(64, 64, 64, 8, 1) == 256
+    assert lib.qnn_qconv2d_asym(p, 1, 8, 8, 16, 0, p, 8, 3, 3, 8, null, 1, 1, 1, 1, null, p, p, 0, 0, 255, p, p, 4096,
+                                None) == EINVAL
+    assert lib.qnn_qconv2d_asym(p, 1, 64, 64, 4096, 0, p, 8, 3, 3, 8, p, 1, 1, 1, 1, null, p, p, 0, 0, 255, p, p, 1 << 20,
+                                None) == EINVAL
     # the fused add: every field is checked on the host before anything is launched
     fields = dict(mult_m=1 << 30, shift_m=1, z_r=0, mult_r=1 << 30, shift_r=1, left_shift=20, mult_o=1 << 30, shift_o=10,
                   z_out=0, act_min=0, act_max=255)
     def gemm_add(residual=p, ldr=64, **kw):
         add = binding._AddParams(**{**fields, **kw})
         return lib.qnn_qgemm_add(p, 64, 0, p, 64, 0, 8, 64, 64, 64, null, p, p, 0, 0, 255, residual, ldr, C.addressof(add),
-                                 p, 64, None)
+                                 p, 64, null, 0, None)
     assert gemm_add(residual=null) == EINVAL
     assert gemm_add(ldr=8) == EINVAL
     assert gemm_add(left_shift=23) == EINVAL
     assert gemm_add(shift_o=32) == EINVAL
     assert gemm_add(z_r=256) == EINVAL
     assert gemm_add(act_min=9, act_max=3) == EINVAL
-    assert lib.qnn_qgemm_add(p, 64, 0, p, 64, 0, 8, 64, 64, 64, null, p, p, 0, 0, 255, p, 64, null, p, 64, None) == EINVAL
+    assert lib.qnn_qgemm_add(p, 64, 0, p, 64, 0, 8, 64, 64, 64, null, p, p, 0, 0, 255, p, 64, null, p, 64, null, 0,
+                             None) == EINVAL
     add = binding._AddParams(**fields)
     assert lib.qnn_qconv2d_add(p, 1, 8, 8, 16, 0, p, 8, 3, 3, 8, 1, 1, 1, 1, null, p, p, 0, 0, 255, null, C.addressof(add),
-                               p, None) == EINVAL
+                               p, null, 0, None) == EINVAL
+
+
+def test_workspace_queries_and_tuning_switches(lib):
+    # split-K shapes of the sweep ask for their partial sums; everything else for nothing
+    assert qnn.qgemm_workspace_bytes(8192, 8192, 8192) == 0
+    assert qnn.qgemm_workspace_bytes(1024, 1024, 8192) == 4 * 1024 * 1024 * 4 and qnn.qgemm_plan(1024, 1024, 8192).endswith("/k4")
+    assert qnn.qgemm_workspace_bytes(256, 256, 4096) == 4 * 256 * 256 * 4
+    assert qnn.qgemm_workspace_bytes(64, 4096, 4096) == 0 and qnn.qgemm_workspace_bytes(4096, 256, 256) == 0
+    assert qnn.qgemm_workspace_bytes(1024, 1024, 8192, weight_bits=4) == 0      # 4-bit weights run unsplit
+    assert qnn.qgemm_workspace_bytes(1000, 10, 100, asym=True) == 4096          # row sums, rounded up to 256 bytes
+    assert qnn.qconv2d_workspace_bytes(2, 7, 7, 512, 512, 3, 3, (1, 1), (1, 1)) == qnn.qgemm_workspace_bytes(98, 512, 4608)
+    assert qnn.qconv2d_workspace_bytes(0, 7, 7, 512, 512, 3, 3, (1, 1), (1, 1)) == 0
+    # switches: unknown names are rejected, known ones change the plan and can be restored
+    assert lib.qnn_tuning_set(b"QNN_NO_SUCH_SWITCH", b"1") == 1
+    assert lib.qnn_tuning_set(None, b"1") == 1
+    assert qnn.qgemm_plan(4096, 4096, 128) == "shortk"
+    qnn.tuning_set("QNN_NO_SHORTK", 1)
+    try:
+        assert qnn.qgemm_plan(4096, 4096, 128) != "shortk"
+        qnn.tuning_set("QNN_FORCE_TILE", "dma64x64")
+        qnn.tuning_set("QNN_FORCE_SPLIT", 3)
+        assert qnn.qgemm_plan(256, 256, 1024) == "dma64x64/k3"
+        assert qnn.qgemm_workspace_bytes(256, 256, 1024) == 3 * 256 * 256 * 4
+    finally:
+        for name in ("QNN_NO_SHORTK", "QNN_FORCE_TILE", "QNN_FORCE_SPLIT"):
+            qnn.tuning_set(name)
+    assert qnn.qgemm_plan(4096, 4096, 128) == "shortk"
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
