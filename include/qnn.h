@@ -118,6 +118,22 @@ qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, 
                      const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/* qnn_qgemm for callers that cannot allocate device memory and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and same
+ * result as qnn_qgemm; the scratch memory (partial sums of products whose K is divided over several
+ * workgroups) is a static 16 MiB device array inside the library, which every GPU the library runs on
+ * holds until the process ends.  The call allocates nothing.  A product whose plan asks for more than
+ * 16 MiB of scratch (qnn_qgemm_workspace_bytes) is rejected with QNN_EUNSUPPORTED and a message in
+ * qnn_last_error().  The array is shared by all calls on one GPU and keeps the last call's contents
+ * (every call writes what it reads, nothing needs clearing): calls that overlap on one GPU -- other
+ * streams, concurrent graph branches -- race on it; order them, or use qnn_qgemm with separate
+ * workspaces.  The device address of the array is looked up at the first call on each device (make
+ * that call outside stream capture). */
+qnn_status qnn_qgemm_noalloc(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
+                             int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
+                             const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
+                             void *stream);
+
 /* Scratch bytes that qnn_qgemm / qnn_qgemm_add (asym == 0) or qnn_qgemm_asym (asym != 0) can use for an
  * M x N x K product with weight_bits-bit weights, and the same for the convolution entry points
  * (Sec. 2.1 eq. 4-6: the partial sums are pieces of the same integer sum, so the result does not

@@ -23,7 +23,7 @@ EXPORTS = [
     "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_rescale_u8", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_qdwconv2d_asym", "qnn_minmax", "qnn_quantize_with",
     "qnn_quantize_dynamic", "qnn_simquant", "qnn_simquant_backward", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
     "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4", "qnn_qgemm_workspace_bytes", "qnn_qconv2d_workspace_bytes",
-    "qnn_tuning_set", "qnn_calibrate_mfma", "qnn_calibrate_copy",
+    "qnn_tuning_set", "qnn_calibrate_mfma", "qnn_calibrate_copy", "qnn_qgemm_noalloc",
 ]
 
 
@@ -58,6 +58,7 @@ def load_library():
         "qnn_dequantize": [vp, vp, sz, f32, i32, vp],
         "qnn_requantize": [vp, vp, sz, sz, vp, vp, ci, i32, i32, i32, vp],
         "qnn_qgemm": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, sz, vp],
+        "qnn_qgemm_noalloc": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
         "qnn_pack_b": [vp, i64, i64, i64, vp, i64, vp],
         "qnn_qconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp],
         "qnn_tuning_set": [C.c_char_p, C.c_char_p],
@@ -100,7 +101,7 @@ def load_library():
 
 def _check(name, rc):
     if rc != 0:
-        detail = load_library().qnn_last_error().decode() if rc == 3 else ""
+        detail = load_library().qnn_last_error().decode() if rc in (2, 3) else ""
         raise QnnError(name, rc, detail)
 
 
@@ -302,6 +303,25 @@ def qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, bias=None, weight_bit
         _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max,
         cp, ldc, wp, wbytes, _stream()))
     return Cm
+
+
+def qgemm_noalloc(A, z_a, B, mult, shift, z_out, act_min, act_max, out, bias=None, weight_bits=8):
+    """qnn_qgemm_noalloc: `qgemm` with columns-contiguous B into the caller's `out`, with the library's static
+    scratch array; neither this wrapper nor the library allocates."""
+    torch = _torch()
+    M, K = A.shape
+    if weight_bits == 4:
+        N, ldb, bp = B.shape[0], B.shape[1] * 2, _dev(B, torch.uint8, "B")
+    else:
+        (N, ldb), bp = B.shape, _dev(B, torch.int8, "B")
+    if tuple(out.shape) != (M, N):
+        raise ValueError(f"out has shape {tuple(out.shape)}, expected {(M, N)}")
+    ap, lda = _dev_rows(A, torch.uint8, "A")
+    cp, ldc = _dev_rows(out, torch.uint8, "C")
+    _check("qnn_qgemm_noalloc", load_library().qnn_qgemm_noalloc(
+        ap, lda, z_a, bp, ldb, B_COLUMNS_CONTIGUOUS, weight_bits, M, N, K, _dev(bias, torch.int32, "bias"),
+        _dev(mult, torch.int32, "mult"), _dev(shift, torch.int32, "shift"), z_out, act_min, act_max, cp, ldc, _stream()))
+    return out
 
 
 def prepare_qgemm(A, z_a, B, mult, shift, z_out, act_min, act_max, out, bias=None, weight_bits=8,

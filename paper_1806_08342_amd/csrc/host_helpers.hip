@@ -60,6 +60,8 @@ Tuning &tuning()
     return t;
 }
 
+void set_last_error(const char *text) { std::snprintf(g_last_error, sizeof(g_last_error), "%s", text); }
+
 // nearest integer, halves go away from zero
 static double nearest_away(double v) { return std::copysign(std::floor(std::fabs(v) + 0.5), v); }
 

@@ -321,6 +321,33 @@ static int pick_vec(int64_t k_like, std::initializer_list<const void *> ptrs, st
     return 1;
 }
 
+// Scratch memory of qnn_qgemm_noalloc: a fixed device array that is part of the library's code object,
+// so that the entry point never allocates.  Every GPU the library runs on holds its own copy at its
+// own address; the array's name is only a host-side handle, the device address comes from
+// hipGetSymbolAddress (once per device, with that device current) and is what the kernels get.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static qnn_status static_scratch(void **out)
+{
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return launch_status(e);
+    if (dev < 0 || dev >= kMaxDevices) return QNN_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)); e != hipSuccess) return launch_status(e);
+        if (!ptr) return QNN_ELAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return QNN_OK;
+}
+
 } // namespace qnn
 
 using namespace qnn;
@@ -467,6 +494,26 @@ qnn_status qnn_qgemm(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, 
 {
     return qgemm_impl(A, lda, z_a, B, ldb, b_layout, weight_bits, M, N, K, bias, mult, shift, z_out, act_min, act_max, C,
                       ldc, workspace, workspace_bytes, stream, nullptr, 0, nullptr);
+}
+
+qnn_status qnn_qgemm_noalloc(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,
+                             int weight_bits, int64_t M, int64_t N, int64_t K, const int32_t *bias, const int32_t *mult,
+                             const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *C, int64_t ldc,
+                             void *stream)
+{
+    const size_t need = workspace_bytes_for(M, N, K, weight_bits, false);
+    if (need > kStaticScratchBytes) {
+        char text[160];
+        std::snprintf(text, sizeof text, "qnn_qgemm_noalloc: this product asks for %zu bytes of scratch, the static array holds %zu",
+                      need, kStaticScratchBytes);
+        set_last_error(text);
+        return QNN_EUNSUPPORTED;
+    }
+    void *ptr = nullptr;
+    if (need > 0)
+        if (qnn_status st = static_scratch(&ptr); st != QNN_OK) return st;
+    return qgemm_impl(A, lda, z_a, B, ldb, b_layout, weight_bits, M, N, K, bias, mult, shift, z_out, act_min, act_max, C,
+                      ldc, ptr, need, stream, nullptr, 0, nullptr);
 }
 
 qnn_status qnn_qgemm_add(const uint8_t *A, int64_t lda, int32_t z_a, const void *B, int64_t ldb, int b_layout,

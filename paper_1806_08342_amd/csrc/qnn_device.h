@@ -11,6 +11,8 @@ namespace qnn {
 
 // records the HIP error text for qnn_last_error() and maps it to QNN_ELAUNCH
 qnn_status launch_status(hipError_t e);
+// text that qnn_last_error() returns on this thread until the next failing call
+void set_last_error(const char *text);
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
