@@ -329,6 +329,291 @@ __global__ void __launch_bounds__(256) dwconv3x3_dot_kernel(const DwArgs g)
     else finish(std::integral_constant<int, 2>{}); // act_min >= z_out: the clamp absorbs the tie term
 }
 
+// Depthwise 3x3 with the multiplies on the matrix unit.
+//
+// The layer moves 2-5 bytes per output, and on the vector ALU it costs about 16 instructions per
+// output byte (the dot products need pixels in the bytes of a dword while NHWC puts channels there,
+// so every input byte goes through byte permutes first): the vector ALU, not HBM, sets the pace.
+// v_mfma_i32_32x32x32_i8 takes the transposition away.  For a block of 32 channels and one kernel tap,
+//   D[pixel][c] += sum_c' A[pixel][c'] * B[c'][c],   B[c'][c] = w[tap][c] if c' == c else 0
+// is that tap's contribution to 32 pixels x 32 channels.  A's fragment is what NHWC memory holds:
+// lane (pixel, half) takes the 16 contiguous channel bytes of its pixel -- no byte shuffling at all;
+// B's fragment is a diagonal matrix built once per wave from the weights.  The unit runs at 1/32
+// of its density and that is fine: nine of these instructions per output row of a wave take fewer
+// issue cycles than the rescale of the same outputs, and they run beside it.  The layer stays
+// HBM-bound and is graded against HBM; the matrix unit only replaces the byte transposition.
+//
+// A wave owns TP = 30 output pixels of one image row x 32 channels and walks down a segment of output
+// rows.  Its input rows -- 32 pixels (stride 1) or 64 pixels (stride 2) x 32 channel bytes, one or
+// two 1 KB copies -- go straight from global memory into a ring of LDS rows that belongs to the wave
+// alone (global_load_lds_dwordx4, RING - 1 rows ahead of the row in use; no barrier anywhere: waves
+// share nothing).  A row is read back three times as fragments (window columns 0, 1, 2 = the same
+// pixels shifted by one); it is kernel row 0, 1 and 2 of three consecutive output rows (stride 1;
+// stride 2: two rows per output row, the odd one shared), whose accumulators form a ring of their
+// own.  An output row that has received its last kernel row is rescaled (all 16 values of a lane
+// belong to ONE channel, so the constants are per lane), its bytes are transposed across the four
+// lanes of a quad into NHWC order and stored.  acc starts at bias + (128 - z_x) * sum(w); codes are
+// offset by 128 (xor) to be signed; taps outside the image hold the code z_x.
+//
+// vmcnt bookkeeping: every wave issues exactly DPW copies per input row, rows
+// past the end of the segment repeat the last one, "at most (RING - 2) x DPW outstanding" means
+// the oldest row has landed, and the output stores can only make that wait stricter.
+using dw_i32x4 = int32_t __attribute__((ext_vector_type(4)));
+using dw_i32x16 = int32_t __attribute__((ext_vector_type(16)));
+
+template <int S, int MODE>
+__global__ void __launch_bounds__(256, 3) dwconv3x3_mfma_kernel(const DwArgs g, const int seg_rows, const int tiles_w,
+                                                                const int cblocks)
+{
+    constexpr int SLOTS = S == 1 ? 3 : 2, TP = 30, DPW = S, ROW_BYTES = DPW * 1024, RING = S == 1 ? 12 : 8, D = RING - 1;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[4 * RING * ROW_BYTES];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int wave_lin = blockIdx.x * 4 + wave; // scalar
+    const int tile_w = wave_lin / cblocks, cblk = wave_lin - tile_w * cblocks;
+    if (tile_w >= tiles_w) return; // whole wave; waves share nothing
+    uint8_t *const ring = lds + wave * (RING * ROW_BYTES);
+    const int n = blockIdx.z;
+    const int hb = blockIdx.y * seg_rows;
+    const int rows = (g.Ho - hb) < seg_rows ? (g.Ho - hb) : seg_rows;
+    const int li = lane & 31, half = lane >> 5;
+    const int w0 = tile_w * TP;
+
+    // ---- input rows: copy j of a row moves, per lane, 16 channel bytes of pixel wi0 + (j * 64 + lane) / 2
+    // (clamped into the image row; pixels outside are replaced after the read-back) to LDS offset
+    // (j * 64 + lane) * 16, i.e. an LDS row is [pixel][32 channel bytes]
+    const int wi0 = w0 * S - g.pw;
+    const int64_t row_bytes = (int64_t)g.W * g.C;
+    const uint8_t *img = g.x + (int64_t)n * g.H * row_bytes;    // scalar
+    uint32_t src_off[DPW];
+#pragma unroll
+    for (int j = 0; j < DPW; ++j) {
+        int wi = wi0 + ((j * 64 + lane) >> 1);
+        wi = wi < 0 ? 0 : (wi >= g.W ? g.W - 1 : wi);
+        int c16 = cblk * 32 + 16 * (lane & 1);
+        c16 = c16 + 16 <= g.C ? c16 : g.C - 16; // blocks that stick out of C: any valid bytes (B is zero there)
+        src_off[j] = (uint32_t)(wi * g.C + c16);
+    }
+    // ---- the row pipeline: input row t of the segment is image row hi_first + t, t = 0 .. steps - 1
+    const int hi_first = hb * S - g.ph;
+    const int steps = S == 1 ? rows + 2 : 2 * rows + 1;
+    int issue_t = 0, issue_slot = 0; // next row to copy and the ring row it goes to (scalar)
+    int read_t = 0, read_slot = 0;   // next row to consume
+    auto issue_row = [&]() {
+        const int t = issue_t < steps ? issue_t : steps - 1; // past the end: repeat the last row (nobody reads that ring row)
+        int hi = hi_first + t;
+        hi = hi < 0 ? 0 : (hi >= g.H ? g.H - 1 : hi);        // rows outside the image: any row inside (replaced by the padding code)
+        const uint8_t *line = img + (int64_t)hi * row_bytes;
+        uint8_t *dst = ring + issue_slot * ROW_BYTES;
+#pragma unroll
+        for (int j = 0; j < DPW; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(line + src_off[j]),
+                                             (__attribute__((address_space(3))) void *)(dst + j * 1024), 16, 0, 0);
+        ++issue_t;
+        issue_slot = issue_slot + 1 == RING ? 0 : issue_slot + 1;
+    };
+    for (int d = 0; d < D; ++d) issue_row(); // D rows in flight before anything else: their latency covers the set-up below
+
+    // ---- B fragments: the diagonal of tap (a, b) for the channels of this block.  Lane (column li, half)
+    // holds rows k = 16 half .. 16 half + 15 of column li: only row k = li is non-zero.
+    const int ch = cblk * 32 + li;                  // the channel this lane accumulates and rescales
+    const bool ch_ok = ch < g.C;
+    const bool diag_here = ch_ok && (li >> 4) == half;
+    dw_i32x4 wq[3][3];
+    int32_t wsum = 0;
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            const int32_t w = ch_ok ? (int32_t)g.w[(a * 3 + b) * g.C + ch] : 0;
+            wsum += w;
+            const uint32_t placed = diag_here ? ((uint32_t)(w & 0xff) << (8 * (li & 3))) : 0u;
+            const int d = (li >> 2) & 3;
+            wq[a][b] = dw_i32x4{d == 0 ? (int32_t)placed : 0, d == 1 ? (int32_t)placed : 0, d == 2 ? (int32_t)placed : 0,
+                                d == 3 ? (int32_t)placed : 0};
+        }
+    const int32_t bias = (ch_ok && g.bias) ? g.bias[ch] : 0;
+    const int32_t init = bias + (128 - g.z_x) * wsum;
+
+    // ---- epilogue constants of this lane's channel (see rescale_fused_w)
+    const int32_t mu = ch_ok ? g.mult[ch] : 0, sf = ch_ok ? g.shift[ch] : 1;
+    const bool fused_ok = sf >= 1 && sf <= 20 && bias > -(1 << 28) && bias < (1 << 28);
+    const int nn = (sf >= 1 && sf <= 20) ? sf : 1;
+    const int32_t n1 = nn + 1;
+    const int32_t cc = 2 * ((1 << (nn - 1)) + (g.z_out << nn)) + 1;
+    const int32_t lo = (g.lo_rel + g.z_out) << (nn + 1);
+    const int32_t hi_ = ((g.hi_rel + g.z_out + 1) << (nn + 1)) - 1;
+    const bool fused = MODE != 0 && __all(fused_ok); // wave-uniform
+
+    // read-back of window column b: pixel li * S + b of the LDS row, 16 channel bytes of this lane's half
+    uint32_t l_off[3];
+    bool a_ok[3], all_ok = true;
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        const int wi = wi0 + li * S + b;
+        a_ok[b] = wi >= 0 && wi < g.W;
+        all_ok = all_ok && a_ok[b];
+        const int lp = li < TP ? li : TP - 1; // lanes 30, 31 own no output pixel: they re-read the last one, inside the row
+        l_off[b] = (uint32_t)((lp * S + b) * 32 + 16 * half);
+    }
+    const bool wave_interior = __all(all_ok);
+    const int32_t fill_s = (int32_t)(((uint32_t)g.z_x * 0x01010101u) ^ 0x80808080u);
+
+    // ---- output addressing: after the quad transposition lane (li, half) stores, for q = 0..3, the 4 channels
+    // (li & ~3) .. + 3 of pixel w0 + 8q + 4 half + (li & 3)
+    const int quad_lane = li & 3;
+    const uint32_t sel1 = (quad_lane & 1) ? 0x03070105u : 0x06020400u;
+    const uint32_t sel2 = (quad_lane & 2) ? 0x03020706u : 0x05040100u;
+    const int64_t out_row_bytes = (int64_t)g.Wo * g.C;
+    int64_t out_row = ((int64_t)n * g.Ho + hb) * out_row_bytes; // scalar: byte offset of the output row that finishes next
+    const int out_c = cblk * 32 + (li & ~3);
+    uint32_t o_off[4];
+    bool o_ok[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int p = 8 * q + 4 * half + quad_lane; // pixel of the tile
+        const int wo = w0 + p;
+        o_ok[q] = p < TP && wo < g.Wo && out_c < g.C;
+        o_off[q] = (uint32_t)((o_ok[q] ? wo : 0) * g.C + (out_c < g.C ? out_c : 0));
+    }
+
+    // accumulators start at zero (an inline constant of the matrix instruction); bias and zero-point term join in
+    // the rescale, inside the add-and-shift that the 32-bit form needs anyway
+    dw_i32x16 acc[SLOTS];
+    auto reset = [&](int slot) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[slot][r] = 0;
+    };
+    auto finish = [&](int slot) {
+        // wave-uniform row base (scalar registers) + 32-bit lane offsets
+        const int64_t row_off = ((int64_t)__builtin_amdgcn_readfirstlane((int)(out_row >> 32)) << 32) |
+                                (uint32_t)__builtin_amdgcn_readfirstlane((int)out_row);
+        uint8_t *out = g.y + row_off;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t x = 0;
+            if (fused && MODE == 2) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int32_t tt = __mulhi((int32_t)(((uint32_t)acc[slot][4 * q + e] + (uint32_t)init) << 2), mu);
+                    x = shift_into_byte(x, med3_i32(fused_w_from_t<false>(tt, cc), lo, hi_), n1, e);
+                }
+            } else if (fused && MODE == 1) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int32_t tt = __mulhi((int32_t)(((uint32_t)acc[slot][4 * q + e] + (uint32_t)init) << 2), mu);
+                    x = shift_into_byte(x, med3_i32(fused_w_from_t<true>(tt, cc), lo, hi_), n1, e);
+                }
+            } else {
+                const RescaleParams rp = make_rescale(mu, sf);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int32_t y = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(acc[slot][4 * q + e] + init, rp)) + g.z_out;
+                    x |= (uint32_t)y << (8 * e);
+                }
+            }
+            // 4 pixels of one channel -> 4 channels of one pixel, across the quad (two exchanges + byte permutes)
+            uint32_t o = (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);
+            x = __builtin_amdgcn_perm(o, x, sel1);
+            o = (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true);
+            x = __builtin_amdgcn_perm(o, x, sel2);
+            if (o_ok[q]) *reinterpret_cast<uint32_t *>(out + o_off[q]) = x;
+        }
+        out_row += out_row_bytes;
+    };
+
+    dw_i32x4 fa[3], fn[3];
+    // requests the LDS read-back of input row read_t into fn (after its copy has landed) and the copy of row read_t + D
+    auto fetch_row = [&]() {
+        __builtin_amdgcn_s_waitcnt((((D - 1) * DPW) & 15) | ((((D - 1) * DPW) >> 4) << 14) | (7 << 4) | (15 << 8)); // vmcnt only
+        asm volatile("" ::: "memory");
+        const uint8_t *src = ring + read_slot * ROW_BYTES;
+#pragma unroll
+        for (int b = 0; b < 3; ++b) fn[b] = *reinterpret_cast<const dw_i32x4 *>(src + l_off[b]);
+        asm volatile("" ::: "memory");
+        issue_row(); // into the ring row that was consumed one step ago
+    };
+    // fn (raw codes of row read_t) -> fa (signed, padding replaced)
+    auto take_row = [&]() {
+        const int hi = hi_first + read_t;
+        const bool row_ok = hi >= 0 && hi < g.H; // scalar
+        if (!row_ok) {
+#pragma unroll
+            for (int b = 0; b < 3; ++b) fa[b] = dw_i32x4{fill_s, fill_s, fill_s, fill_s};
+        } else if (wave_interior) { // the common case: twelve xors
+#pragma unroll
+            for (int b = 0; b < 3; ++b) fa[b] = fn[b] ^ (int32_t)0x80808080; // signed (code - 128)
+        } else {
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                const dw_i32x4 t = fn[b] ^ (int32_t)0x80808080;
+                const bool ok = a_ok[b];
+                fa[b] = dw_i32x4{ok ? t.x : fill_s, ok ? t.y : fill_s, ok ? t.z : fill_s, ok ? t.w : fill_s};
+            }
+        }
+        ++read_t;
+        read_slot = read_slot + 1 == RING ? 0 : read_slot + 1;
+    };
+    // one window column of the current row into one accumulator set (the caller interleaves the sets, so that
+    // consecutive matrix instructions do not depend on each other)
+    auto mac1 = [&](int a, int b, int slot) {
+        acc[slot] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[b], wq[a][b], acc[slot], 0, 0, 0);
+    };
+
+    if constexpr (S == 1) {
+        // row t is kernel row 0 of output k = t, kernel row 1 of k = t - 1, kernel row 2 of k = t - 2; output k lives
+        // in accumulator set k % 3
+        for (int t0 = 0; t0 < steps; t0 += 3) {
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                const int t = t0 + u;
+                if (t >= steps) break; // scalar
+                fetch_row();
+                take_row();
+                const bool has0 = t < rows, has1 = t >= 1 && t - 1 < rows, has2 = t >= 2; // scalar
+                if (has0) reset(u);
+#pragma unroll
+                for (int b = 0; b < 3; ++b) {
+                    if (has2) mac1(2, b, (u + 1) % 3);
+                    if (has1) mac1(1, b, (u + 2) % 3);
+                    if (has0) mac1(0, b, u);
+                }
+                if (has2) finish((u + 1) % 3);
+            }
+        }
+    } else {
+        // output k uses rows 2k, 2k + 1, 2k + 2 of the segment; row 2k + 2 is also the first row of output k + 1;
+        // output k lives in accumulator set k % 2
+        fetch_row();
+        take_row();
+        reset(0);
+#pragma unroll
+        for (int b = 0; b < 3; ++b) mac1(0, b, 0);
+        for (int k0 = 0; k0 < rows; k0 += 2) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int k = k0 + u;
+                if (k >= rows) break; // scalar
+                fetch_row();
+                take_row();
+#pragma unroll
+                for (int b = 0; b < 3; ++b) mac1(1, b, u);
+                fetch_row();
+                take_row();
+                const bool more = k + 1 < rows; // scalar
+                if (more) reset(u ^ 1);
+#pragma unroll
+                for (int b = 0; b < 3; ++b) {
+                    mac1(2, b, u);
+                    if (more) mac1(0, b, u ^ 1);
+                }
+                finish(u);
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); // vmcnt(0): no copy may land in LDS after the wave is gone
+}
+
 // any kernel size / stride / channel count: one lane per output element
 __global__ void __launch_bounds__(256) dwconv_generic_kernel(const DwArgs g)
 {
@@ -404,6 +689,35 @@ static qnn_status qdwconv2d_impl(const uint8_t *x, int N, int H, int W, int C, i
         while ((1u << l) < d) ++l;
         g.shift_cgroups = l > 0 ? l - 1 : 0;
         g.magic_cgroups = d > 1 ? (uint32_t)((((uint64_t)1 << (31 + l)) + d - 1) / d) : 0u;
+        const int variant = tuning().dw_variant; // tuning aid: 0 = patch kernel, 3 = matrix-unit kernel, -1 = by shape
+        // matrix-unit kernel: whole 16-byte channel chunks, rows of at least 24 outputs (narrower images waste
+        // most of the 32-pixel tile and stay with the patch kernel)
+        if ((variant == 3 || variant < 0) && (C % 16) == 0 && (reinterpret_cast<uintptr_t>(x) % 16) == 0 &&
+            (int64_t)H * W * C < (1ll << 31) && (int64_t)g.Ho * g.Wo * C < (1ll << 31) &&
+            // measured: ahead of the patch kernel on wide stride-2 layers (+8 % at 112 x 112) and once a launch has
+            // more than ~10^8 outputs (+25 %: 0.40 against 0.32 of HBM); behind it on the small layers, whose waves
+            // are too few and too short-lived for the row pipeline to pay off
+            (variant == 3 || (stride_h == 2 && g.Wo >= 48) || (int64_t)N * g.Ho * g.Wo * C >= (100ll << 20))) {
+            const int tiles_w = (g.Wo + 29) / 30, cblocks = (C + 31) / 32; // 30 output pixels per wave
+            const int64_t waves_x = (int64_t)tiles_w * cblocks;
+            int seg_rows = tuning().dw_rh > 0 ? tuning().dw_rh : 0;
+            if (seg_rows <= 0) {
+                const int64_t target = 2048; // waves: 2 per SIMD of the chip
+                int64_t segs = (target + waves_x * N - 1) / (waves_x * N);
+                const int64_t most = (g.Ho + 7) / 8; // at least 8 output rows per segment (each re-reads 2 input rows)
+                segs = segs < 1 ? 1 : (segs > most ? most : segs);
+                seg_rows = (int)((g.Ho + segs - 1) / segs);
+            }
+            if (seg_rows > g.Ho) seg_rows = g.Ho;
+            const int segs = (g.Ho + seg_rows - 1) / seg_rows;
+            const dim3 grid((unsigned)((waves_x + 3) / 4), (unsigned)segs, (unsigned)N);
+            const int mode = g.lo_rel >= 0 ? 2 : 1;
+            if (stride_h == 1 && mode == 2) hipLaunchKernelGGL((dwconv3x3_mfma_kernel<1, 2>), grid, dim3(256), 0, s, g, seg_rows, tiles_w, cblocks);
+            else if (stride_h == 1) hipLaunchKernelGGL((dwconv3x3_mfma_kernel<1, 1>), grid, dim3(256), 0, s, g, seg_rows, tiles_w, cblocks);
+            else if (mode == 2) hipLaunchKernelGGL((dwconv3x3_mfma_kernel<2, 2>), grid, dim3(256), 0, s, g, seg_rows, tiles_w, cblocks);
+            else hipLaunchKernelGGL((dwconv3x3_mfma_kernel<2, 1>), grid, dim3(256), 0, s, g, seg_rows, tiles_w, cblocks);
+            return launch_status(hipGetLastError());
+        }
         // taller patches (4 output rows per lane) reuse more of the window, but need enough lanes to
         // give the chip something to do (tiny layers keep 2-row patches: twice the lanes)
         const int tall_env = tuning().dw_rh; // tuning aid: 2 or 4 forces the patch height

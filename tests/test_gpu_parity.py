@@ -375,6 +375,7 @@ def test_qdwconv2d_every_3x3_variant_matches_oracle(tuning, variant, shape):
     # patch heights 2 and 4 of the dot-product kernel and the multiply-add kernel, forced by environment
     name, value = variant.split("=")
     tuning.setenv(name, value)
+    tuning.setenv("QNN_DW_VARIANT", "0")  # the patch kernels (the rolling-window kernels have a test of their own)
     H, W, C, k, s, p = shape
     layer = workloads.Layer("t", "dw", H, W, C, C, k=k, stride=s, pad=p, act="relu6")
     c = synth.conv_case(layer, 3, 1250 + sum(shape), oracle)
@@ -384,6 +385,29 @@ def test_qdwconv2d_every_3x3_variant_matches_oracle(tuning, variant, shape):
         got = host(qnn.qdwconv2d(dev(c["x"]), z_x, dev(c["w"]), c["stride"], c["pad"], dev(c["mult"]), dev(c["shift"]),
                                  c["z_out"], c["act_min"], c["act_max"], bias=dev(c["bias"])))
         assert_same(got, want, f"dwconv {variant} {shape} z_x={z_x}")
+
+
+@pytest.mark.parametrize("variant,seg_rows", [(0, 0), (3, 0), (3, 1), (3, 2), (3, 5), (3, 9)])
+@pytest.mark.parametrize("shape", [(12, 12, 32, 1, 1), (12, 12, 32, 2, 1), (7, 7, 64, 1, 1), (30, 17, 16, 1, 1), (29, 31, 96, 2, 1),
+                                   (23, 45, 144, 1, 1), (9, 140, 32, 1, 1), (10, 150, 32, 2, 1), (17, 6, 512, 1, 1), (16, 9, 1024, 2, 1),
+                                   (8, 8, 48, 1, 0), (11, 13, 80, 2, 0), (5, 40, 64, 1, 2), (3, 3, 16, 1, 1), (28, 28, 576, 1, 1)],
+                         ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("act", ["relu6", "none"])
+def test_qdwconv2d_rolling_window_kernel_matches_oracle(tuning, variant, seg_rows, shape, act):
+    # variant 0: patch kernel, 3: matrix-unit kernel with the window rolling down a segment of rows;
+    # seg_rows forces short segments (many segment borders, rings that wrap, segments of one row)
+    tuning.setenv("QNN_DW_VARIANT", str(variant))
+    if seg_rows:
+        tuning.setenv("QNN_DW_RH", str(seg_rows))
+    H, W, C, s, p = shape
+    layer = workloads.Layer("t", "dw", H, W, C, C, k=3, stride=s, pad=p, act=act)
+    c = synth.conv_case(layer, 2, 1270 + sum(shape), oracle)
+    for z_x in (c["z_x"], 255):
+        want = oracle.qdwconv2d(c["x"], z_x, c["w"], c["stride"], c["pad"], c["mult"], c["shift"], c["z_out"],
+                                c["act_min"], c["act_max"], bias=c["bias"])
+        got = host(qnn.qdwconv2d(dev(c["x"]), z_x, dev(c["w"]), c["stride"], c["pad"], dev(c["mult"]), dev(c["shift"]),
+                                 c["z_out"], c["act_min"], c["act_max"], bias=dev(c["bias"])))
+        assert_same(got, want, f"dwconv variant {variant} seg {seg_rows} {shape} {act} z_x={z_x}")
 
 
 # ------------------------------------------------ pipelined (LDS-DMA) tile configurations
