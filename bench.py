@@ -128,9 +128,9 @@ def time_gemm_sweep(torch, cases, steps, warmup, eager=False, streams=4):
     launches of a pass (the library calls are captured from the stream they run on), so that the short
     products are timed at GPU speed and not at the speed of the Python launch loop; with eager=True the
     launches are issued one by one instead.  The products of a pass are independent problems, so the
-    graph spreads them round-robin over `streams` streams of equal (default) priority that fork from and
-    join the capturing stream: short products then overlap with long ones instead of each paying a full
-    launch-to-launch latency."""
+    graph spreads the short ones round-robin over `streams` streams of equal (default) priority that fork from
+    and join the capturing stream, so that they overlap instead of each paying a full launch-to-launch
+    latency; the products whose kernels occupy the whole chip follow one after another."""
     for _ in range(warmup):
         for c in cases:
             c["launch"]()
@@ -143,17 +143,24 @@ def time_gemm_sweep(torch, cases, steps, warmup, eager=False, streams=4):
         torch.cuda.synchronize()
         return time.perf_counter() - t0
     side = [torch.cuda.Stream() for _ in range(max(streams, 1) - 1)]
+    # products whose kernel fills every CU with resident workgroups (the large pipelined tiles) gain nothing
+    # from company: they run one after another.  The others -- launch-latency-bound or small -- overlap with
+    # each other on all streams first.
+    big = [c for c in cases if c["plan"] in ("dma256x256", "dma256x128")]
+    small = [c for c in cases if c["plan"] not in ("dma256x256", "dma256x128")]
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         main = torch.cuda.current_stream()
         for st in side:
             st.wait_stream(main)
         lanes = [main] + side
-        for k, c in enumerate(cases):
+        for k, c in enumerate(small):
             with torch.cuda.stream(lanes[k % len(lanes)]):
                 c["launch"]()
         for st in side:
             main.wait_stream(st)
+        for c in big:
+            c["launch"]()
     graph.replay()  # untimed: first replay uploads the graph
     torch.cuda.synchronize()
     t0 = time.perf_counter()

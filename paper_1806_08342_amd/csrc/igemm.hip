@@ -76,13 +76,17 @@ static Plan choose_plan(int64_t M, int64_t N, int64_t K, bool dma_ok, bool int4,
             // pick the configuration with the least padded work: whole waves of workgroups over the
             // chip, weighted by the measured relative MFMA rate of each configuration
             struct Cand { TileConfig t; int per_cu; double rate; };
+            // (the 4-wave 256x128 tile, two workgroups per CU: only for a single column of tiles and many rounds --
+            // the 3x3 convolutions over 128 channels -- where one workgroup's epilogue runs under the other's loop)
             static const Cand cands[] = {{TILE_DMA_256x256, 1, 1.00}, {TILE_DMA_256x128, 1, 0.88},
-                                         {TILE_DMA_128x128, 2, 0.72}, {TILE_DMA_256x64, 2, 0.60}};
+                                         {TILE_DMA_128x128, 2, 0.72}, {TILE_DMA_256x64, 2, 0.60},
+                                         {TILE_DMA_256x128_P, 2, 1.00}};
             double best = 0.0;
             TileConfig pick = TILE_COUNT;
             for (const Cand &c : cands) {
                 const int bm = kTileM[c.t], bn = kTileN[c.t];
                 if (N < bn / 2 || M < bm / 2) continue; // mostly empty tiles
+                if (c.t == TILE_DMA_256x128_P && (N > 128 || M < 512 * 256)) continue;
                 const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
                 if (tiles < 160) continue; // would leave too many CUs idle: smaller tiles are better then
                 const int64_t slots = 256 * c.per_cu;
@@ -295,8 +299,8 @@ static qnn_status run_igemm(IgemmArgs &g, int a_mode, int b_mode, int vec, void 
         return launch_status(mat ? launch_dma<128, 256, 2, 2, A_MATRIX, 3, false, false, false, 2>(g, s, one, 2, 2)
                                  : launch_dma<128, 256, 2, 2, A_CONV, 3, false, false, false, 2>(g, s, one, 2, 2));
     case TILE_DMA_256x128_P:
-        return launch_status(mat ? launch_dma<256, 128, 2, 2, A_MATRIX, 3, false, false, false, 2>(g, s, one, 2, 2)
-                                 : launch_dma<256, 128, 2, 2, A_CONV, 3, false, false, false, 2>(g, s, one, 2, 2));
+        return launch_status(mat ? launch_dma<256, 128, 2, 2, A_MATRIX, 3, false, false, false, 2>(g, s, one, 0, 0)
+                                 : launch_dma<256, 128, 2, 2, A_CONV, 3, false, false, false, 2>(g, s, one, 0, 0));
     case TILE_DMA_256x256_W4:
         return launch_status(mat ? launch_dma<256, 256, 2, 2, A_MATRIX, 4>(g, s) : launch_dma<256, 256, 2, 2, A_CONV, 4>(g, s));
     default:

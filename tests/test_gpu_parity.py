@@ -675,6 +675,43 @@ def test_qgemm_split_k_matches_oracle(force_tile, tuning, tile, splits, M, N, K)
         assert_same(got, want, f"split-K qgemm tile={tile} splits={splits} {M}x{N}x{K} z_a={z_a}")
 
 
+def test_two_captured_split_k_graphs_replayed_concurrently_with_their_own_workspaces():
+    # Scratch memory comes from the caller, so two products that both divide K over several workgroups can be
+    # captured into graphs and replayed at the same time on two streams, each with its own workspace; replayed
+    # several times with eager work in between, every replay is compared with the oracle
+    import torch
+    shapes = [(1024, 1024, 8192, 61), (256, 640, 4096, 62)]
+    cases, graphs, streams = [], [], [torch.cuda.Stream(), torch.cuda.Stream()]
+    for (M, N, K, seed), st in zip(shapes, streams):
+        assert "/k" in qnn.qgemm_plan(M, N, K)
+        c = synth.gemm_case(M, N, K, workloads.seed_for(2, seed), oracle)
+        t = dict(A=dev(c["A"]), Bt=dev(c["Bt"]), mult=dev(c["mult"]), shift=dev(c["shift"]),
+                 C=torch.zeros((M, N), dtype=torch.uint8, device="cuda:0"),
+                 ws=torch.empty(qnn.qgemm_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda:0"))
+        rows = np.r_[0:16, M - 16:M]
+        want = oracle.qgemm(c["A"][rows], c["z_a"], c["Bt"], c["mult"], c["shift"], c["z_out"], 0, 255)
+        cases.append((c, t, rows, want))
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(st):
+            qnn.qgemm(t["A"], c["z_a"], t["Bt"], t["mult"], t["shift"], c["z_out"], 0, 255, out=t["C"], workspace=t["ws"])  # warm-up
+            st.synchronize()
+            with torch.cuda.graph(g, stream=st):
+                qnn.qgemm(t["A"], c["z_a"], t["Bt"], t["mult"], t["shift"], c["z_out"], 0, 255, out=t["C"], workspace=t["ws"])
+        graphs.append(g)
+    for rep in range(4):
+        for (c, t, rows, want) in cases:
+            t["C"].zero_()
+            t["ws"].fill_(0xA5 + rep)  # whatever the workspace holds must not matter
+        torch.cuda.synchronize()
+        for g, st in zip(graphs, streams):
+            with torch.cuda.stream(st):
+                g.replay()
+        torch.cuda.synchronize()
+        for (c, t, rows, want) in cases:
+            assert_same(host(t["C"])[rows], want, f"concurrent split-K graph replay {rep} {tuple(t['C'].shape)}")
+
+
 @pytest.mark.parametrize("tile", ["dma128x128", "dma64x64"])
 @pytest.mark.parametrize("shape", [(14, 14, 64, 96, 3, 1, 1), (9, 9, 128, 40, 5, 1, 2), (7, 7, 512, 130, 3, 1, 1)],
                          ids=lambda s: "x".join(map(str, s)))
