@@ -476,7 +476,13 @@ def main():
     ap.add_argument("--streams", type=int, default=4,
                     help="streams the independent products of a sweep pass are spread over inside the graph (1: one after another)")
     ap.add_argument("--sweep-only", action="store_true",
-                    help="only the timed sweep passes (the command the rocprofv3 summaries of the sweep are taken from)")
+                    help="only the timed sweep passes (the command the rocprofv3 summaries of the sweep are taken from); "
+                         "the JSON line then lists the products in launch order")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="with --sweep-only: also one plain 1 GiB copy (reference point for the HBM byte counters)")
+    ap.add_argument("--stack-only", default=None,
+                    help="only the layer rows of one conv stack: mobilenet_v1_b64, mobilenet_v1_b1, resnet50_b256 or "
+                         "mobilenet_v2_int4_b32 (the command the rocprofv3 summaries of the conv kernels are taken from)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every box has one; the path needs no exchange between GPUs); "
@@ -492,6 +498,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     qnn.load_library()  # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
+
+    if args.stack_only:
+        stacks = {"mobilenet_v1_b64": (workloads.mobilenet_v1(), 64, 3), "mobilenet_v1_b1": (workloads.mobilenet_v1(), 1, 3),
+                  "resnet50_b256": (workloads.fuse_adds(workloads.resnet50()), 256, 4),
+                  "mobilenet_v2_int4_b32": (workloads.fuse_adds(workloads.mobilenet_v2(4)), 32, 5)}
+        layers_, batch_, cfg_ = stacks[args.stack_only]
+        print(json.dumps({args.stack_only: time_stack(torch, qnn, workloads, synth, layers_, batch_, cfg_, whole_graph=False)}))
+        return
 
     cases = build_gemm_sweep(torch, qnn, workloads, synth)
     elapsed = time_gemm_sweep(torch, cases, args.steps, args.warmup, eager=args.eager, streams=args.streams)
@@ -517,6 +531,15 @@ def main():
         "frac_of_int8_peak": round(value / PEAK_INT8_TOPS, 4),
     }
     if args.sweep_only:
+        big = [c for c in cases if c["plan"] in ("dma256x256", "dma256x128")]
+        small = [c for c in cases if c["plan"] not in ("dma256x256", "dma256x128")]
+        result["launch_order"] = [[c["M"], c["N"], c["K"], c["plan"]] for c in (cases if args.eager else small + big)]
+        if args.calibrate_copy:
+            src = _device_uint8(torch, (1 << 30,), 12345)
+            dst = torch.empty_like(src)
+            qnn.calibrate_copy(src, dst)
+            torch.cuda.synchronize()
+            result["calibration_copy_bytes"] = 1 << 30
         print(json.dumps(result))
         return
 

@@ -29,7 +29,29 @@ struct DwArgs {
     int64_t total_work; // lanes of work
     int wruns, hruns;   // patches of RW x RH output pixels per image row / column
     uint32_t magic_cgroups, shift_cgroups; // x / (C/4) = umulhi(x, magic) >> shift for x < 2^31
+    int xcd_remap;      // renumber the workgroups (see xcd_neighbours)
 };
+
+// The hardware deals workgroups to the 8 XCDs (each with a private L2) round-robin by linear
+// id, so spatial neighbours -- which re-read each other's halo rows and columns -- end up behind
+// eight different L2s and every halo byte is fetched from the fabric twice.  This renumbering
+// gives XCD k the k-th contiguous eighth of the (x fastest, then y, then z) order instead:
+// workgroup lin runs on XCD lin % 8 as its (lin / 8)-th, and takes the place
+// k * (total / 8) + min(k, total % 8) + lin / 8, a bijection of 0 .. total - 1.
+__device__ __forceinline__ void xcd_neighbours(bool on, uint32_t &bx, uint32_t &by, uint32_t &bz)
+{
+    bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    if (!on) return;
+    const uint32_t gx = gridDim.x, gy = gridDim.y;
+    const uint32_t total = gx * gy * gridDim.z; // the dispatcher keeps this below 2^31
+    const uint32_t lin = bx + gx * (by + gy * bz);
+    const uint32_t xcd = lin & 7u, per = total >> 3, rem = total & 7u;
+    const uint32_t id = xcd * per + (xcd < rem ? xcd : rem) + (lin >> 3);
+    const uint32_t t = id / gx;
+    bx = id - t * gx;
+    bz = t / gy;
+    by = t - bz * gy;
+}
 
 __device__ __forceinline__ int32_t sbyte(uint32_t v, int j) { return (int32_t)(int8_t)(v >> (8 * j)); }
 __device__ __forceinline__ int32_t ubyte(uint32_t v, int j) { return (int32_t)((v >> (8 * j)) & 0xffu); }
@@ -176,12 +198,14 @@ __global__ void __launch_bounds__(256) dwconv3x3_dot_kernel(const DwArgs g)
 {
     constexpr int RW = 4;
     constexpr int ROWS = (RH - 1) * S + 3, COLS = (RW - 1) * S + 3; // 6 or 9 input pixels per window row
-    const uint32_t lane_x = blockIdx.x * 256u + threadIdx.x;
+    uint32_t bx, by, bz;
+    xcd_neighbours(g.xcd_remap != 0, bx, by, bz);
+    const uint32_t lane_x = bx * 256u + threadIdx.x;
     const uint32_t cgroups = (uint32_t)g.C >> 2;
     const uint32_t pw = cgroups == 1 ? lane_x : __umulhi(lane_x, g.magic_cgroups) >> g.shift_cgroups; // lane_x / cgroups
     const uint32_t cg = lane_x - pw * cgroups;
     if (pw >= (uint32_t)g.wruns) return;
-    const int n = blockIdx.z, ph = blockIdx.y; // wave-uniform
+    const int n = (int)bz, ph = (int)by; // wave-uniform
     const int c0 = (int)cg * 4;
     const int ho0 = ph * RH, wo0 = (int)pw * RW;
 
@@ -369,12 +393,14 @@ __global__ void __launch_bounds__(256, 3) dwconv3x3_mfma_kernel(const DwArgs g, 
     __shared__ __attribute__((aligned(16))) uint8_t lds[4 * RING * ROW_BYTES];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int wave_lin = blockIdx.x * 4 + wave; // scalar
+    uint32_t bx, by, bz;
+    xcd_neighbours(g.xcd_remap != 0, bx, by, bz);
+    const int wave_lin = (int)bx * 4 + wave; // scalar
     const int tile_w = wave_lin / cblocks, cblk = wave_lin - tile_w * cblocks;
     if (tile_w >= tiles_w) return; // whole wave; waves share nothing
     uint8_t *const ring = lds + wave * (RING * ROW_BYTES);
-    const int n = blockIdx.z;
-    const int hb = blockIdx.y * seg_rows;
+    const int n = (int)bz;
+    const int hb = (int)by * seg_rows;
     const int rows = (g.Ho - hb) < seg_rows ? (g.Ho - hb) : seg_rows;
     const int li = lane & 31, half = lane >> 5;
     const int w0 = tile_w * TP;
@@ -711,6 +737,7 @@ static qnn_status qdwconv2d_impl(const uint8_t *x, int N, int H, int W, int C, i
             if (seg_rows > g.Ho) seg_rows = g.Ho;
             const int segs = (g.Ho + seg_rows - 1) / seg_rows;
             const dim3 grid((unsigned)((waves_x + 3) / 4), (unsigned)segs, (unsigned)N);
+            g.xcd_remap = tuning().dw_xcd != 0 && (int64_t)grid.x * grid.y * grid.z < (1ll << 31);
             const int mode = g.lo_rel >= 0 ? 2 : 1;
             if (stride_h == 1 && mode == 2) hipLaunchKernelGGL((dwconv3x3_mfma_kernel<1, 2>), grid, dim3(256), 0, s, g, seg_rows, tiles_w, cblocks);
             else if (stride_h == 1) hipLaunchKernelGGL((dwconv3x3_mfma_kernel<1, 1>), grid, dim3(256), 0, s, g, seg_rows, tiles_w, cblocks);
@@ -725,6 +752,7 @@ static qnn_status qdwconv2d_impl(const uint8_t *x, int N, int H, int W, int C, i
         const bool tall = tall_env ? tall_env == 4 : lanes_tall >= 16384;
         if (tall) g.hruns = (g.Ho + 3) / 4;
         const dim3 grid((unsigned)((lanes_x + 255) / 256), (unsigned)g.hruns, (unsigned)N);
+        g.xcd_remap = tuning().dw_xcd != 0 && (int64_t)grid.x * grid.y * grid.z < (1ll << 31);
         if (tall && stride_h == 1) hipLaunchKernelGGL((dwconv3x3_dot_kernel<1, 4>), grid, dim3(256), 0, s, g);
         else if (tall) hipLaunchKernelGGL((dwconv3x3_dot_kernel<2, 4>), grid, dim3(256), 0, s, g);
         else if (stride_h == 1) hipLaunchKernelGGL((dwconv3x3_dot_kernel<1, RH>), grid, dim3(256), 0, s, g);

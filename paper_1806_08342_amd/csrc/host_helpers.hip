@@ -32,6 +32,7 @@ static const TuningField kTuningFields[] = {
     {"QNN_XCD_ROWS", &Tuning::xcd_rows, -1},      {"QNN_DW_RH", &Tuning::dw_rh, 0},
     {"QNN_DW_MAD", &Tuning::dw_mad, 0},           {"QNN_GEMM_PRIO", &Tuning::gemm_prio, -1},
     {"QNN_PERSIST", &Tuning::persist, -1},        {"QNN_DW_VARIANT", &Tuning::dw_variant, -1},
+    {"QNN_DW_XCD", &Tuning::dw_xcd, 1},
 };
 
 static bool tuning_assign(Tuning &t, const char *name, const char *value)
