@@ -127,6 +127,24 @@ def dequantize(q, scale, zero_point):
     return x
 
 
+def quantize_wide(x, scale, zero_point, qmin=0, qmax=65535):
+    """eq. 1-2 with codes of up to 16 bits (uint16 result)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.empty(x.shape, dtype=np.uint16)
+    _check(lib().oracle_quantize_wide(_p(x, np.float32), _p(q, np.uint16), C.c_size_t(x.size), C.c_float(scale),
+                                      int(zero_point), int(qmin), int(qmax)))
+    return q
+
+
+def dequantize_wide(q, scale, zero_point):
+    """eq. 3 for uint16 codes."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    x = np.empty(q.shape, dtype=np.float32)
+    _check(lib().oracle_dequantize_wide(_p(q, np.uint16), _p(x, np.float32), C.c_size_t(q.size), C.c_float(scale),
+                                        int(zero_point)))
+    return x
+
+
 def quantize_weights(w, bits=8, restricted=True):
     """w: [channels, ...] fp32 -> (int8 array of the same shape, Delta_c[channels])."""
     w = np.ascontiguousarray(w, dtype=np.float32)
@@ -315,7 +333,9 @@ def dynamic_qparams(x, bits=8, state=None, momentum=0.0):
 
 
 def simquant(x, scale, zero_point, qmin=0, qmax=255):
-    """Sec. 2.4 eq. 12-13: a quantizer followed by a de-quantizer."""
+    """Sec. 2.4 eq. 12-13: a quantizer followed by a de-quantizer (codes of up to 16 bits)."""
+    if qmax > 255:
+        return dequantize_wide(quantize_wide(x, scale, zero_point, qmin, qmax), scale, zero_point)
     return dequantize(quantize(x, scale, zero_point, qmin, qmax), scale, zero_point)
 
 
@@ -323,6 +343,9 @@ def simquant_backward(x, grad_y, scale, zero_point, qmin=0, qmax=255):
     """Sec. 2.4 eq. 14-15 (straight-through estimator): the gradient passes where x lies inside the
     representable range [x_min, x_max] = de-quantized extreme codes, and is zero elsewhere."""
     x = np.asarray(x, dtype=np.float32)
-    ends = dequantize(np.array([qmin, qmax], dtype=np.uint8), scale, zero_point)
+    if qmax > 255:
+        ends = dequantize_wide(np.array([qmin, qmax], dtype=np.uint16), scale, zero_point)
+    else:
+        ends = dequantize(np.array([qmin, qmax], dtype=np.uint8), scale, zero_point)
     inside = (x >= ends[0]) & (x <= ends[1])
     return np.where(inside, np.asarray(grad_y, dtype=np.float32), np.float32(0.0)).astype(np.float32)

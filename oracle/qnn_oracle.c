@@ -147,6 +147,39 @@ int oracle_dequantize(const uint8_t *q, float *x, size_t n, float scale, int32_t
     return ORACLE_OK;
 }
 
+/* The same two maps for code ranges wider than a byte (up to 16 bits: the lower- and higher-precision
+ * activation experiments of Sec. 3.3 use 4-bit and 16-bit codes).  Same arithmetic, codes in uint16. */
+int oracle_quantize_wide(const float *x, uint16_t *q, size_t n, float scale, int32_t zero_point, int32_t qmin,
+                         int32_t qmax)
+{
+    if ((n && (!x || !q)) || !(scale > 0.0f) || isinf(scale)) return ORACLE_EINVAL;
+    if (qmin < 0 || qmax > 65535 || qmin > qmax || zero_point < qmin || zero_point > qmax) return ORACLE_EINVAL;
+    const float lo = (float)(qmin - zero_point);
+    const float hi = (float)(qmax - zero_point);
+#pragma omp parallel for schedule(static)
+    for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
+        volatile float t = x[i] / scale;
+        float r = (t != t) ? 0.0f : roundf(t);
+        if (r < lo) r = lo;
+        if (r > hi) r = hi;
+        q[i] = (uint16_t)((int32_t)r + zero_point);
+    }
+    return ORACLE_OK;
+}
+
+int oracle_dequantize_wide(const uint16_t *q, float *x, size_t n, float scale, int32_t zero_point)
+{
+    if ((n && (!x || !q)) || !(scale > 0.0f) || isinf(scale)) return ORACLE_EINVAL;
+    if (zero_point < 0 || zero_point > 65535) return ORACLE_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (ptrdiff_t i = 0; i < (ptrdiff_t)n; ++i) {
+        volatile float d = (float)((int32_t)q[i] - zero_point);
+        volatile float v = d * scale;
+        x[i] = v;
+    }
+    return ORACLE_OK;
+}
+
 /* ------------------------- symmetric per-channel weight quantizer (Sec. 2.2) */
 
 /* w is [channels][per_channel] fp32.  Delta_c = max|w_c| / (2^(bits-1) - 1)

@@ -13,6 +13,8 @@ int oracle_choose_qparams(double, double, int, float *, int32_t *);
 int oracle_act_range(int, float, int32_t, int32_t *, int32_t *);
 int oracle_quantize(const float *, uint8_t *, size_t, float, int32_t, int32_t, int32_t);
 int oracle_dequantize(const uint8_t *, float *, size_t, float, int32_t);
+int oracle_quantize_wide(const float *, uint16_t *, size_t, float, int32_t, int32_t, int32_t);
+int oracle_dequantize_wide(const uint16_t *, float *, size_t, float, int32_t);
 int oracle_quantize_weights(const float *, size_t, size_t, int, int, int8_t *, float *);
 int oracle_pack_int4(const int8_t *, size_t, uint8_t *);
 int oracle_unpack_int4(const uint8_t *, size_t, int8_t *);
@@ -62,6 +64,11 @@ int main(void)
     CHECK(oracle_quantize(xs, q, 8, 1e-6f, 128, 0, 255) == 0);
     CHECK(oracle_dequantize(q, back, 8, 1e-6f, 128) == 0);
     CHECK(q[3] == 255 && q[4] == 0 && q[2] == 128);
+    uint16_t qw[8];
+    CHECK(oracle_quantize_wide(xs, qw, 8, 1e-6f, 32768, 0, 65535) == 0);
+    CHECK(oracle_dequantize_wide(qw, back, 8, 1e-6f, 32768) == 0);
+    CHECK(qw[3] == 65535 && qw[4] == 0 && qw[2] == 32768);
+    CHECK(oracle_quantize_wide(xs, qw, 8, 1e-6f, 0, 0, 65536) != 0);
 
     /* weights: 8 and 4 bits, packing */
     float wf[2 * 6] = {-1.0f, 0.5f, 0.25f, 0.0f, 1.0f, -0.125f, 0, 0, 0, 0, 0, 0};

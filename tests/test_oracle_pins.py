@@ -544,6 +544,48 @@ def test_simquant_is_eq_13_idempotent_and_bounded():
     assert len(np.unique(y4)) <= 16 and y4.min() == -2.0 and y4.max() == 1.75
 
 
+def test_wide_codes_every_16_bit_code_round_trips_and_eq_13_holds_in_fp64():
+    """Codes of up to 16 bits (Sec. 3.3 compares 4-, 8- and 16-bit activations).  Pins: (a) on a byte
+    range the wide maps ARE the byte maps; (b) with a power-of-two step the grid points (k - z) Delta are
+    exact, so every one of the 65536 codes must come back from quantize(dequantize(k)); (c) eq. 13
+    evaluated in fp64 (exact for a power-of-two step); (d) error at most half a step inside the range,
+    saturation outside, and a 16-bit quantizer over the same real range is 257 times finer than an 8-bit one."""
+    rng = np.random.default_rng(4242)
+    x = rng.normal(0, 2, 20000).astype(np.float32)
+    assert np.array_equal(oracle.quantize_wide(x, 0.037, 117, 0, 255), oracle.quantize(x, 0.037, 117).astype(np.uint16))
+    q8 = rng.integers(0, 256, 999, dtype=np.uint8)
+    assert np.array_equal(oracle.dequantize_wide(q8.astype(np.uint16), 0.037, 117), oracle.dequantize(q8, 0.037, 117))
+    scale, z = 2.0 ** -14, 30000
+    codes = np.arange(65536, dtype=np.uint16)
+    grid = oracle.dequantize_wide(codes, scale, z)
+    assert np.array_equal(grid.astype(np.float64), (codes.astype(np.float64) - z) * scale)
+    assert np.array_equal(oracle.quantize_wide(grid, scale, z), codes)
+    y = oracle.simquant(x, scale, z, 0, 65535)
+    t = x.astype(np.float64) / scale
+    r = np.where(t >= 0, np.floor(t + 0.5), -np.floor(-t + 0.5))
+    assert np.array_equal(y.astype(np.float64), (np.clip(r + z, 0, 65535) - z) * scale)
+    assert np.array_equal(oracle.simquant(y, scale, z, 0, 65535), y)
+    lo, hi = (0 - z) * scale, (65535 - z) * scale
+    inside = (x >= lo) & (x <= hi)
+    assert inside.sum() > 100 and (~inside).sum() > 100
+    assert np.max(np.abs(y[inside].astype(np.float64) - x[inside])) <= scale / 2
+    assert np.all(y[x > hi] == np.float32(hi)) and np.all(y[x < lo] == np.float32(lo))
+    # a restricted code range inside the wide one (12-bit codes) saturates at ITS ends
+    y12 = oracle.simquant(x, scale, 2048, 0, 4095)
+    assert y12.max() == np.float32((4095 - 2048) * scale) and y12.min() == np.float32(-2048 * scale)
+    # same real range [-4, 4): 16-bit step = 8-bit step / 257 (Sec. 2.1: Delta = range / (2^bits - 1))
+    s8, z8 = oracle.choose_qparams(-4.0, 4.0, 8)
+    s16, z16 = oracle.choose_qparams(-4.0, 4.0, 16)
+    assert abs(s8 / s16 - 257.0) < 1e-3
+    xin = x[(x > -3.9) & (x < 3.9)]
+    e8 = np.max(np.abs(oracle.simquant(xin, s8, z8) - xin))
+    e16 = np.max(np.abs(oracle.simquant(xin, s16, z16, 0, 65535) - xin))
+    assert e16 <= s16 / 2 * 1.01 + 1e-7 and e8 > 50 * e16
+    # the straight-through mask follows the wide range
+    ends = np.array([lo, hi, np.nextafter(np.float32(lo), np.float32(-9)), np.nextafter(np.float32(hi), np.float32(9))], np.float32)
+    assert oracle.simquant_backward(ends, np.ones(4, np.float32), scale, z, 0, 65535).tolist() == [1.0, 1.0, 0.0, 0.0]
+
+
 def test_simquant_backward_is_the_indicator_of_the_range():
     x = np.array([-10.0, -3.2, -3.1875, 0.0, 4.78125, 4.8, 100.0, np.nan], np.float32)
     g = np.arange(1, 9, dtype=np.float32)
