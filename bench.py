@@ -404,6 +404,28 @@ def calibrate(torch, qnn):
     t = graph_time(torch, [lambda s=s, d=d: qnn.calibrate_copy(s, d) for s, d in zip(srcs, dsts)], min_launches=6)
     out["copy_1GiB_16B_per_lane"] = dict(us=round(t * 1e6, 1), gbs=round(2.0 * n / t * 1e-9, 1),
                                          frac_of_peak=round(2.0 * n / t / (PEAK_HBM_GBS * 1e9), 3))
+    del srcs, dsts
+    # The dominant GEMM kernel itself on 8192^3 with the sweep's operands (uniform bytes, Gaussian weights) and
+    # with operands that toggle no bits (all codes zero).  Same instructions, same memory traffic; what differs
+    # is the power the data draws in the multipliers and on the wires, i.e. the clock the chip sustains.
+    m = 8192
+    mult = torch.full((m,), 1 << 30, dtype=torch.int32, device="cuda:0")
+    shift = torch.full((m,), 12, dtype=torch.int32, device="cuda:0")
+    for name in ("gemm_8192_sweep_operands", "gemm_8192_zero_operands"):
+        if name.endswith("sweep_operands"):
+            A = _device_uint8(torch, (m, m), 777)
+            B = (torch.randn((m, m), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(778)) * (127 / 4.5))
+            B = B.round().clamp(-127, 127).to(torch.int8)
+        else:
+            A = torch.zeros((m, m), dtype=torch.uint8, device="cuda:0")
+            B = torch.zeros((m, m), dtype=torch.int8, device="cuda:0")
+        Cm = torch.empty((m, m), dtype=torch.uint8, device="cuda:0")
+        fn = qnn.prepare_qgemm(A, 128, B, mult, shift, 3, 0, 255, Cm)
+        t = graph_time(torch, [fn], min_launches=10)
+        ops = 2.0 * m * m * m
+        out[name] = dict(us=round(t * 1e6, 1), tops=round(ops / t * 1e-12, 1), frac_of_peak=round(ops / t / (PEAK_INT8_TOPS * 1e12), 3),
+                         plan=qnn.qgemm_plan(m, m, m))
+        del A, B, Cm, fn
     return out
 
 

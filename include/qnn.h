@@ -289,8 +289,9 @@ qnn_status qnn_quantize_dynamic(const float *x, uint8_t *q, size_t n, qnn_dyn_qp
 
 /* Simulated quantization for quantization-aware training (Sec. 2.4).
  * Forward (eq. 12-13): y[i] = dequantize(quantize(x[i])) with the given quantizer and code range
- *   [qmin, qmax] within 0..255 (e.g. 0..15 for 4-bit activations); same arithmetic as qnn_quantize /
- *   qnn_dequantize, so y is bit-identical to calling the two.
+ *   [qmin, qmax] within 0..65535 (0..15 for 4-bit, 0..65535 for 16-bit activations, Sec. 3.3); same
+ *   arithmetic as qnn_quantize / qnn_dequantize (qnn_quantize_u16 / qnn_dequantize_u16 beyond a byte), so y
+ *   is bit-identical to calling the two.
  * Backward (straight-through estimator, eq. 14-15): grad_x[i] = grad_y[i] if x_min <= x[i] <= x_max, else
  *   0, with x_min = (qmin - zero_point) * scale and x_max = (qmax - zero_point) * scale in binary32
  *   (NaN inputs get no gradient).
@@ -299,6 +300,14 @@ qnn_status qnn_simquant(const float *x, float *y, size_t n, float scale, int32_t
                         void *stream);
 qnn_status qnn_simquant_backward(const float *x, const float *grad_y, float *grad_x, size_t n, float scale,
                                  int32_t zero_point, int32_t qmin, int32_t qmax, void *stream);
+
+/* Quantizer and de-quantizer of Sec. 2.1 (eq. 1-3) for codes of up to 16 bits, stored as uint16: the
+ * arithmetic of qnn_quantize / qnn_dequantize with [qmin, qmax] within 0..65535 (Sec. 3.3 evaluates
+ * 16-bit activations).  x: DEVICE fp32[n]; q: DEVICE uint16[n] (2-byte aligned; 4 elements per lane when x
+ * is 16-byte and q 8-byte aligned).  n == 0 is allowed.  QNN_EINVAL as for the byte versions. */
+qnn_status qnn_quantize_u16(const float *x, uint16_t *q, size_t n, float scale, int32_t zero_point, int32_t qmin,
+                            int32_t qmax, void *stream);
+qnn_status qnn_dequantize_u16(const uint16_t *q, float *x, size_t n, float scale, int32_t zero_point, void *stream);
 
 /* Depthwise convolution with a zero-point per channel of the weights (as qnn_qconv2d_asym; one lane per
  * output evaluates sum (x - z_x)(w - z_w[c]) over the taps inside the image directly).  z_w: DEVICE int32[C]. */

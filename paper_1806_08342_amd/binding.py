@@ -23,7 +23,7 @@ EXPORTS = [
     "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_rescale_u8", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_qdwconv2d_asym", "qnn_minmax", "qnn_quantize_with",
     "qnn_quantize_dynamic", "qnn_simquant", "qnn_simquant_backward", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
     "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4", "qnn_qgemm_workspace_bytes", "qnn_qconv2d_workspace_bytes",
-    "qnn_tuning_set", "qnn_calibrate_mfma", "qnn_calibrate_copy", "qnn_qgemm_noalloc",
+    "qnn_tuning_set", "qnn_calibrate_mfma", "qnn_calibrate_copy", "qnn_qgemm_noalloc", "qnn_quantize_u16", "qnn_dequantize_u16",
 ]
 
 
@@ -56,6 +56,8 @@ def load_library():
     sigs = {
         "qnn_quantize": [vp, vp, sz, f32, i32, i32, i32, vp],
         "qnn_dequantize": [vp, vp, sz, f32, i32, vp],
+        "qnn_quantize_u16": [vp, vp, sz, f32, i32, i32, i32, vp],
+        "qnn_dequantize_u16": [vp, vp, sz, f32, i32, vp],
         "qnn_requantize": [vp, vp, sz, sz, vp, vp, ci, i32, i32, i32, vp],
         "qnn_qgemm": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp, sz, vp],
         "qnn_qgemm_noalloc": [vp, i64, i32, vp, i64, ci, ci, i64, i64, i64, vp, vp, vp, i32, i32, i32, vp, i64, vp],
@@ -266,6 +268,27 @@ def dequantize(q, scale, zero_point, out=None):
     x = torch.empty(q.shape, dtype=torch.float32, device=q.device) if out is None else out
     _check("qnn_dequantize", load_library().qnn_dequantize(_dev(q, torch.uint8, "q"), _dev(x, torch.float32, "x"),
                                                           q.numel(), scale, zero_point, _stream()))
+    return x
+
+
+def quantize_u16(x, scale, zero_point, qmin=0, qmax=65535, out=None):
+    """Codes of up to 16 bits as a uint16 tensor."""
+    torch = _torch()
+    q = torch.empty(x.shape, dtype=torch.uint16, device=x.device) if out is None else out
+    if tuple(q.shape) != tuple(x.shape):
+        raise ValueError(f"out: shape {tuple(q.shape)}, expected {tuple(x.shape)}")
+    _check("qnn_quantize_u16", load_library().qnn_quantize_u16(_dev(x, torch.float32, "x"), _dev(q, torch.uint16, "q"),
+                                                              x.numel(), scale, zero_point, qmin, qmax, _stream()))
+    return q
+
+
+def dequantize_u16(q, scale, zero_point, out=None):
+    torch = _torch()
+    x = torch.empty(q.shape, dtype=torch.float32, device=q.device) if out is None else out
+    if tuple(x.shape) != tuple(q.shape):
+        raise ValueError(f"out: shape {tuple(x.shape)}, expected {tuple(q.shape)}")
+    _check("qnn_dequantize_u16", load_library().qnn_dequantize_u16(_dev(q, torch.uint16, "q"), _dev(x, torch.float32, "x"),
+                                                                  q.numel(), scale, zero_point, _stream()))
     return x
 
 

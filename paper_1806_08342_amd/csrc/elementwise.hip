@@ -227,6 +227,59 @@ __global__ void __launch_bounds__(kThreads) simquant_backward_kernel(const float
     }
 }
 
+// 16-bit codes (Sec. 3.3 compares activation precisions of 4, 8 and 16 bits): the same arithmetic with
+// uint16 storage.  A lane handles 4 consecutive elements (16 bytes in, 8 bytes out) when the pointers
+// allow it.
+using u32x2 = uint32_t __attribute__((ext_vector_type(2)));
+
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) quantize_u16_kernel(const float *__restrict__ x, uint16_t *__restrict__ q,
+                                                                size_t n, float scale, int32_t z, float lo, float hi)
+{
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    size_t done = 0;
+    if (VEC == 4) {
+        const size_t nvec = n / 4;
+        const f32x4 *xv = reinterpret_cast<const f32x4 *>(x);
+        u32x2 *qv = reinterpret_cast<u32x2 *>(q);
+        for (size_t v = tid; v < nvec; v += nthreads) {
+            const f32x4 a = __builtin_nontemporal_load(&xv[v]);
+            u32x2 p;
+            p.x = quantize_one(a.x, scale, lo, hi, z) | (quantize_one(a.y, scale, lo, hi, z) << 16);
+            p.y = quantize_one(a.z, scale, lo, hi, z) | (quantize_one(a.w, scale, lo, hi, z) << 16);
+            __builtin_nontemporal_store(p, &qv[v]);
+        }
+        done = nvec * 4;
+    }
+    for (size_t i = done + tid; i < n; i += nthreads) q[i] = (uint16_t)quantize_one(x[i], scale, lo, hi, z);
+}
+
+template <int VEC>
+__global__ void __launch_bounds__(kThreads) dequantize_u16_kernel(const uint16_t *__restrict__ q, float *__restrict__ x,
+                                                                  size_t n, float scale, int32_t z)
+{
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    size_t done = 0;
+    if (VEC == 4) {
+        const size_t nvec = n / 4;
+        const u32x2 *qv = reinterpret_cast<const u32x2 *>(q);
+        f32x4 *xv = reinterpret_cast<f32x4 *>(x);
+        for (size_t v = tid; v < nvec; v += nthreads) {
+            const u32x2 p = __builtin_nontemporal_load(&qv[v]);
+            f32x4 o;
+            o.x = __fmul_rn((float)((int32_t)(p.x & 0xffffu) - z), scale);
+            o.y = __fmul_rn((float)((int32_t)(p.x >> 16) - z), scale);
+            o.z = __fmul_rn((float)((int32_t)(p.y & 0xffffu) - z), scale);
+            o.w = __fmul_rn((float)((int32_t)(p.y >> 16) - z), scale);
+            __builtin_nontemporal_store(o, &xv[v]);
+        }
+        done = nvec * 4;
+    }
+    for (size_t i = done + tid; i < n; i += nthreads) x[i] = __fmul_rn((float)((int32_t)q[i] - z), scale);
+}
+
 // ---------------------------------------------------------------- dequantize
 
 template <int VEC>
@@ -562,6 +615,37 @@ qnn_status qnn_dequantize(const uint8_t *q, float *x, size_t n, float scale, int
     return launch_status(hipGetLastError());
 }
 
+qnn_status qnn_quantize_u16(const float *x, uint16_t *q, size_t n, float scale, int32_t zero_point, int32_t qmin,
+                            int32_t qmax, void *stream)
+{
+    if (!(scale > 0.0f) || __builtin_isinf(scale)) return QNN_EINVAL;
+    if (qmin < 0 || qmax > 65535 || qmin > qmax || zero_point < qmin || zero_point > qmax) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (!x || !q) return QNN_EINVAL;
+    const float lo = (float)(qmin - zero_point), hi = (float)(qmax - zero_point);
+    if (aligned(x, 16) && aligned(q, 8))
+        hipLaunchKernelGGL(quantize_u16_kernel<4>, dim3(grid_for(n / 4 + 1, kThreads * 4)), dim3(kThreads), 0,
+                           as_stream(stream), x, q, n, scale, zero_point, lo, hi);
+    else
+        hipLaunchKernelGGL(quantize_u16_kernel<1>, dim3(grid_for(n, kThreads * 4)), dim3(kThreads), 0, as_stream(stream),
+                           x, q, n, scale, zero_point, lo, hi);
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_dequantize_u16(const uint16_t *q, float *x, size_t n, float scale, int32_t zero_point, void *stream)
+{
+    if (!(scale > 0.0f) || __builtin_isinf(scale) || zero_point < 0 || zero_point > 65535) return QNN_EINVAL;
+    if (n == 0) return QNN_OK;
+    if (!x || !q) return QNN_EINVAL;
+    if (aligned(x, 16) && aligned(q, 8))
+        hipLaunchKernelGGL(dequantize_u16_kernel<4>, dim3(grid_for(n / 4 + 1, kThreads * 4)), dim3(kThreads), 0,
+                           as_stream(stream), q, x, n, scale, zero_point);
+    else
+        hipLaunchKernelGGL(dequantize_u16_kernel<1>, dim3(grid_for(n, kThreads * 4)), dim3(kThreads), 0,
+                           as_stream(stream), q, x, n, scale, zero_point);
+    return launch_status(hipGetLastError());
+}
+
 qnn_status qnn_requantize(const int32_t *acc, uint8_t *y, size_t rows, size_t channels, const int32_t *mult,
                           const int32_t *shift, int per_channel, int32_t z_out, int32_t act_min, int32_t act_max,
                           void *stream)
@@ -622,7 +706,7 @@ qnn_status qnn_quantize_dynamic(const float *x, uint8_t *q, size_t n, qnn_dyn_qp
 qnn_status qnn_simquant(const float *x, float *y, size_t n, float scale, int32_t zero_point, int32_t qmin, int32_t qmax,
                         void *stream)
 {
-    if (!(scale > 0.0f) || __builtin_isinf(scale) || qmin < 0 || qmax > 255 || qmin > qmax) return QNN_EINVAL;
+    if (!(scale > 0.0f) || __builtin_isinf(scale) || qmin < 0 || qmax > 65535 || qmin > qmax) return QNN_EINVAL;
     if (zero_point < qmin || zero_point > qmax) return QNN_EINVAL;
     if (n == 0) return QNN_OK;
     if (!x || !y) return QNN_EINVAL;
@@ -634,7 +718,7 @@ qnn_status qnn_simquant(const float *x, float *y, size_t n, float scale, int32_t
 qnn_status qnn_simquant_backward(const float *x, const float *grad_y, float *grad_x, size_t n, float scale,
                                  int32_t zero_point, int32_t qmin, int32_t qmax, void *stream)
 {
-    if (!(scale > 0.0f) || __builtin_isinf(scale) || qmin < 0 || qmax > 255 || qmin > qmax) return QNN_EINVAL;
+    if (!(scale > 0.0f) || __builtin_isinf(scale) || qmin < 0 || qmax > 65535 || qmin > qmax) return QNN_EINVAL;
     if (zero_point < qmin || zero_point > qmax) return QNN_EINVAL;
     if (n == 0) return QNN_OK;
     if (!x || !grad_y || !grad_x) return QNN_EINVAL;

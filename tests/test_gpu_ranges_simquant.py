@@ -89,7 +89,8 @@ def test_simquant_forward_and_backward_match_oracle(n):
     if n >= 4096:
         x[:5] = [np.nan, np.inf, -np.inf, 1e30, -0.0]
     for scale, z, qmin, qmax in [(0.0213, 131, 0, 255), (2.0 ** -5, 102, 0, 255), (0.25, 8, 0, 15), (1 / 3, 0, 0, 255),
-                                 (0.05, 255, 0, 255)]:
+                                 (0.05, 255, 0, 255), (2.0 ** -14, 30000, 0, 65535), (1.7e-4, 21845, 0, 65535),
+                                 (0.003, 2048, 0, 4095), (1e-3, 65535, 0, 65535)]:
         y = host(qnn.simquant(dev(x), scale, z, qmin, qmax))
         assert np.array_equal(_bits(y), _bits(oracle.simquant(x, scale, z, qmin, qmax))), (scale, z)
         gx = host(qnn.simquant_backward(dev(x), dev(g), scale, z, qmin, qmax))
@@ -98,6 +99,31 @@ def test_simquant_forward_and_backward_match_oracle(n):
     ends = oracle.dequantize(np.array([0, 255], np.uint8), 2.0 ** -5, 102)
     gx = host(qnn.simquant_backward(dev(ends), dev(np.ones(2, np.float32)), 2.0 ** -5, 102))
     assert gx.tolist() == [1.0, 1.0]
+
+
+@pytest.mark.parametrize("n,offset", [(0, 0), (1, 0), (5, 1), (4099, 0), (4099, 3), (1_000_003, 0)])
+def test_quantize_and_dequantize_with_16_bit_codes_match_oracle(n, offset):
+    """Sec. 3.3 activation precision of 16 bits: uint16 codes.  `offset` shifts both pointers off their
+    vector alignment (the one-element-per-lane form of the kernels)."""
+    import torch
+    rng = np.random.default_rng(9100 + n + offset)
+    x = rng.normal(0, 2, n + offset).astype(np.float32)
+    if n >= 4096:
+        x[offset:offset + 6] = [np.nan, np.inf, -np.inf, 1e30, -0.0, 1e-45]
+    xd = dev(x)[offset:]
+    x = x[offset:]
+    for scale, z, qmin, qmax in [(2.0 ** -14, 30000, 0, 65535), (1.7e-4, 21845, 0, 65535), (0.003, 2048, 0, 4095),
+                                 (0.0213, 131, 0, 255), (1e-3, 0, 0, 65535)]:
+        qbuf = torch.zeros(n + offset, dtype=torch.uint16, device="cuda:0")[offset:]
+        q = qnn.quantize_u16(xd, scale, z, qmin, qmax, out=qbuf)
+        want = oracle.quantize_wide(x, scale, z, qmin, qmax)
+        got = q.cpu().view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(got, want), (scale, z)
+        back = host(qnn.dequantize_u16(q, scale, z))
+        assert np.array_equal(_bits(back), _bits(oracle.dequantize_wide(want, scale, z))), (scale, z)
+        if n:
+            y = host(qnn.simquant(xd.contiguous(), scale, z, qmin, qmax))
+            assert np.array_equal(_bits(y), _bits(back))  # SimQuant == de-quantize(quantize)
 
 
 # ------------------------------------------------------------ rescale of uint8 codes (concat)

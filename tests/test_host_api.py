@@ -136,6 +136,14 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     assert lib.qnn_simquant_backward(p, p, p, 16, C.c_float(0.1), 0, 9, 3, None) == EINVAL
     assert lib.qnn_simquant_backward(p, null, p, 16, C.c_float(0.1), 0, 0, 255, None) == EINVAL
     assert lib.qnn_simquant(null, null, 0, C.c_float(0.1), 0, 0, 255, None) == 0
+    assert lib.qnn_simquant(p, p, 16, C.c_float(0.1), 0, 0, 65536, None) == EINVAL
+    assert lib.qnn_quantize_u16(p, p, 16, C.c_float(0.1), 0, 0, 65536, None) == EINVAL
+    assert lib.qnn_quantize_u16(p, p, 16, C.c_float(0.1), 70000, 0, 65535, None) == EINVAL
+    assert lib.qnn_quantize_u16(p, null, 16, C.c_float(0.1), 0, 0, 65535, None) == EINVAL
+    assert lib.qnn_quantize_u16(null, null, 0, C.c_float(0.1), 0, 0, 65535, None) == 0
+    assert lib.qnn_dequantize_u16(p, p, 16, C.c_float(0.0), 0, None) == EINVAL
+    assert lib.qnn_dequantize_u16(p, p, 16, C.c_float(0.1), 65536, None) == EINVAL
+    assert lib.qnn_dequantize_u16(null, null, 0, C.c_float(0.1), 0, None) == 0
     assert lib.qnn_rescale_u8(p, 8, 0, 1 << 30, 1, 0, 0, 255, p, 4, 2, 8, None) == EINVAL   # ldy < cols
     assert lib.qnn_rescale_u8(p, 8, 300, 1 << 30, 1, 0, 0, 255, p, 8, 2, 8, None) == EINVAL
     assert lib.qnn_rescale_u8(null, 8, 0, 1 << 30, 1, 0, 0, 255, null, 8, 0, 8, None) == 0
