@@ -405,6 +405,16 @@ def calibrate(torch, qnn):
     out["copy_1GiB_16B_per_lane"] = dict(us=round(t * 1e6, 1), gbs=round(2.0 * n / t * 1e-9, 1),
                                          frac_of_peak=round(2.0 * n / t / (PEAK_HBM_GBS * 1e9), 3))
     del srcs, dsts
+    # The same copy kernel at the byte counts of two depthwise layers of MobileNetV1 at batch 64 (112 x 112 x 32
+    # and 14 x 14 x 512, stride 1: as many bytes out as in), timed like the layer rows: what a launch that only
+    # moves a layer's bytes costs on this machine, launch floor included.
+    for name, nbytes in (("copy_25.7MB_each_way", 64 * 112 * 112 * 32), ("copy_6.4MB_each_way", 64 * 14 * 14 * 512)):
+        sets, label = _sets_for(2 * nbytes)
+        bufs = [(_device_uint8(torch, (nbytes,), 500 + i), torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")) for i in range(sets)]
+        t = graph_time(torch, [lambda s=s, d=d: qnn.calibrate_copy(s, d) for s, d in bufs], min_launches=10, est_s=1e-5)
+        out[name] = dict(us=round(t * 1e6, 2), gbs=round(2.0 * nbytes / t * 1e-9, 1), frac_of_peak=round(2.0 * nbytes / t / (PEAK_HBM_GBS * 1e9), 3),
+                         sets=sets, memory=label)
+        del bufs
     # The dominant GEMM kernel itself on 8192^3 with the sweep's operands (uniform bytes, Gaussian weights) and
     # with operands that toggle no bits (all codes zero).  Same instructions, same memory traffic; what differs
     # is the power the data draws in the multipliers and on the wires, i.e. the clock the chip sustains.

@@ -420,7 +420,7 @@ struct QaddArgs {
 // The rescaled value of an input depends only on its 8-bit code, so each block first
 // tabulates RESCALE((v - z) * 2^L) for the 256 codes of a and of b in LDS; the streaming
 // loop is then two table reads, an add and one rescale per element.
-// FUSED: the output rescale may use the 32-bit fused form (1 <= shift_o <= 21 and both tables
+// FUSED: the output rescale may use the 32-bit fused form (1 <= shift_o <= 20 and both tables
 // bounded by 2^28, which shift_a, shift_b >= 0 and left_shift <= 20 guarantee).
 template <int VEC, bool FUSED>
 __global__ void __launch_bounds__(kThreads) qadd_kernel(const uint8_t *__restrict__ a, const uint8_t *__restrict__ b,

@@ -35,6 +35,9 @@ __device__ __forceinline__ RescaleParams make_rescale(int32_t mult, int32_t shif
 {
     RescaleParams p;
     p.mult = mult;
+    // per-channel parameters live in device memory and cannot be validated by the host: keep the shift
+    // counts below inside what a 32-bit shift defines
+    shift = shift < -31 ? -31 : (shift > 31 ? 31 : shift);
     p.rshift = shift > 0 ? shift : 0;
     p.lshift = shift < 0 ? -shift : 0;
     p.half = p.rshift ? (1 << (p.rshift - 1)) : 0;

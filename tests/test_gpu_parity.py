@@ -410,6 +410,26 @@ def test_qdwconv2d_rolling_window_kernel_matches_oracle(tuning, variant, seg_row
         assert_same(got, want, f"dwconv variant {variant} seg {seg_rows} {shape} {act} z_x={z_x}")
 
 
+@pytest.mark.parametrize("variant", [0, 3])
+@pytest.mark.parametrize("xcd", [0, 1])
+@pytest.mark.parametrize("shape,batch", [((12, 12, 32, 1, 1), 1), ((29, 31, 96, 2, 1), 3), ((23, 45, 144, 1, 1), 2),
+                                         ((9, 140, 32, 1, 1), 5), ((56, 56, 128, 1, 1), 3), ((28, 28, 256, 2, 1), 7)],
+                         ids=lambda s: "x".join(map(str, s)) if isinstance(s, tuple) else str(s))
+def test_qdwconv2d_workgroup_numbering_per_xcd_is_a_permutation(tuning, variant, xcd, shape, batch):
+    # the renumbering that hands each XCD a contiguous share of the patches must visit every patch once,
+    # whatever the workgroup count modulo 8 (batches and shapes chosen to give remainders 0..7)
+    tuning.setenv("QNN_DW_VARIANT", str(variant))
+    tuning.setenv("QNN_DW_XCD", str(xcd))
+    H, W, C, s_, p = shape
+    layer = workloads.Layer("t", "dw", H, W, C, C, k=3, stride=s_, pad=p, act="relu6")
+    c = synth.conv_case(layer, batch, 1390 + sum(shape) + batch, oracle)
+    want = oracle.qdwconv2d(c["x"], c["z_x"], c["w"], c["stride"], c["pad"], c["mult"], c["shift"], c["z_out"],
+                            c["act_min"], c["act_max"], bias=c["bias"])
+    got = host(qnn.qdwconv2d(dev(c["x"]), c["z_x"], dev(c["w"]), c["stride"], c["pad"], dev(c["mult"]), dev(c["shift"]),
+                             c["z_out"], c["act_min"], c["act_max"], bias=dev(c["bias"])))
+    assert_same(got, want, f"dwconv variant {variant} xcd {xcd} {shape} batch {batch}")
+
+
 # ------------------------------------------------ pipelined (LDS-DMA) tile configurations
 
 @pytest.fixture
