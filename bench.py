@@ -398,6 +398,16 @@ def calibrate(torch, qnn):
             ops[0] = qnn.calibrate_mfma(1024, 4096, rnd, sink)  # 4 workgroups of 8 waves per CU, 16384 MFMAs per wave
         t = graph_time(torch, [fn], min_launches=4)
         out[name] = dict(us=round(t * 1e6, 1), tops=round(ops[0] / t * 1e-12, 1), frac_of_peak=round(ops[0] / t / (PEAK_INT8_TOPS * 1e12), 3))
+    # the vector ALU on the epilogue's own instruction sequence (registers only): accumulators turned into output
+    # bytes per second, for 1, 2 and 4 waves per SIMD
+    for w in (1, 2, 4):
+        cnt = [0.0]
+
+        def fn(w=w):
+            cnt[0] = qnn.calibrate_rescale(256 * w, 2048, sink)
+        t = graph_time(torch, [fn], min_launches=4)
+        out[f"rescale_loop_{w}_waves_per_simd"] = dict(us=round(t * 1e6, 1), outputs_per_s=round(cnt[0] / t, -9),
+                                                        lane_ops_per_output="5 + 1 (feedback)")
     n = 1 << 30
     srcs = [_device_uint8(torch, (n,), 12345 + i) for i in range(2)]
     dsts = [torch.empty_like(srcs[0]) for _ in range(2)]

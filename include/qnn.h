@@ -323,9 +323,14 @@ qnn_status qnn_qdwconv2d_asym(const uint8_t *x, int N, int H, int W, int C, int3
  *   integer operations the launch performs (2 per multiply-accumulate).  sink: DEVICE int32
  *   [workgroups * 512] (written).
  * qnn_calibrate_copy: dst[0..bytes) = src[0..bytes), 16 bytes per lane and access; bytes % 16 == 0,
- *   both DEVICE pointers 16-byte aligned. */
+ *   both DEVICE pointers 16-byte aligned.
+ * qnn_calibrate_rescale: `workgroups` workgroups of 256 lanes each rescale iters x 16 accumulators held in
+ *   registers with the instruction sequence of the fused epilogues (RESCALE + clamp + byte packing in its
+ *   cheapest exact form); *outputs (HOST) receives the number of accumulators rescaled.  sink: DEVICE int32
+ *   [workgroups * 256] (written). */
 qnn_status qnn_calibrate_mfma(int workgroups, int iters, int random_operands, int32_t *sink, double *ops, void *stream);
 qnn_status qnn_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream);
+qnn_status qnn_calibrate_rescale(int workgroups, int iters, int32_t *sink, double *outputs, void *stream);
 
 /* ------------------------------------------------------------------ host-only helpers */
 

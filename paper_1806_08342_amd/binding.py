@@ -23,7 +23,7 @@ EXPORTS = [
     "qnn_qconv2d", "qnn_qdwconv2d", "qnn_qadd", "qnn_qgemm_add", "qnn_qconv2d_add", "qnn_rescale_u8", "qnn_qgemm_asym", "qnn_qconv2d_asym", "qnn_qdwconv2d_asym", "qnn_minmax", "qnn_quantize_with",
     "qnn_quantize_dynamic", "qnn_simquant", "qnn_simquant_backward", "qnn_choose_qparams", "qnn_quantize_multiplier", "qnn_act_range",
     "qnn_qadd_params", "qnn_quantize_weights", "qnn_pack_int4", "qnn_qgemm_workspace_bytes", "qnn_qconv2d_workspace_bytes",
-    "qnn_tuning_set", "qnn_calibrate_mfma", "qnn_calibrate_copy", "qnn_qgemm_noalloc", "qnn_quantize_u16", "qnn_dequantize_u16",
+    "qnn_tuning_set", "qnn_calibrate_mfma", "qnn_calibrate_copy", "qnn_qgemm_noalloc", "qnn_quantize_u16", "qnn_dequantize_u16", "qnn_calibrate_rescale",
 ]
 
 
@@ -65,6 +65,7 @@ def load_library():
         "qnn_qconv2d": [vp, ci, ci, ci, ci, i32, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp],
         "qnn_tuning_set": [C.c_char_p, C.c_char_p],
         "qnn_calibrate_mfma": [ci, ci, ci, vp, C.POINTER(f64), vp],
+        "qnn_calibrate_rescale": [ci, ci, vp, C.POINTER(f64), vp],
         "qnn_calibrate_copy": [vp, vp, sz, vp],
         "qnn_minmax": [vp, sz, f32, ci, vp, vp],
         "qnn_quantize_with": [vp, vp, sz, vp, vp],
@@ -181,6 +182,15 @@ def calibrate_mfma(workgroups, iters, random_operands, sink):
     _check("qnn_calibrate_mfma", load_library().qnn_calibrate_mfma(int(workgroups), int(iters), int(bool(random_operands)),
                                                                    _dev(sink, torch.int32, "sink"), C.byref(ops), _stream()))
     return float(ops.value)
+
+
+def calibrate_rescale(workgroups, iters, sink):
+    """Enqueue the register-only rescale loop; returns the number of accumulators it rescales."""
+    torch = _torch()
+    n = C.c_double()
+    _check("qnn_calibrate_rescale", load_library().qnn_calibrate_rescale(int(workgroups), int(iters), _dev(sink, torch.int32, "sink"),
+                                                                         C.byref(n), _stream()))
+    return float(n.value)
 
 
 def calibrate_copy(src, dst):

@@ -1,8 +1,10 @@
 // Calibration kernels for the benchmark: what this very machine sustains on the two resources
 // the hot path is bounded by, measured in the same process as the kernels they are compared with.
 //   qnn_calibrate_mfma: a register-only loop of v_mfma_i32_32x32x32_i8 (no memory traffic at all);
-//   qnn_calibrate_copy: a plain copy with 16 bytes per lane per access.
-// Neither is part of the inference path.
+//   qnn_calibrate_copy: a plain copy with 16 bytes per lane per access;
+//   qnn_calibrate_rescale: the exact rescale of the epilogues (its cheapest form) on registers only:
+//     how many accumulators per second the vector ALU of the chip can turn into output bytes.
+// None is part of the inference path.
 #include "igemm.h"
 
 namespace qnn {
@@ -55,6 +57,41 @@ __global__ void __launch_bounds__(256) calibrate_copy_kernel(const u32x4 *__rest
         __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// Every lane rescales 16 independent accumulators per round with the instruction sequence the
+// epilogues use when act_min >= z_out (add + shift, high multiply, add, 3-way median, shift into a
+// byte of the packed dword) and feeds the packed dwords back into the accumulators, so that nothing
+// can be hoisted out of the loop.  No memory traffic inside the loop.
+__global__ void __launch_bounds__(256) calibrate_rescale_kernel(int iters, int32_t mult, int32_t shift, int32_t *sink)
+{
+    const uint32_t id = blockIdx.x * 256u + threadIdx.x;
+    int32_t acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        uint32_t h = (id * 16u + i + 1u) * 2654435761u;
+        h ^= h >> 15, h *= 2246822519u, h ^= h >> 13;
+        acc[i] = (int32_t)(h >> 10) - (1 << 21); // |acc| < 2^21, as after a K <= 256 reduction
+    }
+    const FusedRescale p = make_fused(mult, shift, (int32_t)(id & 1023u), 3, 3, 255);
+    for (int it = 0; it < iters; ++it) {
+        uint32_t packed[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t x = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x = shift_into_byte(x, rescale_fused_w<false>(acc[4 * q + e], p), p.n1, e);
+            }
+            packed[q] = x;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = (acc[i] ^ (int32_t)(packed[i & 3] >> (i & 12))) & 0x3fffff; // next round's inputs
+    }
+    int32_t t = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += acc[i];
+    sink[id] = t;
+}
+
 } // namespace qnn
 
 using namespace qnn;
@@ -67,6 +104,15 @@ qnn_status qnn_calibrate_mfma(int workgroups, int iters, int random_operands, in
     hipLaunchKernelGGL(calibrate_mfma_kernel, dim3((unsigned)workgroups), dim3(512), 0, as_stream(stream), iters,
                        random_operands, sink);
     *ops = (double)workgroups * 8.0 * (double)iters * 4.0 * 2.0 * 32.0 * 32.0 * 32.0;
+    return launch_status(hipGetLastError());
+}
+
+qnn_status qnn_calibrate_rescale(int workgroups, int iters, int32_t *sink, double *outputs, void *stream)
+{
+    if (workgroups <= 0 || workgroups > 65536 || iters <= 0 || !sink || !outputs) return QNN_EINVAL;
+    hipLaunchKernelGGL(calibrate_rescale_kernel, dim3((unsigned)workgroups), dim3(256), 0, as_stream(stream), iters,
+                       1518500250, 9, sink);
+    *outputs = (double)workgroups * 256.0 * (double)iters * 16.0;
     return launch_status(hipGetLastError());
 }
 
