@@ -382,11 +382,13 @@ __global__ void __launch_bounds__(256) dwconv3x3_dot_kernel(const DwArgs g)
 // vmcnt bookkeeping: every wave issues exactly DPW copies per input row, rows
 // past the end of the segment repeat the last one, "at most (RING - 2) x DPW outstanding" means
 // the oldest row has landed, and the output stores can only make that wait stricter.
+// (Measured: a wait that also allows for the stores issued since -- possible in the steady state, where their
+// number is known -- and even no wait at all leave the time of a launch unchanged.)
 using dw_i32x4 = int32_t __attribute__((ext_vector_type(4)));
 using dw_i32x16 = int32_t __attribute__((ext_vector_type(16)));
 
 template <int S, int MODE>
-__global__ void __launch_bounds__(256, 3) dwconv3x3_mfma_kernel(const DwArgs g, const int seg_rows, const int tiles_w,
+__global__ void __launch_bounds__(256, 2) dwconv3x3_mfma_kernel(const DwArgs g, const int seg_rows, const int tiles_w,
                                                                 const int cblocks)
 {
     constexpr int SLOTS = S == 1 ? 3 : 2, TP = 30, DPW = S, ROW_BYTES = DPW * 1024, RING = S == 1 ? 12 : 8, D = RING - 1;
@@ -425,7 +427,7 @@ __global__ void __launch_bounds__(256, 3) dwconv3x3_mfma_kernel(const DwArgs g, 
     const int steps = S == 1 ? rows + 2 : 2 * rows + 1;
     int issue_t = 0, issue_slot = 0; // next row to copy and the ring row it goes to (scalar)
     int read_t = 0, read_slot = 0;   // next row to consume
-    auto issue_row = [&]() {
+    auto issue_row = [&]() __attribute__((always_inline)) {
         const int t = issue_t < steps ? issue_t : steps - 1; // past the end: repeat the last row (nobody reads that ring row)
         int hi = hi_first + t;
         hi = hi < 0 ? 0 : (hi >= g.H ? g.H - 1 : hi);        // rows outside the image: any row inside (replaced by the padding code)
@@ -506,52 +508,55 @@ __global__ void __launch_bounds__(256, 3) dwconv3x3_mfma_kernel(const DwArgs g, 
     // accumulators start at zero (an inline constant of the matrix instruction); bias and zero-point term join in
     // the rescale, inside the add-and-shift that the 32-bit form needs anyway
     dw_i32x16 acc[SLOTS];
-    auto reset = [&](int slot) {
+    auto reset = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[slot][r] = 0;
     };
-    auto finish = [&](int slot) {
+    auto finish = [&](int slot) __attribute__((always_inline)) {
         // wave-uniform row base (scalar registers) + 32-bit lane offsets
         const int64_t row_off = ((int64_t)__builtin_amdgcn_readfirstlane((int)(out_row >> 32)) << 32) |
                                 (uint32_t)__builtin_amdgcn_readfirstlane((int)out_row);
         uint8_t *out = g.y + row_off;
+        uint32_t x[4];
+        if (fused) { // one test per output row; the general form below is the rare case
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            uint32_t x = 0;
-            if (fused && MODE == 2) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int32_t tt = __mulhi((int32_t)(((uint32_t)acc[slot][4 * q + e] + (uint32_t)init) << 2), mu);
-                    x = shift_into_byte(x, med3_i32(fused_w_from_t<false>(tt, cc), lo, hi_), n1, e);
-                }
-            } else if (fused && MODE == 1) {
+            for (int q = 0; q < 4; ++q) {
+                x[q] = 0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int32_t tt = __mulhi((int32_t)(((uint32_t)acc[slot][4 * q + e] + (uint32_t)init) << 2), mu);
-                    x = shift_into_byte(x, med3_i32(fused_w_from_t<true>(tt, cc), lo, hi_), n1, e);
+                    x[q] = shift_into_byte(x[q], med3_i32(fused_w_from_t<MODE == 1>(tt, cc), lo, hi_), n1, e);
                 }
-            } else {
-                const RescaleParams rp = make_rescale(mu, sf);
+            }
+        } else {
+            const RescaleParams rp = make_rescale(mu, sf);
+#pragma nounroll
+            for (int q = 0; q < 4; ++q) {
+                x[q] = 0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int32_t y = clamp_i32(g.lo_rel, g.hi_rel, rescale_general(acc[slot][4 * q + e] + init, rp)) + g.z_out;
-                    x |= (uint32_t)y << (8 * e);
+                    x[q] |= (uint32_t)y << (8 * e);
                 }
             }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
             // 4 pixels of one channel -> 4 channels of one pixel, across the quad (two exchanges + byte permutes)
-            uint32_t o = (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true);
-            x = __builtin_amdgcn_perm(o, x, sel1);
-            o = (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true);
-            x = __builtin_amdgcn_perm(o, x, sel2);
-            if (o_ok[q]) *reinterpret_cast<uint32_t *>(out + o_off[q]) = x;
+            uint32_t o = (uint32_t)__builtin_amdgcn_mov_dpp((int)x[q], 0xB1, 0xF, 0xF, true);
+            uint32_t v = __builtin_amdgcn_perm(o, x[q], sel1);
+            o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);
+            v = __builtin_amdgcn_perm(o, v, sel2);
+            if (o_ok[q]) *reinterpret_cast<uint32_t *>(out + o_off[q]) = v;
         }
         out_row += out_row_bytes;
     };
 
     dw_i32x4 fa[3], fn[3];
     // requests the LDS read-back of input row read_t into fn (after its copy has landed) and the copy of row read_t + D
-    auto fetch_row = [&]() {
-        __builtin_amdgcn_s_waitcnt((((D - 1) * DPW) & 15) | ((((D - 1) * DPW) >> 4) << 14) | (7 << 4) | (15 << 8)); // vmcnt only
+    auto fetch_row = [&]() __attribute__((always_inline)) {
+        constexpr int N = (D - 1) * DPW;
+        __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8)); // vmcnt only
         asm volatile("" ::: "memory");
         const uint8_t *src = ring + read_slot * ROW_BYTES;
 #pragma unroll
@@ -560,7 +565,7 @@ __global__ void __launch_bounds__(256, 3) dwconv3x3_mfma_kernel(const DwArgs g, 
         issue_row(); // into the ring row that was consumed one step ago
     };
     // fn (raw codes of row read_t) -> fa (signed, padding replaced)
-    auto take_row = [&]() {
+    auto take_row = [&]() __attribute__((always_inline)) {
         const int hi = hi_first + read_t;
         const bool row_ok = hi >= 0 && hi < g.H; // scalar
         if (!row_ok) {
@@ -582,14 +587,57 @@ __global__ void __launch_bounds__(256, 3) dwconv3x3_mfma_kernel(const DwArgs g, 
     };
     // one window column of the current row into one accumulator set (the caller interleaves the sets, so that
     // consecutive matrix instructions do not depend on each other)
-    auto mac1 = [&](int a, int b, int slot) {
+    auto mac1 = [&](int a, int b, int slot) __attribute__((always_inline)) {
         acc[slot] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[b], wq[a][b], acc[slot], 0, 0, 0);
+    };
+
+    // Steady state of the row pipeline, free of run-time conditions: every output row involved exists and every
+    // input row lies inside the image, so a step is LDS read-back, sign flip (EDGE: plus the padding selects of
+    // the window columns that stick out of the image), nine matrix instructions -- the first one of a new output
+    // row takes the constant zero as its accumulator input, which replaces the reset -- and one rescale.
+    const dw_i32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    auto take_inside = [&](auto edge) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            const dw_i32x4 t = fn[b] ^ (int32_t)0x80808080;
+            if constexpr (decltype(edge)::value) {
+                const bool ok = a_ok[b];
+                fa[b] = dw_i32x4{ok ? t.x : fill_s, ok ? t.y : fill_s, ok ? t.z : fill_s, ok ? t.w : fill_s};
+            } else {
+                fa[b] = t;
+            }
+        }
+        ++read_t;
+        read_slot = read_slot + 1 == RING ? 0 : read_slot + 1;
+    };
+    auto mac0 = [&](int b, int slot) __attribute__((always_inline)) { // kernel row 0: window column 0 opens the accumulator set
+        acc[slot] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[b], wq[0][b], b == 0 ? zero16 : acc[slot], 0, 0, 0);
     };
 
     if constexpr (S == 1) {
         // row t is kernel row 0 of output k = t, kernel row 1 of k = t - 1, kernel row 2 of k = t - 2; output k lives
         // in accumulator set k % 3
+        auto steady3 = [&](auto edge) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                fetch_row();
+                take_inside(edge);
+#pragma unroll
+                for (int b = 0; b < 3; ++b) {
+                    mac1(2, b, (u + 1) % 3);
+                    mac1(1, b, (u + 2) % 3);
+                    mac0(b, u);
+                }
+                finish((u + 1) % 3);
+            }
+        };
         for (int t0 = 0; t0 < steps; t0 += 3) {
+            // rows t0 .. t0 + 2: all three outputs of every step exist and all three input rows are inside the image
+            if (t0 >= 2 && t0 + 2 < rows && hi_first + t0 >= 0 && hi_first + t0 + 2 < g.H) { // scalar
+                if (wave_interior) steady3(std::false_type{});
+                else steady3(std::true_type{});
+                continue;
+            }
 #pragma unroll
             for (int u = 0; u < 3; ++u) {
                 const int t = t0 + u;
@@ -615,7 +663,30 @@ __global__ void __launch_bounds__(256, 3) dwconv3x3_mfma_kernel(const DwArgs g, 
         reset(0);
 #pragma unroll
         for (int b = 0; b < 3; ++b) mac1(0, b, 0);
+        auto steady2 = [&](auto edge) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                fetch_row();
+                take_inside(edge);
+#pragma unroll
+                for (int b = 0; b < 3; ++b) mac1(1, b, u);
+                fetch_row();
+                take_inside(edge);
+#pragma unroll
+                for (int b = 0; b < 3; ++b) {
+                    mac1(2, b, u);
+                    mac0(b, u ^ 1);
+                }
+                finish(u);
+            }
+        };
         for (int k0 = 0; k0 < rows; k0 += 2) {
+            // outputs k0, k0 + 1 and k0 + 2 exist and input rows 2 k0 + 1 .. 2 k0 + 4 are inside the image
+            if (k0 + 2 < rows && hi_first + 2 * k0 + 1 >= 0 && hi_first + 2 * k0 + 4 < g.H) { // scalar
+                if (wave_interior) steady2(std::false_type{});
+                else steady2(std::true_type{});
+                continue;
+            }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int k = k0 + u;
@@ -720,10 +791,12 @@ static qnn_status qdwconv2d_impl(const uint8_t *x, int N, int H, int W, int C, i
         // most of the 32-pixel tile and stay with the patch kernel)
         if ((variant == 3 || variant < 0) && (C % 16) == 0 && (reinterpret_cast<uintptr_t>(x) % 16) == 0 &&
             (int64_t)H * W * C < (1ll << 31) && (int64_t)g.Ho * g.Wo * C < (1ll << 31) &&
-            // measured: ahead of the patch kernel on wide stride-2 layers (+8 % at 112 x 112) and once a launch has
-            // more than ~10^8 outputs (+25 %: 0.40 against 0.32 of HBM); behind it on the small layers, whose waves
-            // are too few and too short-lived for the row pipeline to pay off
-            (variant == 3 || (stride_h == 2 && g.Wo >= 48) || (int64_t)N * g.Ho * g.Wo * C >= (100ll << 20))) {
+            // measured: ahead of the patch kernel on stride-2 layers from 56 x 56 inputs up (+15 % at 112 x 112 and
+            // at 56 x 56), by 5 % on stride-1 layers at least 48 pixels wide, and once a launch has more than ~10^8 outputs
+            // (+25 %: 0.40 against 0.32 of HBM); behind it on the small layers, whose image rows fill less than
+            // half of the 30-pixel tile
+            (variant == 3 || (stride_h == 2 && g.Wo >= 24) || (stride_h == 1 && g.Wo >= 48) ||
+             (int64_t)N * g.Ho * g.Wo * C >= (100ll << 20))) {
             const int tiles_w = (g.Wo + 29) / 30, cblocks = (C + 31) / 32; // 30 output pixels per wave
             const int64_t waves_x = (int64_t)tiles_w * cblocks;
             int seg_rows = tuning().dw_rh > 0 ? tuning().dw_rh : 0;
