@@ -220,6 +220,35 @@ def time_skinny_int4(torch, qnn, workloads, synth):
     return rows
 
 
+def time_skinny_large(torch, qnn):
+    """Weight streaming where the bytes, not the launch, set the time: M = 1 and 16 rows against a 16384 x 16384
+    weight matrix (268 MB as int8, 134 MB packed to 4 bits), timed like the other rows."""
+    rows = []
+    N = K = 16384
+    mult = torch.full((N,), 1518500250, dtype=torch.int32, device="cuda:0")
+    shift = torch.full((N,), 14, dtype=torch.int32, device="cuda:0")
+    for bits in (8, 4):
+        for M in (1, 16):
+            nbytes = M * K + K * N * bits // 8 + M * N + 12 * N
+            sets, label = _sets_for(nbytes)
+            fns, keep = [], []
+            for i in range(sets):
+                A = _device_uint8(torch, (M, K), 7100 + i)
+                if bits == 8:
+                    B = _device_uint8(torch, (N, K), 7200 + i).view(torch.int8)
+                else:
+                    B = _device_uint8(torch, (N, K // 2), 7300 + i)
+                C = torch.empty((M, N), dtype=torch.uint8, device="cuda:0")
+                keep.append((A, B, C))
+                fns.append(qnn.prepare_qgemm(A, 128, B, mult, shift, 128, 0, 255, C, weight_bits=bits))
+            t = graph_time(torch, fns, est_s=5e-5)
+            rows.append(dict(M=M, N=N, K=K, weight_bits=bits, us=round(t * 1e6, 2), tops=round(2.0 * M * N * K / t * 1e-12, 2),
+                             gbs=round(nbytes / t * 1e-9, 1), bound="hbm", frac=round(nbytes / (PEAK_HBM_GBS * 1e9) / t, 3),
+                             sets=sets, memory=label))
+            del fns, keep
+    return rows
+
+
 # ----------------------------------------------------------------------------- conv stacks
 
 def _layer_launches(torch, qnn, synth, workloads, l, batch, seed, sets):
@@ -609,6 +638,7 @@ def main():
 
     if not args.no_secondary:
         result["gemm_rows_int4_skinny"] = time_skinny_int4(torch, qnn, workloads, synth)
+        result["gemm_rows_skinny_16384"] = time_skinny_large(torch, qnn)
         result["calibration"] = calibrate(torch, qnn)
         sec = {}
         sec["streaming"] = time_streaming(torch, qnn)

@@ -45,7 +45,59 @@ __global__ void __launch_bounds__(512) skinny_gemm_kernel(const IgemmArgs g)
     const bool need_colsum = g.z_a != 128;
 
     const int ksteps = g.K / BK; // K % 64 == 0 (dispatcher)
-    for (int ks0 = wave; ks0 < ksteps; ks0 += NW * UNROLL) {
+    // 4-bit weights, wide form: a lane fetches 16 bytes = 32 consecutive weights per load, so that as many weight
+    // bytes are in flight as with 8-bit weights (the kernel lives on memory-level parallelism).  The 32 weights
+    // feed two matrix instructions; the reduction index is renumbered for that -- quarter q of the lanes takes
+    // k = 128 s + 32 q + 16 h + (0..15) in instruction h of step s, on both operands alike, and a sum does not care
+    // about the order of its terms.
+    bool wide = false;
+    if constexpr (INT4) wide = (g.K & 127) == 0 && (g.ldb & 31) == 0 && (reinterpret_cast<uintptr_t>(g.B) & 15) == 0;
+    if constexpr (INT4) {
+        if (wide) {
+            constexpr int UW = MT >= 4 ? 2 : 4;
+            const int steps2 = g.K / 128, kq = (lane >> 4) * 32;
+            for (int s0 = wave; s0 < steps2; s0 += NW * UW) {
+                u32x4 raw[UW];
+                i32x4 fa[UW][2][MT];
+#pragma unroll
+                for (int u = 0; u < UW; ++u) {
+                    const int st = s0 + u * NW;
+                    const int k = (st < steps2 ? st : steps2 - 1) * 128 + kq; // past the end: re-read, ignored below
+                    raw[u] = *reinterpret_cast<const u32x4 *>(brow + (k >> 1));
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) {
+                        fa[u][0][t] = *reinterpret_cast<const i32x4 *>(arow[t] + k);
+                        fa[u][1][t] = *reinterpret_cast<const i32x4 *>(arow[t] + k + 16);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UW; ++u) {
+                    if (s0 + u * NW >= steps2) break;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        i32x4 fb; // dword d of raw holds weights 8d .. 8d+7, two per byte, low nibble first; kept times 16
+#pragma unroll
+                        for (int d = 0; d < 2; ++d) {
+                            const uint32_t r = raw[u][2 * h + d];
+                            const uint32_t even = (r << 4) & 0xF0F0F0F0u, odd = r & 0xF0F0F0F0u;
+                            fb[2 * d] = (int32_t)__builtin_amdgcn_perm(odd, even, 0x05010400u);
+                            fb[2 * d + 1] = (int32_t)__builtin_amdgcn_perm(odd, even, 0x07030602u);
+                        }
+                        if (need_colsum) {
+#pragma unroll
+                            for (int d = 0; d < 4; ++d) colsum = __builtin_amdgcn_sdot4(fb[d], 0x01010101, colsum, false);
+                        }
+#pragma unroll
+                        for (int t = 0; t < MT; ++t) {
+                            const i32x4 xs = fa[u][h][t] ^ (int32_t)0x80808080;
+                            acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fb, xs, acc[t], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    for (int ks0 = wave; ks0 < (wide ? 0 : ksteps); ks0 += NW * UNROLL) {
         i32x4 fb[UNROLL];       // weights
         i32x4 fa[UNROLL][MT];   // activations
 #pragma unroll

@@ -794,7 +794,8 @@ def test_qgemm_default_plan_large_shape_sampled_rows():
 # ------------------------------------------------------------ few-row (weight streaming) kernel
 
 @pytest.mark.parametrize("M,N,K", [(1, 16, 64), (5, 50, 192), (16, 33, 64), (17, 100, 1024), (33, 257, 576), (64, 48, 4096),
-                                   (48, 1000, 128)])
+                                   (48, 1000, 128), (1, 40, 128), (3, 64, 384), (32, 20, 2048), (64, 16, 256), (2, 7, 8192),
+                                   (20, 130, 1152)])
 @pytest.mark.parametrize("bits", [8, 4])
 def test_qgemm_few_rows_matches_oracle(M, N, K, bits):
     assert qnn.qgemm_plan(M, N, K) == "skinny16"
