@@ -31,7 +31,11 @@
  *     never synchronise.  Output buffers must not overlap input buffers.
  *   - Return value: QNN_OK, or an error code; on error nothing is enqueued.
  *     QNN_EINVAL      a null pointer, a non-positive size, a parameter outside
- *                     the documented range;
+ *                     the documented range.  An EMPTY input is not an error: n == 0
+ *                     elements, M == 0 rows of a product, or N == 0 images of a
+ *                     convolution return QNN_OK without enqueuing anything and
+ *                     without looking at the pointers (all other sizes must be
+ *                     positive);
  *     QNN_EUNSUPPORTED a documented feature this build does not implement;
  *     QNN_ELAUNCH     the HIP runtime refused the launch (qnn_last_error()
  *                     gives the HIP error text).

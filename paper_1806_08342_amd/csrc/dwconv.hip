@@ -747,11 +747,12 @@ static qnn_status qdwconv2d_impl(const uint8_t *x, int N, int H, int W, int C, i
                                  const int32_t *shift, int32_t z_out, int32_t act_min, int32_t act_max, uint8_t *y,
                                  void *stream, const int32_t *z_w)
 {
-    if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
-    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || kh <= 0 || kw <= 0 || kh > 7 || kw > 7) return QNN_EINVAL;
+    if (N < 0 || H <= 0 || W <= 0 || C <= 0 || kh <= 0 || kw <= 0 || kh > 7 || kw > 7) return QNN_EINVAL;
     if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return QNN_EINVAL;
     if (H + 2 * (int64_t)pad_h < kh || W + 2 * (int64_t)pad_w < kw) return QNN_EINVAL;
     if (z_x < 0 || z_x > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
+    if (N == 0) return QNN_OK; // an empty batch: nothing to compute, no pointer is looked at
+    if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
     DwArgs g = {};
     g.x = x, g.w = w, g.y = y, g.bias = bias, g.mult = mult, g.shift = shift, g.zw = z_w;
     g.N = N, g.H = H, g.W = W, g.C = C, g.kh = kh, g.kw = kw;

@@ -377,13 +377,14 @@ static qnn_status qgemm_impl(const uint8_t *A, int64_t lda, int32_t z_a, const v
                              int64_t ldc, void *workspace, size_t workspace_bytes, void *stream, const uint8_t *residual,
                              int64_t ldr, const qnn_add_params *add, const int32_t *z_w = nullptr)
 {
-    if (!A || !B || !mult || !shift || !C) return QNN_EINVAL;
-    if (M <= 0 || N <= 0 || K <= 0 || K > 65536 || N > 0x7fffffff || lda < K || ldc < N) return QNN_EINVAL;
+    if (M < 0 || N <= 0 || K <= 0 || K > 65536 || N > 0x7fffffff || lda < K || ldc < N) return QNN_EINVAL;
     if (z_a < 0 || z_a > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
     if (weight_bits != 8 && weight_bits != 4) return QNN_EINVAL;
     if (b_layout != QNN_B_COLUMNS_CONTIGUOUS && b_layout != QNN_B_ROWS_CONTIGUOUS) return QNN_EINVAL;
     if (b_layout == QNN_B_COLUMNS_CONTIGUOUS ? ldb < K : ldb < N) return QNN_EINVAL;
     if (weight_bits == 4 && (b_layout != QNN_B_COLUMNS_CONTIGUOUS || (K % 2) || (ldb % 2))) return QNN_EINVAL;
+    if (M == 0) return QNN_OK; // an empty batch: nothing to compute, no pointer is looked at
+    if (!A || !B || !mult || !shift || !C) return QNN_EINVAL;
 
     IgemmArgs g = {};
     g.A = A, g.lda = lda;
@@ -409,14 +410,15 @@ static qnn_status qconv2d_impl(const uint8_t *x, int N, int H, int W, int Cin, i
                                void *stream, const uint8_t *residual, const qnn_add_params *add,
                                const int32_t *z_w = nullptr)
 {
-    if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
-    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0) return QNN_EINVAL;
+    if (N < 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0) return QNN_EINVAL;
     if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return QNN_EINVAL;
     if (H + 2 * (int64_t)pad_h < kh || W + 2 * (int64_t)pad_w < kw) return QNN_EINVAL;
     const int64_t K = (int64_t)kh * kw * Cin;
     if (K > 65536 || z_x < 0 || z_x > 255 || bad_out_range(z_out, act_min, act_max)) return QNN_EINVAL;
     if (weight_bits != 8 && weight_bits != 4) return QNN_EINVAL;
     if (weight_bits == 4 && (Cin % 2)) return QNN_EINVAL;
+    if (N == 0) return QNN_OK; // an empty batch: nothing to compute, no pointer is looked at
+    if (!x || !w || !mult || !shift || !y) return QNN_EINVAL;
     const int Ho = (H + 2 * pad_h - kh) / stride_h + 1, Wo = (W + 2 * pad_w - kw) / stride_w + 1;
 
     IgemmArgs g = {};

@@ -791,6 +791,20 @@ def test_qgemm_default_plan_large_shape_sampled_rows():
     assert_same(got[rows], want, "qgemm 4096x4096x512 sampled rows")
 
 
+def test_empty_batches_are_no_ops():
+    import torch
+    z = lambda *shape, dt=torch.uint8: torch.empty(shape, dtype=dt, device="cuda:0")
+    mult = torch.full((8,), 1 << 30, dtype=torch.int32, device="cuda:0")
+    shift = torch.full((8,), 5, dtype=torch.int32, device="cuda:0")
+    assert tuple(qnn.qgemm(z(0, 64), 128, z(8, 64, dt=torch.int8), mult, shift, 0, 0, 255).shape) == (0, 8)
+    w = z(8, 3, 3, 16, dt=torch.int8)
+    assert tuple(qnn.qconv2d(z(0, 9, 9, 16), 3, w, (1, 1), (1, 1), mult, shift, 0, 0, 255).shape) == (0, 9, 9, 8)
+    wd = z(3, 3, 8, dt=torch.int8)
+    assert tuple(qnn.qdwconv2d(z(0, 9, 9, 8), 3, wd, (2, 2), (1, 1), mult, shift, 0, 0, 255).shape) == (0, 5, 5, 8)
+    assert qnn.quantize(z(0, dt=torch.float32), 0.1, 3).numel() == 0
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------ few-row (weight streaming) kernel
 
 @pytest.mark.parametrize("M,N,K", [(1, 16, 64), (5, 50, 192), (16, 33, 64), (17, 100, 1024), (33, 257, 576), (64, 48, 4096),

@@ -102,7 +102,8 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     assert g(bits=4, layout=1) == EINVAL                    # 4-bit needs contiguous columns
     assert g(lda=8) == EINVAL
     assert g(z_a=256) == EINVAL
-    assert g(M=0) == EINVAL
+    assert g(M=0) == 0                                      # an empty batch is a no-op
+    assert g(M=-1) == EINVAL
     assert g(mult=null) == EINVAL
     conv = lambda **kw: lib.qnn_qconv2d(*[kw.get(k, d) for k, d in [
         ("x", p), ("N", 1), ("H", 8), ("W", 8), ("Cin", 16), ("z_x", 0), ("w", p), ("Cout", 8), ("kh", 3), ("kw", 3),
@@ -113,6 +114,8 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     assert conv(bits=4, Cin=15) == EINVAL
     assert conv(Cin=8192) == EINVAL                          # kh*kw*Cin > 65536
     assert conv(lo=-1) == EINVAL
+    assert conv(N=0, x=null, y=null) == 0                    # an empty batch is a no-op
+    assert conv(N=-1) == EINVAL
     dw = lambda **kw: lib.qnn_qdwconv2d(*[kw.get(k, d) for k, d in [
         ("x", p), ("N", 1), ("H", 8), ("W", 8), ("C", 16), ("z_x", 0), ("w", p), ("kh", 3), ("kw", 3), ("sh", 1),
         ("sw", 1), ("ph", 1), ("pw", 1), ("bias", null), ("mult", p), ("shift", p), ("z_out", 0), ("lo", 0),
@@ -120,6 +123,8 @@ def test_device_entry_points_reject_bad_arguments_before_launching(lib):
     assert dw(kh=9) == EINVAL
     assert dw(z_x=-1) == EINVAL
     assert dw(w=null) == EINVAL
+    assert dw(N=0, x=null, y=null) == 0
+    assert dw(N=-2) == EINVAL
     assert lib.qnn_qadd(p, 0, 1, 0, p, 0, 1, 0, 23, 1, 0, 0, 0, 255, p, 16, None) == EINVAL   # left_shift > 22
     assert lib.qnn_qadd(p, 0, 1, 40, p, 0, 1, 0, 20, 1, 0, 0, 0, 255, p, 16, None) == EINVAL  # shift out of range
     assert lib.qnn_qadd(null, 0, 1, 0, null, 0, 1, 0, 20, 1, 0, 0, 0, 255, null, 0, None) == 0
