@@ -73,6 +73,10 @@ static Plan choose_plan(int64_t M, int64_t N, int64_t K, bool dma_ok, bool int4,
             if (N <= 64) return Plan{TILE_DMA_256x64_S3, 1};
             if (N >= 128) return Plan{TILE_DMA_128x128_S3, 1};
         } else {
+            // short reductions over several rounds of tiles: the 4-wave 128x256 tile with two workgroups per CU, whose
+            // epilogues run under the other workgroup's loop (measured 11-25 % ahead of the 8-wave tiles for
+            // K = 320 ... 512 from two rounds on, 5 % at K = 768, level at K = 1024 and on single rounds)
+            if (K <= 768 && N >= 256 && ((M + 127) / 128) * ((N + 255) / 256) >= 1024) return Plan{TILE_DMA_128x256_P, 1};
             // pick the configuration with the least padded work: whole waves of workgroups over the
             // chip, weighted by the measured relative MFMA rate of each configuration
             struct Cand { TileConfig t; int per_cu; double rate; };
