@@ -796,7 +796,10 @@ static qnn_status qdwconv2d_impl(const uint8_t *x, int N, int H, int W, int C, i
             // at 56 x 56), by 5 % on stride-1 layers at least 48 pixels wide, and once a launch has more than ~10^8 outputs
             // (+25 %: 0.40 against 0.32 of HBM); behind it on the small layers, whose image rows fill less than
             // half of the 30-pixel tile
-            (variant == 3 || (stride_h == 2 && g.Wo >= 24) || (stride_h == 1 && g.Wo >= 48) ||
+            // (and never below 2^21 outputs: a few dozen waves walking their segments row by row take longer than the
+            // patch kernel's thousands of independent lanes -- 9 against 4 us on one 112 x 112 x 32 image)
+            (variant == 3 ||
+             ((int64_t)N * g.Ho * g.Wo * C >= (1ll << 21) && ((stride_h == 2 && g.Wo >= 24) || (stride_h == 1 && g.Wo >= 48))) ||
              (int64_t)N * g.Ho * g.Wo * C >= (100ll << 20))) {
             const int tiles_w = (g.Wo + 29) / 30, cblocks = (C + 31) / 32; // 30 output pixels per wave
             const int64_t waves_x = (int64_t)tiles_w * cblocks;
