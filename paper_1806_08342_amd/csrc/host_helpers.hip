@@ -33,6 +33,7 @@ static const TuningField kTuningFields[] = {
     {"QNN_DW_MAD", &Tuning::dw_mad, 0},           {"QNN_GEMM_PRIO", &Tuning::gemm_prio, -1},
     {"QNN_PERSIST", &Tuning::persist, -1},        {"QNN_DW_VARIANT", &Tuning::dw_variant, -1},
     {"QNN_DW_XCD", &Tuning::dw_xcd, 1},
+    {"QNN_SHORTK_ALDS", &Tuning::shortk_alds, 1},
 };
 
 static bool tuning_assign(Tuning &t, const char *name, const char *value)

@@ -20,11 +20,18 @@ static void launch_shortk_add(const ShortKArgs &a, int64_t waves, hipStream_t s)
     hipLaunchKernelGGL(kernel, dim3((unsigned)((waves + kWaves - 1) / kWaves)), dim3(kWaves * 64), kLds, s, a);
 }
 
-template <int KS, bool INT4, int VEC> static void launch_shortk_one(const ShortKArgs &a, int64_t waves, hipStream_t s)
+template <int KS, bool INT4, int VEC> static void launch_shortk_one(const ShortKArgs &a, int64_t waves, hipStream_t s, bool alds)
 {
     constexpr int NB = KS <= 4 ? 4 : 2;
     // weights: 16-byte loads when every 16-element piece of a column is 16-byte aligned, else dwords
     const bool b16 = !INT4 && aligned_to(a.g.B, 16) && (a.g.ldb % 16) == 0 && (a.g.K % 16) == 0;
+    if constexpr (VEC == 16 && (KS == 4 || KS == 8)) {
+        if (alds) { // A rows through LDS, shared by the waves of a workgroup (the caller sized `waves` in workgroups)
+            if (b16) hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 16, 0, true>), dim3((unsigned)waves), dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 4, 0, true>), dim3((unsigned)waves), dim3(256), 0, s, a);
+            return;
+        }
+    }
     if constexpr (VEC == 16) {
         if (a.g.R) { // residual add in the store phase (the launcher only leaves R set for VEC == 16)
             // from 2^24 outputs on the 65536-entry pair table pays for itself; below, two 256-entry tables
@@ -39,12 +46,12 @@ template <int KS, bool INT4, int VEC> static void launch_shortk_one(const ShortK
     else hipLaunchKernelGGL((shortk_kernel<NB, KS, INT4, VEC, 4>), dim3(blocks), dim3(256), 0, s, a);
 }
 
-template <bool INT4, int VEC> static void launch_shortk_ks(const ShortKArgs &a, int ks, int64_t waves, hipStream_t s)
+template <bool INT4, int VEC> static void launch_shortk_ks(const ShortKArgs &a, int ks, int64_t waves, hipStream_t s, bool alds)
 {
-    if (ks <= 1) launch_shortk_one<1, INT4, VEC>(a, waves, s);
-    else if (ks <= 2) launch_shortk_one<2, INT4, VEC>(a, waves, s);
-    else if (ks <= 4) launch_shortk_one<4, INT4, VEC>(a, waves, s);
-    else launch_shortk_one<8, INT4, VEC>(a, waves, s);
+    if (ks <= 1) launch_shortk_one<1, INT4, VEC>(a, waves, s, false);
+    else if (ks <= 2) launch_shortk_one<2, INT4, VEC>(a, waves, s, false);
+    else if (ks <= 4) launch_shortk_one<4, INT4, VEC>(a, waves, s, alds);
+    else launch_shortk_one<8, INT4, VEC>(a, waves, s, alds);
 }
 
 bool shortk_eligible(const IgemmArgs &g, int b_mode, bool strided)
@@ -79,19 +86,34 @@ qnn_status launch_shortk(IgemmArgs &g, int b_mode, bool strided, hipStream_t s)
     const int64_t per_walker = (row_blocks + walkers - 1) / walkers;
     walkers = (row_blocks + per_walker - 1) / per_walker;
     a.walkers = (int)walkers;
-    const int64_t waves = walkers * a.col_groups;
+    int64_t waves = walkers * a.col_groups;
     if (waves > 0x7fffffff) return QNN_EINVAL;
     const int64_t row_pitch = strided ? g.Cin : g.lda;
     const bool v16 = aligned_to(g.A, 16) && (row_pitch % 16) == 0 && (g.K % 16) == 0;
     // the add is built into the 16-byte variants only, for outputs and residuals made of whole aligned chunks
     const bool add_pass = g.R != nullptr && !add_fused;
     if (add_pass) a.g.R = nullptr;
+    // K = 128 / 256 with enough column groups to fill a workgroup: the A rows go through LDS once per workgroup.
+    // Not with the add built in: its 8-wave workgroups (one per CU, sharing the table of code pairs) lose more at
+    // the barrier of every row block than the shared rows save (measured 65 against 58 us on 50176 x 1024 x 256).
+    const int wg_waves = 4;
+    const bool alds = tuning().shortk_alds != 0 && !strided && v16 && !a.g.R && (g.K == 128 || g.K == 256) && a.col_groups >= wg_waves;
+    if (alds) {
+        const int64_t groups = (a.col_groups + wg_waves - 1) / wg_waves;
+        const int64_t resident_wgs = 256 * 2;
+        int64_t wk = resident_wgs / groups;
+        wk = wk < 1 ? 1 : (wk > row_blocks ? row_blocks : wk);
+        const int64_t per = (row_blocks + wk - 1) / wk;
+        wk = (row_blocks + per - 1) / per;
+        a.walkers = (int)wk;
+        waves = groups * wk; // workgroups
+    }
     if (b_mode == B_INT4) {
-        if (v16) launch_shortk_ks<true, 16>(a, ks, waves, s);
-        else launch_shortk_ks<true, 8>(a, ks, waves, s);
+        if (v16) launch_shortk_ks<true, 16>(a, ks, waves, s, alds);
+        else launch_shortk_ks<true, 8>(a, ks, waves, s, false);
     } else {
-        if (v16) launch_shortk_ks<false, 16>(a, ks, waves, s);
-        else launch_shortk_ks<false, 8>(a, ks, waves, s);
+        if (v16) launch_shortk_ks<false, 16>(a, ks, waves, s, alds);
+        else launch_shortk_ks<false, 8>(a, ks, waves, s, false);
     }
     const qnn_status st = launch_status(hipGetLastError());
     if (st != QNN_OK || !add_pass) return st;

@@ -64,11 +64,23 @@ struct ShortKColumn {
 // from LDS to global memory; the residual chunks of a row block are requested one round ahead.
 // The add is a function of two 8-bit codes, so the workgroup (8 waves here, to share it) first
 // tabulates all 65536 results in LDS; combining a pair of codes is then one byte gather.
-template <int NB, int KS, bool INT4, int VEC, int BVEC, int ADD = 0> // ADD: 0 none, 1 two 256-entry tables, 2 pair table
+// ALDS (K = 128 or 256, plain matrices, 16-byte aligned rows): the A rows of a row block are shared by the waves
+// of a workgroup, which then own neighbouring column groups of the SAME rows.  The block's 32 x K bytes are
+// copied once per workgroup straight into LDS (global_load_lds_dwordx4, whole 128-byte lines per 8 lanes, next
+// block's copy in flight during the current block) and every wave reads its fragments from there.  Fetching the
+// fragments from global memory costs one vector-cache access per lane and instruction (every lane is on a row
+// of its own): counters showed the address unit busy for 58 % and the vector cache for 70-80 % of that kernel's
+// time, on a par with the vector ALU.  LDS positions are XOR-swizzled on the global-address side, so that the
+// 16 lanes that share a cycle of a 16-byte LDS read hit 16 different bank groups.
+template <int NB, int KS, bool INT4, int VEC, int BVEC, int ADD = 0, bool ALDS = false> // ADD: 0 none, 1 two 256-entry tables, 2 pair table
 __global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 ? 3 : 2)) shortk_kernel(const ShortKArgs s)
 {
     constexpr int PITCH = 32 * NB + 32; // bytes per staged output row: the 8 rows a store instruction touches fall in distinct banks
     constexpr int WAVES = ADD == 2 ? 8 : 4; // the pair table is shared by 8 waves (one workgroup per CU)
+    constexpr int KBYTES = KS * 32, CPR = KBYTES / 16; // ALDS: bytes and 16-byte chunks of an A row (K == KS * 32)
+    constexpr int ATILE = 32 * KBYTES;
+    static_assert(!ALDS || (KS == 4 || KS == 8), "the staged form exists for K = 128 and K = 256");
+    __shared__ __attribute__((aligned(16))) uint8_t a_tiles[ALDS ? 2 * ATILE : 16];
     __shared__ __attribute__((aligned(16))) uint8_t stage_static[ADD ? 16 : 4 * 32 * PITCH];
     extern __shared__ __attribute__((aligned(16))) uint8_t dyn_lds[]; // ADD: [table(s)][output tiles of the waves]
     uint8_t *const pair_tab = dyn_lds;
@@ -100,9 +112,19 @@ __global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 
     const int frow = lane & 31, fhalf = lane >> 5;
 
     // wave -> (column group, walker): neighbouring waves take neighbouring column groups of the same rows
-    const int64_t gw = (int64_t)blockIdx.x * WAVES + wave;
-    const int cg = (int)(gw % s.col_groups), walker = (int)(gw / s.col_groups);
-    if (walker >= s.walkers) return; // no barriers below: a wave may leave alone
+    int cg, walker;
+    bool active = true; // ALDS: a wave beyond the last column group only helps with the copies and the barriers
+    if constexpr (ALDS) {
+        const int groups = (s.col_groups + WAVES - 1) / WAVES; // workgroups side by side; the grid is groups x walkers
+        cg = (int)(blockIdx.x % groups) * WAVES + wave;
+        walker = (int)(blockIdx.x / groups);
+        active = cg < s.col_groups;
+        cg = active ? cg : s.col_groups - 1;
+    } else {
+        const int64_t gw = (int64_t)blockIdx.x * WAVES + wave;
+        cg = (int)(gw % s.col_groups), walker = (int)(gw / s.col_groups);
+        if (walker >= s.walkers) return; // no barriers below: a wave may leave alone
+    }
     const int n0 = cg * 32 * NB;
     const int blocks_here = (g.N - n0 + 31) / 32 < NB ? (g.N - n0 + 31) / 32 : NB; // column blocks that exist
 
@@ -177,6 +199,31 @@ __global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 
         for (int ks = 0; ks < KS; ++ks) fa[ks] = shortk_load16<VEC>(p, ks * 32, g.K - fhalf * 16);
     };
 
+    // ALDS: copy of row block rbx into a_tiles[buf]; wave w, pass i moves LDS chunks (i * WAVES + w) * 64 + lane:
+    // LDS chunk q = (row, position p) holds global chunk p ^ swz(row) of that row
+    auto swz = [](int row) { return CPR == 16 ? (row & 15) : ((row >> 1) & 7); };
+    auto issue_tile = [&](int rbx, int buf) __attribute__((always_inline)) {
+        constexpr int PASSES = (32 * CPR + WAVES * 64 - 1) / (WAVES * 64);
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            const int q0 = (i * WAVES + wave) * 64; // wave-uniform
+            if (q0 >= 32 * CPR) break;
+            const int q = q0 + lane;
+            const int row = q / CPR, pos = q % CPR;
+            int m = rbx * 32 + row;
+            m = m < M ? m : M - 1;
+            const uint8_t *src = g.A + (int64_t)m * g.lda + ((pos ^ swz(row)) * 16);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(a_tiles + buf * ATILE + q0 * 16), 16, 0, 0);
+        }
+    };
+    auto read_tile = [&](int buf, i32x4 (&fa)[KS]) __attribute__((always_inline)) {
+        const uint8_t *base = a_tiles + buf * ATILE + frow * KBYTES;
+        const int sw = swz(frow);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) fa[ks] = *reinterpret_cast<const i32x4 *>(base + (((2 * ks + fhalf) ^ sw) * 16));
+    };
+
     // lane-invariant parts of the LDS and global addresses of the output tile
     int st_lds[NB], st_row[NB];
     bool st_col_ok[NB];
@@ -186,7 +233,7 @@ __global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 
         const int idx = i * 64 + lane;
         st_row[i] = idx / (2 * NB);
         const int col0 = n0 + (idx % (2 * NB)) * 16;
-        st_col_ok[i] = col0 < g.N;
+        st_col_ok[i] = col0 < g.N && active;
         st_lds[i] = st_row[i] * PITCH + (idx % (2 * NB)) * 16;
         st_off[i] = (int64_t)st_row[i] * g.ldc + col0;
     }
@@ -287,9 +334,20 @@ __global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 
     auto walk = [&](auto mode_tag) { // 0: general rescale, 1: fused form, 2: fused form without the tie term
     constexpr bool FUSED = decltype(mode_tag)::value > 0, TIES = decltype(mode_tag)::value == 1;
     i32x4 fa[KS];
-    int rb = walker, rb_stored = -1;
-    if (rb < row_blocks) load_rows(rb, fa);
-    for (; rb < row_blocks; rb += s.walkers) {
+    int rb = walker, rb_stored = -1, turn = 0;
+    if constexpr (ALDS) { // two copies in flight; the first block's fragments are in registers before the loop
+        if (rb < row_blocks) {
+            issue_tile(rb, 0);
+            if (rb + s.walkers < row_blocks) issue_tile(rb + s.walkers, 1);
+            __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); // vmcnt(0)
+            asm volatile("" ::: "memory");
+            __syncthreads();
+            read_tile(0, fa);
+        }
+    } else {
+        if (rb < row_blocks) load_rows(rb, fa);
+    }
+    for (; rb < row_blocks; rb += s.walkers, turn ^= 1) {
         i32x16 acc[NB];
 #pragma unroll
         for (int j = 0; j < NB; ++j)
@@ -302,11 +360,27 @@ __global__ void __launch_bounds__(ADD == 2 ? 512 : 256, ADD == 2 ? 1 : (KS <= 1 
             for (int j = 0; j < NB; ++j)
                 acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xs, fb[ks][j], acc[j], 0, 0, 0); // columns past N: clamped loads, never stored
         }
+        if constexpr (ALDS) {
+            // The fragments are consumed.  The next block's copy (issued one round ago, like every store still
+            // outstanding) has landed in this wave's part; after the barrier in all parts, and every wave has read
+            // the current block (one round ago), whose buffer the copy of the block after next may overwrite.
+            // The read-back of the next block's fragments then passes under the epilogue below.
+            if (rb + s.walkers < row_blocks) { // uniform over the workgroup
+                __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8)); // vmcnt(0)
+                asm volatile("" ::: "memory");
+                __syncthreads();
+                read_tile(turn ^ 1, fa);
+                asm volatile("" ::: "memory");
+                if (rb + 2 * s.walkers < row_blocks) issue_tile(rb + 2 * s.walkers, turn);
+            }
+        }
         if (rb_stored >= 0) store_block(rb_stored);
         if constexpr (ADD) load_res(rb); // used one round from now, when this block is stored
         // the fragments are consumed: fetch the next block's into the same registers now, so that
         // the loads are in flight during the epilogue
-        if (rb + s.walkers < row_blocks) load_rows(rb + s.walkers, fa);
+        if constexpr (!ALDS) {
+            if (rb + s.walkers < row_blocks) load_rows(rb + s.walkers, fa);
+        }
 
         // ---- epilogue into the wave's LDS tile: after the 4x4 byte transposition inside each
         // quad of lanes a lane holds 4 consecutive columns of one row

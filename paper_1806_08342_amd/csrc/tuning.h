@@ -17,6 +17,7 @@ struct Tuning {
     int gemm_prio = -1;       // QNN_GEMM_PRIO: issue-priority scheme of the pipelined tile kernel (-1 = per tile)
     int persist = -1;         // QNN_PERSIST: 0 = one workgroup per tile, 1 = persistent workgroups, -1 = per tile
     int dw_variant = -1;      // QNN_DW_VARIANT: depthwise kernel family (-1 = choose)
+    int shortk_alds = 1;      // QNN_SHORTK_ALDS: short-K kernel with the A rows staged in LDS per workgroup (K = 128, 256)
     int dw_xcd = 1;           // QNN_DW_XCD: depthwise workgroups renumbered so that an XCD gets neighbouring patches
     bool forced() const { return force_tile[0] != 0; }
 };

@@ -76,6 +76,21 @@ def test_qgemm_add_pair_table(M, N, K, bits):
                     act="none")
 
 
+@pytest.mark.parametrize("alds", [1, 0])
+@pytest.mark.parametrize("M,N,K,bits", [(1000, 512, 128, 8), (4099, 520, 256, 8), (133, 1030, 128, 4), (2500, 256, 256, 4),
+                                         (16400, 1024, 256, 8),   # 2^24 outputs: 8-wave workgroups with the table of code pairs
+                                         (33000, 1024, 128, 4)])
+def test_qgemm_add_short_k_rows_through_lds(tuning, alds, M, N, K, bits):
+    # K = 128 / 256 with at least one workgroup's worth of column groups: without an add these shapes stage the A
+    # rows in LDS once per workgroup; with the add built in they keep the direct loads whatever the switch says,
+    # and as a second pass behind the staged kernel when the operands are not made of whole aligned chunks
+    tuning.setenv("QNN_SHORTK_ALDS", str(alds))
+    assert qnn.qgemm_plan(M, N, K) == "shortk"
+    _check_gemm_add(M, N, K, 4300 + M + N + K + bits, f"qgemm_add short-K through LDS={alds} {M}x{N}x{K} bits={bits}", bits=bits)
+    _check_gemm_add(M, N, K, 4400 + M + N + K + bits, f"qgemm_add short-K through LDS={alds} {M}x{N}x{K} bits={bits}, general add rescale",
+                    bits=bits, odd=True, act="none")
+
+
 @pytest.mark.parametrize("tile", ["dma128x128", "dma256x256", "dma256x64", "dma256x128", "dma128x128s3", "dma64x64",
                                   "dma256x64s3", "128x128", "64x64"])
 @pytest.mark.parametrize("M,N,K", [(300, 270, 512), (513, 130, 320)])

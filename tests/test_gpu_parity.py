@@ -791,6 +791,33 @@ def test_qgemm_default_plan_large_shape_sampled_rows():
     assert_same(got[rows], want, "qgemm 4096x4096x512 sampled rows")
 
 
+@pytest.mark.parametrize("alds", [1, 0])
+@pytest.mark.parametrize("M,N,K", [(1, 256, 256), (31, 300, 256), (100, 256, 256), (1000, 300, 256), (33, 512, 128), (5000, 1024, 128),
+                                   (4097, 520, 256), (65, 8192, 256), (7000, 2100, 128)])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_qgemm_short_k_rows_through_lds(tuning, alds, M, N, K, bits):
+    # short-K kernel with the A rows copied to LDS once per workgroup (K = 128 / 256): ragged row blocks, column
+    # counts that leave a workgroup with idle waves, one and many walkers; the switch off = direct fragment loads
+    tuning.setenv("QNN_SHORTK_ALDS", str(alds))
+    if M > 64:
+        assert qnn.qgemm_plan(M, N, K) == "shortk"
+    rng = np.random.default_rng(1600 + M + N + K + bits)
+    A = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    A[0, :] = 255
+    A[-1, :] = 0
+    lim = 8 if bits == 4 else 128
+    Bt = rng.integers(-lim, lim, (N, K)).astype(np.int8)
+    Bt[0, :] = -lim
+    B = oracle.pack_int4(Bt) if bits == 4 else Bt
+    real = 10 ** rng.uniform(-4.2, -3.2, N) / np.sqrt(K / 64.0) * (16.0 if bits == 4 else 1.0)
+    mult, shift = oracle.quantize_multipliers(real)
+    bias = rng.integers(-20000, 20000, N).astype(np.int32)
+    for z_a, lo in ((0, 0), (128, 120), (255, 0)):
+        want = oracle.qgemm(A, z_a, B, mult, shift, 120, lo, 250, bias=bias, weight_bits=bits)
+        got = host(qnn.qgemm(dev(A), z_a, dev(B), dev(mult), dev(shift), 120, lo, 250, bias=dev(bias), weight_bits=bits))
+        assert_same(got, want, f"short-K through LDS={alds} {M}x{N}x{K} bits={bits} z_a={z_a}")
+
+
 def test_empty_batches_are_no_ops():
     import torch
     z = lambda *shape, dt=torch.uint8: torch.empty(shape, dtype=dt, device="cuda:0")
