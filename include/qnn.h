@@ -41,7 +41,8 @@
  *                     gives the HIP error text).
  *     The contents of device arrays (mult, shift, bias) are trusted and not read
  *     on the host; `shift` entries must lie in [-31, 31], which the host helper
- *     qnn_quantize_multiplier guarantees.
+ *     qnn_quantize_multiplier guarantees (the kernels treat a value outside as the
+ *     nearest end of that range).
  *
  * The fixed-point rescale (not defined by the paper; this is the library's
  * definition, referred to as RESCALE(a; mult, shift) below), on an int32 a:
