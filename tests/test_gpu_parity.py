@@ -580,6 +580,25 @@ def test_qgemm_short_k_general_rescale_columns(K, N):
         assert_same(got, want, f"short-K general rescale {M}x{N}x{K} z_a={z_a}")
 
 
+@pytest.mark.parametrize("K,pad_a,pad_c", [(256, 16, 16), (128, 48, 32), (256, 32, 0), (256, 8, 16)])
+def test_qgemm_short_k_rows_through_lds_spaced_rows(K, pad_a, pad_c):
+    # the staged form (A rows copied to LDS per workgroup) on column slices of wider matrices: lda > K, ldc > N;
+    # pad 8 leaves the rows 8-byte aligned only, which takes the direct loads instead
+    import torch
+    M, N = 1333, 576
+    rng = np.random.default_rng(2100 + K + pad_a + pad_c)
+    wide_a = rng.integers(0, 256, (M, K + pad_a)).astype(np.uint8)
+    A = wide_a[:, :K]
+    Bt = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    bias, mult, shift = _short_k_params(rng, N, K, 8)
+    wide_c = torch.full((M, N + pad_c), 77, dtype=torch.uint8, device="cuda")
+    want = oracle.qgemm(np.ascontiguousarray(A), 100, Bt, mult, shift, 128, 0, 255, bias=bias)
+    qnn.qgemm(dev(wide_a)[:, :K], 100, dev(Bt), dev(mult), dev(shift), 128, 0, 255, bias=dev(bias), out=wide_c[:, :N])
+    got = host(wide_c)
+    assert_same(got[:, :N], want, f"short-K through LDS, spaced rows K={K}")
+    assert (got[:, N:] == 77).all(), "columns outside the output slice were written"
+
+
 @pytest.mark.parametrize("K,pad_a,pad_c", [(64, 16, 16), (64, 8, 3), (96, 24, 0), (128, 0, 5), (40, 8, 1)])
 def test_qgemm_short_k_spaced_rows(K, pad_a, pad_c):
     # A and C are column slices of wider matrices (lda > K, ldc > N); pad 8 leaves rows only 8-byte aligned
